@@ -1,0 +1,124 @@
+/*
+ * approx_topk.h - C ABI of the MI355X (gfx950) bucketed approximate top-k library.
+ *
+ * Method: arxiv 2412.04358, Section 2 ("Algorithm design choices"):
+ *   Stage 1  split each row of n elements into b interleaved buckets (element i goes to
+ *            bucket i mod b, Appendix A.1), keep the k_b largest of every bucket and
+ *            concatenate the b*k_b survivors;
+ *   Stage 2  if b*k_b > k, keep the k largest of the survivors (an exact top-k).
+ *
+ * Conventions fixed by this library where the paper is silent:
+ *   - "larger" means: greater value, and among equal values the lower column index
+ *     (at every stage).  Values compare as IEEE numbers (+0 == -0); rows must not
+ *     contain NaN (behaviour is then unspecified, but memory-safe).
+ *   - Output order.  Without Stage 2 (b*k_b == k): bucket-major, slot j*k_b + t holds
+ *     the t-th largest element of bucket j.  With Stage 2, and for exact_topk: largest
+ *     first.
+ *   - out_vals carries the selected element's own bits (the sign of a zero survives).
+ *
+ * All data pointers are DEVICE pointers on the current HIP device.  The caller owns every
+ * buffer; the library keeps no pointer after the call's work has finished.  Calls are
+ * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default stream):
+ * they enqueue kernels and return; buffers must stay valid until the stream has drained.
+ * A per-device scratch pool (partial results, tickets, radix-select state) is owned by
+ * the library; it grows on demand (growing allocates, which may synchronise the device)
+ * and is shared by all calls on a device, so calls that may run concurrently on
+ * different streams of one device must be serialised by the caller.
+ *
+ * Every function returns ATK_OK (0) or a negative error code.  Arguments are checked on
+ * the host before any HIP call is made; nothing is launched when a check fails.
+ */
+#ifndef APPROX_TOPK_H
+#define APPROX_TOPK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types of x / out_vals */
+enum { ATK_F32 = 0, ATK_BF16 = 1 };
+
+/* return codes */
+enum {
+    ATK_OK = 0,
+    ATK_ERR_NULL_PTR = -1,    /* a required pointer is NULL */
+    ATK_ERR_BAD_SHAPE = -2,   /* m, n or k out of range (m,n,k >= 1, k <= n, n < 2^31, m*n and m*k < 2^40) */
+    ATK_ERR_BAD_PARAMS = -3,  /* b, k_b violate 1 <= b <= n, 1 <= k_b <= min(k, n/b), b*k_b >= k */
+    ATK_ERR_UNSUPPORTED = -4, /* legal for the method, not implemented here (see each function) */
+    ATK_ERR_DTYPE = -5,       /* dtype is neither ATK_F32 nor ATK_BF16 */
+    ATK_ERR_HIP = -6,         /* a HIP runtime call failed; see atk_last_hip_error() */
+    ATK_ERR_ALIGN = -7        /* a pointer is not aligned to its element size */
+};
+
+/* Largest supported k_b (per-lane insertion buffers live in registers). */
+#define ATK_MAX_KB 16
+
+/*
+ * Bucketed approximate top-k of every row (Section 2, Stage 1 + Stage 2; Figure 2 left).
+ *
+ *   x         device, m x n row-major contiguous, element type `dtype`; read only.
+ *   m, n      rows, row length.            k   outputs per row, 1 <= k <= n.
+ *   b, k_b    buckets per row and survivors per bucket: 1 <= b <= n,
+ *             1 <= k_b <= min(k, n/b), b*k_b >= k.
+ *   out_vals  device, m x k, element type `dtype`.
+ *   out_idx   device, m x k int32 column indices (0-based, within the row).
+ *
+ * ATK_ERR_UNSUPPORTED: n not a multiple of b; k_b > ATK_MAX_KB; a Stage 2 whose
+ * b*k_b candidates exceed the on-chip limit reported by atk_stage2_max_candidates().
+ */
+int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
+                void *out_vals, int32_t *out_idx, void *stream);
+
+/*
+ * Exact top-k of every row, the comparison point (Section 1; the radix-select listing of
+ * Appendix D.2 is the algorithm family): the k largest elements, largest first.
+ * Arguments as for approx_topk.
+ */
+int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *out_vals, int32_t *out_idx,
+               void *stream);
+
+/* Static, never-freed description of a return code. */
+const char *atk_strerror(int code);
+
+/* hipError_t value of the most recent ATK_ERR_HIP on the calling thread (0 if none). */
+int atk_last_hip_error(void);
+
+/* Host-only argument checks (the same ones approx_topk / exact_topk run first). Pointers are not examined. */
+int atk_check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
+int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype);
+
+/* Largest b*k_b for which Stage 2 runs on-chip in the same launch. */
+int64_t atk_stage2_max_candidates(void);
+
+/* Bytes of library scratch an approx_topk / exact_topk call with these arguments uses (0 if none, <0 = error code). */
+int64_t atk_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
+int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype);
+
+/*
+ * Writes a one-line, human-readable description of the launch plan the library would use
+ * (threads per workgroup, lanes per bucket column, row splits, fused Stage 2, ...) into
+ * buf (NUL-terminated, truncated to buflen).  Host only; used by tests and the benchmark log.
+ * The plan can be overridden for tuning with the environment variable ATK_PLAN, e.g.
+ * "T=256,S=16" (threads per workgroup, splits per row).
+ */
+int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
+                      int64_t buflen);
+
+/*
+ * Measurement utilities (Appendix B.1 protocol, and the roofline's empirical ceiling).
+ *
+ * atk_read_ceiling: a read-only streaming kernel over `bytes` bytes (multiple of 16, 16-byte
+ *   aligned) of device memory at x; xors everything into the 8-byte device word *sink.
+ *   It bounds from above what any single-pass kernel over x can reach.
+ * atk_sleep: a kernel that spins for about `microseconds` (one wave), used to queue work
+ *   behind it so that host launch latency stays out of event timings.
+ */
+int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream);
+int atk_sleep(int64_t microseconds, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APPROX_TOPK_H */

@@ -1,0 +1,18 @@
+"""MI355X (gfx950) bucketed approximate top-k, after arxiv 2412.04358.
+
+`approx_topk` / `exact_topk` call the hand-written HIP library through its C ABI; the
+library is loaded on first use and a missing build raises, there is no CPU fallback.
+"""
+from .binding import (  # noqa: F401
+    ATK_BF16,
+    ATK_F32,
+    ApproxTopkError,
+    approx_topk,
+    approx_topk_raw,
+    exact_topk,
+    exact_topk_raw,
+    lib_path,
+    load_library,
+    plan_describe,
+    strerror,
+)
