@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the bucketed approximate top-k hot path on one MI355X.
+
+One step = one pass of the whole hot path over the headline workload (arxiv 2412.04358,
+Figure 1 left, restated synthetically): m=128 rows of n=65536 float32 N(0,1), k=64,
+k_b=1, b swept over {64, 128, 256, 512, 1024} (b*k_b/k = 1..16; Stage 2 runs for b > 64).
+That is five approx_topk calls per step.  Every call reads a different, already resident
+input buffer from a ring larger than the 256 MB Infinity Cache, so each launch streams its
+rows from HBM ("cold"); the same-buffer ("warm") figure is reported beside it.
+
+Metric: total bandwidth = minimum bytes (m*n*4 read + m*k*8 written) / runtime
+(Figure 1 caption), in GB/s and as a fraction of the 8 TB/s HBM peak.
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+M, N, K = 128, 65536, 64
+SWEEP_B = [64, 128, 256, 512, 1024]
+RING = 12  # 12 x 33.5 MB = 403 MB > 256 MB Infinity Cache
+
+
+def min_bytes(m, n, k, es=4):
+    return m * n * es + m * k * (es + 4)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", action="store_true", help="also time every configuration of the paper's sweeps")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (rows shard with no exchange); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2412_04358_amd as atk
+    from paper_2412_04358_amd import workloads
+
+    if not os.path.exists(atk.lib_path()):
+        import __graft_entry__
+
+        __graft_entry__.build()
+    lib = atk.load_library()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- inputs resident in HBM before anything is timed
+    ring = [workloads.normal_rows(M, N, seed=s).to(dev) for s in range(RING)]
+    out_v = torch.empty((M, K), dtype=torch.float32, device=dev)
+    out_i = torch.empty((M, K), dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    calls = 0
+
+    def launch(x, b):
+        rc = atk.approx_topk_raw(x.data_ptr(), M, N, K, b, 1, atk.ATK_F32, out_v.data_ptr(), out_i.data_ptr(), stream)
+        if rc != 0:
+            raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
+
+    def step(i, cold=True):
+        for j, b in enumerate(SWEEP_B):
+            launch(ring[(i * len(SWEEP_B) + j) % RING] if cold else ring[0], b)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly `steps` steps
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    step_bytes = len(SWEEP_B) * min_bytes(M, N, K)
+    value = step_bytes / (wall / args.steps) / 1e9
+
+    # ---- per-b timings (cold ring and warm single buffer), back-to-back launches between two events
+    def time_case(b, cold, reps=300):
+        for i in range(10):
+            launch(ring[i % RING] if cold else ring[0], b)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            launch(ring[i % RING] if cold else ring[0], b)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps  # us per launch
+
+    cases = {}
+    for b in SWEEP_B:
+        us_c, us_w = time_case(b, True), time_case(b, False)
+        cases["b=%d" % b] = {
+            "us_cold": round(us_c, 3), "GBps_cold": round(min_bytes(M, N, K) / us_c / 1e3, 1),
+            "us_warm": round(us_w, 3), "GBps_warm": round(min_bytes(M, N, K) / us_w / 1e3, 1),
+            "plan": atk.plan_describe(M, N, K, b, 1),
+        }
+
+    # ---- empirical ceiling: a read-only kernel over the same buffers
+    sink = torch.zeros(65536 // 8, dtype=torch.int64, device=dev)  # ATK_CEILING_SINK_BYTES
+
+    def ceiling(cold, reps=300):
+        for i in range(10):
+            lib.atk_read_ceiling(ring[i % RING].data_ptr(), M * N * 4, sink.data_ptr(), stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            lib.atk_read_ceiling((ring[i % RING] if cold else ring[0]).data_ptr(), M * N * 4, sink.data_ptr(), stream)
+        e1.record()
+        torch.cuda.synchronize()
+        return M * N * 4 / (e0.elapsed_time(e1) * 1e-3 / reps) / 1e9
+
+    ceil_cold, ceil_warm = ceiling(True), ceiling(False)
+
+    # ---- roofline of the dominant kernel (the fused streaming kernel; HBM-bound):
+    # algorithmic bytes per launch = m*n*4 read + m*k*8 written; average launch duration from HIP
+    # events over the timed region (5 launches per step).
+    launches = args.steps * len(SWEEP_B)
+    avg_launch_s = ev_ms * 1e-3 / launches
+    achieved = min_bytes(M, N, K) / avg_launch_s / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "kernel": "stage1_kernel<f32,V=4,KB=1>", "avg_launch_us": round(avg_launch_s * 1e6, 3),
+                "read_only_ceiling_GBps": {"cold": round(ceil_cold, 1), "warm": round(ceil_warm, 1)}}
+    traffic_file = os.path.join(ROOT, "profiles", "traffic_stage1_cfg2.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            roofline["traffic"] = json.load(f).get("bytes_per_launch")
+
+    # ---- CPU baseline: the oracle, untouched, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+        rows = 32
+        xs = workloads.as_numpy_bits(workloads.normal_rows(M, N, seed=0)[:rows])
+        oracle.approx_topk(xs[:2], K, 64, 1, threads=threads)  # load the library, warm the pages
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            for b in SWEEP_B:
+                oracle.approx_topk(xs, K, b, 1, threads=threads)
+            reps += 1
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(reps * len(SWEEP_B) * min_bytes(rows, N, K) / dt / 1e9, 4), "unit": "GB/s",
+               "cores": threads, "kind": "oracle",
+               "sample": "%d of the %d rows, the same 5-value b sweep, %d repetitions in %.1f s" % (rows, M, reps, dt)}
+
+    out = {
+        "metric": "total bandwidth GB/s (min bytes / runtime), m=128 float32",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "cfg2: m=128 n=65536 f32 N(0,1) k=64 k_b=1, b in {64,128,256,512,1024}, "
+                               "Stage 2 for b>64; one step = the 5 calls; inputs rotate over a 403 MB ring (HBM-cold)",
+                   "m": M, "n": N, "k": K, "k_b": 1, "b": SWEEP_B},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "event_ms_per_step": round(ev_ms / args.steps, 5),
+        "cases": cases,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    if args.detail:
+        out["detail"] = detail(atk, workloads, torch, dev)
+    print(json.dumps(out))
+
+
+def detail(atk, workloads, torch, dev):
+    """Every configuration of the other sweeps: us per launch (cold where a ring fits), GB/s."""
+    res = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    for name in ["cfg3", "cfg4", "cfg5"]:
+        c = workloads.CONFIGS[name]
+        m, n = c["m"], c["n"]
+        es = 4 if c["dtype"] == "f32" else 2
+        dt = atk.ATK_F32 if c["dtype"] == "f32" else atk.ATK_BF16
+        nring = 1 if name == "cfg4" else 10  # 537 MB rows are cold by size
+        if name == "cfg5":
+            ring = [workloads.attention_scores(seed=s).to(dev) for s in range(nring)]
+        else:
+            ring = [workloads.normal_rows(m, n, seed=s, dtype=c["dtype"]).to(dev) for s in range(nring)]
+        for (k, b, k_b) in c["cases"]:
+            ov = torch.empty((m, k), dtype=ring[0].dtype, device=dev)
+            oi = torch.empty((m, k), dtype=torch.int32, device=dev)
+
+            def launch(i):
+                rc = atk.approx_topk_raw(ring[i % nring].data_ptr(), m, n, k, b, k_b, dt, ov.data_ptr(), oi.data_ptr(),
+                                         stream)
+                assert rc == 0, atk.strerror(rc)
+
+            reps = 50 if name == "cfg4" else 200
+            for i in range(5):
+                launch(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                launch(i)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            nbytes = m * n * es + m * k * (es + 4)
+            res["%s k=%d b=%d k_b=%d" % (name, k, b, k_b)] = {
+                "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                "plan": atk.plan_describe(m, n, k, b, k_b, dt)}
+        del ring
+        torch.cuda.empty_cache()
+    return res
+
+
+if __name__ == "__main__":
+    main()

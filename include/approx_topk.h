@@ -110,11 +110,13 @@ int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, i
  * Measurement utilities (Appendix B.1 protocol, and the roofline's empirical ceiling).
  *
  * atk_read_ceiling: a read-only streaming kernel over `bytes` bytes (multiple of 16, 16-byte
- *   aligned) of device memory at x; xors everything into the 8-byte device word *sink.
- *   It bounds from above what any single-pass kernel over x can reach.
+ *   aligned) of device memory at x; every wave xors what it read into its own word of
+ *   `sink`, a device buffer of ATK_CEILING_SINK_BYTES bytes.  It bounds from above what any
+ *   single-pass kernel over x can reach.
  * atk_sleep: a kernel that spins for about `microseconds` (one wave), used to queue work
  *   behind it so that host launch latency stays out of event timings.
  */
+#define ATK_CEILING_SINK_BYTES 65536
 int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream);
 int atk_sleep(int64_t microseconds, void *stream);
 

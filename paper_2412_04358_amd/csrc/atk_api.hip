@@ -1,0 +1,358 @@
+// C ABI of the library (include/approx_topk.h): argument checks, launch planning, the
+// per-device scratch pool, and the measurement utilities.
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+#include "atk_common.h"
+
+namespace atk {
+
+static thread_local int g_last_hip_error = 0;
+
+static int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return ATK_ERR_HIP;
+}
+
+static int64_t pow2_ceil(int64_t v) {
+    int64_t p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ------------------------------------------------------------------------------------ checks
+static int check_common(int64_t m, int64_t n, int64_t k, int dtype) {
+    if (dtype != ATK_F32 && dtype != ATK_BF16) return ATK_ERR_DTYPE;
+    if (m < 1 || n < 1 || k < 1 || k > n) return ATK_ERR_BAD_SHAPE;
+    if (n >= (1ll << 31)) return ATK_ERR_BAD_SHAPE;  // int32 column indices
+    if (m > (1ll << 40) / n || m > (1ll << 40) / k) return ATK_ERR_BAD_SHAPE;
+    return ATK_OK;
+}
+
+// Section 2: b in {1..n}, k_b in {1..min(k, n/b)}, b*k_b >= k.
+static int check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    int rc = check_common(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    if (b < 1 || b > n || k_b < 1) return ATK_ERR_BAD_PARAMS;
+    if (k_b > k || k_b > n / b) return ATK_ERR_BAD_PARAMS;
+    if (b * k_b < k) return ATK_ERR_BAD_PARAMS;
+    if (n % b != 0) return ATK_ERR_UNSUPPORTED;
+    if (k_b > ATK_MAX_KB) return ATK_ERR_UNSUPPORTED;
+    return ATK_OK;
+}
+
+// ------------------------------------------------------------------------------------ plan override
+// ATK_PLAN="T=128,S=4": tuning knobs for sweeps; values are clamped to what the kernels accept.
+static void plan_override(int *T, int *S) {
+    const char *e = getenv("ATK_PLAN");
+    if (!e) return;
+    const char *p = strstr(e, "T=");
+    if (p && T) {
+        int v = atoi(p + 2);
+        if (v == 64 || v == 128 || v == 256) *T = v;
+    }
+    p = strstr(e, "S=");
+    if (p && S) {
+        int v = atoi(p + 2);
+        if (v >= 1 && v <= 4096) *S = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------ approx plan
+static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, bool ptr16,
+                             Plan *pl) {
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    Plan p;
+    memset(&p, 0, sizeof p);
+    p.dtype = dtype;
+    p.m = m;
+    p.n = n;
+    p.k = k;
+    p.b = b;
+    p.k_b = (int)k_b;
+    p.KB = (int)pow2_ceil(k_b);
+    int vmax;
+    if (dtype == ATK_F32)
+        vmax = (p.KB <= 8) ? 4 : 2;
+    else
+        vmax = (p.KB <= 4) ? 8 : (p.KB == 8 ? 4 : 2);
+    p.V = (ptr16 && b % vmax == 0) ? vmax : 1;
+    p.G = b / p.V;
+    p.L = n / b;
+    p.stage2 = b * k_b > k;
+
+    int T = kMaxThreads, S_forced = 0;
+    plan_override(&T, &S_forced);
+    // keep the LDS merge tree (KB*V*T composites) inside 48 KB
+    while ((int64_t)p.KB * p.V * T * 8 > 48 * 1024 && T > kWave) T >>= 1;
+    p.Gw = (int)((p.G < T) ? p.G : T);
+    p.P = T / p.Gw;
+    if (p.P > p.L) p.P = (int)p.L;
+    if (p.P < 1) p.P = 1;
+    {
+        int64_t need = (int64_t)p.P * p.Gw;
+        T = (int)(ceil_div(need, kWave) * kWave);
+        if (T > kMaxThreads) T = kMaxThreads;
+    }
+    p.T = T;
+    p.colblocks = (int)ceil_div(p.G, p.Gw);
+
+    // row splits: enough workgroups to fill 256 CUs, every lane keeps >= 4 loads, and the
+    // partial lists stay below 1/8 of the bytes streamed
+    int64_t base = m * p.colblocks;
+    int64_t target_wgs = (int64_t)kNumCU * 1024 / T;
+    int64_t S = 1;
+    if (base < target_wgs) S = ceil_div(target_wgs, base);
+    int64_t s_rows = p.L / ((int64_t)p.P * 4);
+    int64_t s_traffic = (p.L * es) / (128 * k_b);
+    if (S > s_rows) S = s_rows;
+    if (S > s_traffic) S = s_traffic;
+    if (S_forced) S = S_forced;
+    if (S > p.L / p.P) S = p.L / p.P;
+    if (S < 1) S = 1;
+    int64_t rps = ceil_div(p.L, S);
+    rps = ceil_div(rps, p.P) * p.P;
+    S = ceil_div(p.L, rps);
+    p.S = (int)S;
+    p.rows_per_split = (int)rps;
+
+    p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
+    p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
+
+    int64_t lds_tree = (p.P > 1) ? (int64_t)p.KB * p.V * T * 8 : 0;
+    int64_t lds_s2 = p.stage2 ? (b * k_b + pow2_ceil(k)) * 8 + 264 * 4 : 0;
+    int64_t lds = lds_tree > lds_s2 ? lds_tree : lds_s2;
+    if (lds < 64) lds = 64;
+    if (p.stage2 && b * k_b > kStage2MaxCand) return ATK_ERR_UNSUPPORTED;
+    if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
+    p.lds_bytes = (int)lds;
+
+    p.scratch_ticket_bytes = p.use_scratch ? m * kTicketStride * 4 : 0;
+    p.scratch_lists_bytes = p.use_scratch ? m * p.S * b * k_b * 8 : 0;
+    p.grid = m * p.S * p.colblocks;
+    if (p.grid >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
+    *pl = p;
+    return ATK_OK;
+}
+
+int make_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, Plan *pl) {
+    return make_plan_aligned(m, n, k, b, k_b, dtype, true, pl);
+}
+
+// ------------------------------------------------------------------------------------ scratch pool
+// Two grow-only allocations per device: `state` (tickets and other words that every kernel
+// leaves zeroed, so that the next call can rely on zeros) and `data` (partial lists and
+// other buffers that carry nothing from call to call).  Both are zero-filled when
+// (re)allocated.  They are kept apart so that one call's data can never alias what a later
+// call, with other sizes, takes for zeroed state.
+static std::mutex g_pool_mu;
+enum { kPoolState = 0, kPoolData = 1 };
+static void *g_pool_ptr[64][2];
+static size_t g_pool_bytes[64][2];
+
+static hipError_t get_pool(int which, size_t bytes, void **out) {
+    *out = nullptr;
+    if (bytes == 0) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_pool_mu);
+    if (g_pool_bytes[dev][which] < bytes) {
+        if (g_pool_ptr[dev][which]) {
+            e = hipFree(g_pool_ptr[dev][which]);  // waits for work that may still use it
+            g_pool_ptr[dev][which] = nullptr;
+            g_pool_bytes[dev][which] = 0;
+            if (e != hipSuccess) return e;
+        }
+        size_t want = bytes + bytes / 4;
+        if (which == kPoolState && want < 64 * 1024) want = 64 * 1024;
+        void *p = nullptr;
+        e = hipMalloc(&p, want);
+        if (e != hipSuccess) return e;
+        e = hipMemset(p, 0, want);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+            (void)hipFree(p);
+            return e;
+        }
+        g_pool_ptr[dev][which] = p;
+        g_pool_bytes[dev][which] = want;
+    }
+    *out = g_pool_ptr[dev][which];
+    return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------ utilities
+__global__ void __launch_bounds__(256) read_ceiling_kernel(const uint4 *x, int64_t n_vec, u64 *sink) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc = 0;
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const v4u *px = (const v4u *)x;
+    for (; i + 7 * stride < n_vec; i += 8 * stride) {
+        v4u v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(px + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < n_vec; i += stride) {
+        v4u v = __builtin_nontemporal_load(px + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc ^= __shfl_xor(acc, off, 64);
+    // one word per wave, no contended atomics: sink holds gridDim.x * 4 words
+    if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = acc;
+}
+
+__global__ void sleep_kernel(int64_t ticks, u64 *unused) {
+    // wall_clock64() counts at a fixed 100 MHz; the loop ends after `ticks` of it.
+    const u64 start = wall_clock64();
+    while ((int64_t)(wall_clock64() - start) < ticks) __builtin_amdgcn_s_sleep(32);
+    (void)unused;
+}
+
+}  // namespace atk
+
+using namespace atk;
+
+// ====================================================================================== C ABI
+extern "C" {
+
+const char *atk_strerror(int code) {
+    switch (code) {
+        case ATK_OK: return "ok";
+        case ATK_ERR_NULL_PTR: return "a required pointer is NULL";
+        case ATK_ERR_BAD_SHAPE: return "m, n or k out of range (need m,n,k >= 1, k <= n, n < 2^31)";
+        case ATK_ERR_BAD_PARAMS: return "b, k_b must satisfy 1 <= b <= n, 1 <= k_b <= min(k, n/b), b*k_b >= k";
+        case ATK_ERR_UNSUPPORTED: return "parameters are legal for the method but not supported by this library";
+        case ATK_ERR_DTYPE: return "dtype must be ATK_F32 (0) or ATK_BF16 (1)";
+        case ATK_ERR_HIP: return "a HIP runtime call failed";
+        case ATK_ERR_ALIGN: return "a pointer is not aligned to its element size";
+    }
+    return "unknown error code";
+}
+
+int atk_last_hip_error(void) { return g_last_hip_error; }
+
+int atk_check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    Plan pl;
+    return make_plan(m, n, k, b, k_b, dtype, &pl);
+}
+
+int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype) {
+    int rc = check_common(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    ExactPlan pl;
+    return make_exact_plan(m, n, k, dtype, &pl);
+}
+
+int64_t atk_stage2_max_candidates(void) { return kStage2MaxCand; }
+
+int64_t atk_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    Plan pl;
+    rc = make_plan(m, n, k, b, k_b, dtype, &pl);
+    if (rc != ATK_OK) return rc;
+    return pl.scratch_ticket_bytes + pl.scratch_lists_bytes;
+}
+
+int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype) {
+    int rc = check_common(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    ExactPlan pl;
+    rc = make_exact_plan(m, n, k, dtype, &pl);
+    if (rc != ATK_OK) return rc;
+    return pl.scratch_bytes + pl.state_bytes;
+}
+
+int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
+                      int64_t buflen) {
+    if (!buf || buflen < 1) return ATK_ERR_NULL_PTR;
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    Plan pl;
+    rc = make_plan(m, n, k, b, k_b, dtype, &pl);
+    if (rc != ATK_OK) return rc;
+    snprintf(buf, (size_t)buflen,
+             "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
+             "scratch=%d lds=%d scratch_bytes=%lld",
+             pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid,
+             (int)pl.stage2, (int)pl.direct, (int)pl.use_scratch, pl.lds_bytes,
+             (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes));
+    return ATK_OK;
+}
+
+int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
+                void *out_vals, int32_t *out_idx, void *stream) {
+    if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
+    if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
+    Plan pl;
+    rc = make_plan_aligned(m, n, k, b, k_b, dtype, ((uintptr_t)x & 15u) == 0, &pl);
+    if (rc != ATK_OK) return rc;
+    void *state = nullptr, *data = nullptr;
+    hipError_t e = get_pool(kPoolState, (size_t)pl.scratch_ticket_bytes, &state);
+    if (e != hipSuccess) return hip_fail(e);
+    e = get_pool(kPoolData, (size_t)pl.scratch_lists_bytes, &data);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_approx(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return ATK_OK;
+}
+
+int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *out_vals, int32_t *out_idx,
+               void *stream) {
+    if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
+    int rc = check_common(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
+    if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
+    ExactPlan pl;
+    rc = make_exact_plan(m, n, k, dtype, &pl);
+    if (rc != ATK_OK) return rc;
+    void *state = nullptr, *data = nullptr;
+    hipError_t e = get_pool(kPoolState, (size_t)pl.state_bytes, &state);
+    if (e != hipSuccess) return hip_fail(e);
+    e = get_pool(kPoolData, (size_t)pl.scratch_bytes, &data);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_exact(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return ATK_OK;
+}
+
+int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream) {
+    if (!x || !sink) return ATK_ERR_NULL_PTR;
+    if (bytes < 16 || (bytes & 15) || ((uintptr_t)x & 15u) || ((uintptr_t)sink & 7u)) return ATK_ERR_ALIGN;
+    const int64_t n_vec = bytes / 16;
+    int64_t wgs = (n_vec + 256 * 8 - 1) / (256 * 8);
+    if (wgs > ATK_CEILING_SINK_BYTES / 32) wgs = ATK_CEILING_SINK_BYTES / 32;
+    hipLaunchKernelGGL(read_ceiling_kernel, dim3((unsigned)wgs), dim3(256), 0, (hipStream_t)stream, (const uint4 *)x,
+                       n_vec, (u64 *)sink);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return ATK_OK;
+}
+
+int atk_sleep(int64_t microseconds, void *stream) {
+    if (microseconds < 0 || microseconds > 1000000) return ATK_ERR_BAD_SHAPE;
+    hipLaunchKernelGGL(sleep_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, microseconds * 100, (u64 *)nullptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return ATK_OK;
+}
+
+}  // extern "C"

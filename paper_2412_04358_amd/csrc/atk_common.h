@@ -1,0 +1,147 @@
+// Shared declarations of the HIP library: plans, device helpers, launch entry points.
+// gfx950 (MI355X) only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/approx_topk.h"
+
+typedef unsigned long long u64;
+
+namespace atk {
+
+constexpr int kWave = 64;
+constexpr int kMaxThreads = 256;          // threads per workgroup of the streaming kernels
+constexpr int kStage2MaxCand = 8192;      // composites held in LDS by the fused Stage 2
+constexpr int kLdsBudget = 64 * 1024;     // static+dynamic LDS per workgroup we allow ourselves
+constexpr int kNumCU = 256;               // MI355X
+constexpr int kTicketStride = 32;          // words between row tickets: one 128-byte line each, so that
+                                          // atomics of different rows do not queue up on one line
+constexpr int kEmptyT = 0x7fffffff;       // "no element yet" row marker of a register slot
+
+// ------------------------------------------------------------------------------------
+// Launch plan of approx_topk (host side, filled by make_plan()).
+//
+// A row of n elements is viewed as an L x b matrix (L = n/b rows, row-major): column j is
+// bucket j (Appendix A.1, interleaved assignment), so Stage 1 is a column-wise top-k_b.
+// A lane owns V adjacent columns (one 16-byte load) and walks down the matrix rows.
+struct Plan {
+    int dtype;        // ATK_F32 / ATK_BF16
+    int V;            // columns per lane: 16 B / sizeof(element), or 1 for the scalar path
+    int KB;           // register slots per column: k_b rounded up to a power of two
+    int k_b;          // survivors per bucket
+    int T;            // threads per workgroup
+    int Gw;           // column groups (lanes side by side) per workgroup
+    int P;            // row phases: lanes of one workgroup that share a column group
+    int colblocks;    // workgroups side by side across the b columns
+    int S;            // row splits: workgroups stacked down the L matrix rows
+    int rows_per_split;
+    int64_t G;        // column groups per row = b / V
+    int64_t L;        // matrix rows = n / b
+    int64_t m, n, k, b;
+    bool stage2;      // b*k_b > k
+    bool direct;      // every lane owns whole buckets: write results straight from registers
+    bool use_scratch; // partial lists go through global scratch + a per-row ticket
+    int64_t scratch_lists_bytes;   // composites
+    int64_t scratch_ticket_bytes;  // one counter per row
+    int lds_bytes;    // dynamic LDS of the launch
+    int64_t grid;
+};
+
+int make_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, Plan *plan);
+
+// Enqueue the fused Stage 1 (+ merge, + Stage 2) kernel for `plan`.
+// state: zeroed words (tickets); data: partial lists.
+hipError_t launch_approx(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state, void *data,
+                         hipStream_t stream);
+
+// ------------------------------------------------------------------------------------
+// exact_topk plan
+struct ExactPlan {
+    int dtype;
+    int64_t m, n, k;
+    bool single_wg;         // whole row fits one workgroup's LDS
+    int T;
+    int lds_bytes;
+    int chunks;             // workgroups per row of the global path
+    int64_t scratch_bytes;  // data pool
+    int64_t state_bytes;    // zeroed-state pool
+};
+int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *plan);
+hipError_t launch_exact(const ExactPlan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state,
+                        void *data, hipStream_t stream);
+
+// ------------------------------------------------------------------------------------
+// Device helpers.
+#ifdef __HIPCC__
+
+// Order-preserving map float bits -> unsigned key, with -0 mapped onto +0's key, so that
+// integer order on keys equals IEEE order on values (NaN-free input).
+__device__ __forceinline__ uint32_t ukey_of_bits(uint32_t bits) {
+    uint32_t c = (bits == 0x80000000u) ? 0u : bits;
+    uint32_t mask = (uint32_t)((int32_t)c >> 31) | 0x80000000u;
+    return c ^ mask;
+}
+__device__ __forceinline__ uint32_t bits_of_ukey(uint32_t key) {
+    return (key & 0x80000000u) ? (key ^ 0x80000000u) : ~key;
+}
+
+// Composite word: [63:32] value key, [31:1] 0x7fffffff - index, [0] "the element was -0".
+// Larger composite <=> larger value, or equal value and lower index.  (key, index) pairs
+// of one row are distinct, so bit 0 never decides an order; it only carries the sign of
+// a zero to the output.  0 is never a valid composite (the key of -inf is 0x007fffff) and
+// marks an empty slot.
+__device__ __forceinline__ u64 make_composite(uint32_t bits, int32_t idx) {
+    uint32_t key = ukey_of_bits(bits);
+    uint32_t lo = ((0x7fffffffu - (uint32_t)idx) << 1) | (bits == 0x80000000u ? 1u : 0u);
+    return ((u64)key << 32) | lo;
+}
+__device__ __forceinline__ int32_t composite_index(u64 c) {
+    return (int32_t)(0x7fffffffu - ((uint32_t)c >> 1));
+}
+__device__ __forceinline__ uint32_t composite_bits(u64 c) {
+    return ((uint32_t)c & 1u) ? 0x80000000u : bits_of_ukey((uint32_t)(c >> 32));
+}
+
+__device__ __forceinline__ u64 umax64(u64 a, u64 b) { return a > b ? a : b; }
+
+// mine <- the KB largest of (mine U theirs); both sorted descending, result sorted descending.
+template <int KB>
+__device__ __forceinline__ void merge_topk(u64 (&mine)[KB], const u64 (&theirs)[KB]) {
+#pragma unroll
+    for (int j = 0; j < KB; ++j) mine[j] = umax64(mine[j], theirs[KB - 1 - j]);
+    // mine is now bitonic and holds the KB largest: sort it descending
+#pragma unroll
+    for (int stride = KB / 2; stride >= 1; stride >>= 1) {
+#pragma unroll
+        for (int i = 0; i < KB; ++i) {
+            if ((i & stride) == 0) {
+                u64 a = mine[i], c = mine[i + stride];
+                bool sw = c > a;
+                mine[i] = sw ? c : a;
+                mine[i + stride] = sw ? a : c;
+            }
+        }
+    }
+}
+
+// Store the value part of an output element.
+template <int ELT>
+__device__ __forceinline__ void store_val(void *out_vals, int64_t pos, uint32_t bits32) {
+    if (ELT == ATK_F32)
+        ((uint32_t *)out_vals)[pos] = bits32;
+    else
+        ((uint16_t *)out_vals)[pos] = (uint16_t)(bits32 >> 16);
+}
+
+// Exact top-k of `count` distinct composites held in LDS at cand[0..count): the k largest,
+// written largest first to out_vals/out_idx of row `row_out` (row stride k).
+// All threads of the workgroup must call it.  sel: LDS, >= next_pow2(k) words; hist: LDS, 256+8 words.
+template <int ELT>
+__device__ void select_sort_write(u64 *cand, int count, int k, u64 *sel, uint32_t *hist, void *out_vals,
+                                  int32_t *out_idx, int64_t row_out);
+
+#endif  // __HIPCC__
+
+}  // namespace atk

@@ -1,0 +1,392 @@
+// Fused kernel of approx_topk: Stage 1 (per-bucket top-k_b), the merges needed when one
+// bucket is spread over several lanes / workgroups, and Stage 2 (exact top-k of the
+// b*k_b candidates) when b*k_b > k.   Section 2 and Appendix A of arxiv 2412.04358.
+//
+// Mapping.  Bucket j of a row holds the elements i = j (mod b) (Appendix A.1), so the row
+// is an L x b row-major matrix whose column j is bucket j.  A lane owns V adjacent columns
+// (one 16-byte load per matrix row) and keeps, per column, the k_b largest elements seen
+// so far in registers ("a max priority queue of size k_b ... in per-thread registers",
+// Appendix A).  Lanes side by side read consecutive addresses, so the interleaved layout
+// costs nothing.  When b is small, several lanes (row phases) share a column group, and
+// when m*b is too small to fill the chip, several workgroups (row splits) do; their sorted
+// lists are merged once at the end (Appendix A, mode (2): "merge the per-thread queues
+// once"), first in LDS, then - across workgroups - by whichever workgroup of the row
+// finishes last (a ticket counter), which also runs Stage 2.
+#include <cstdlib>
+#include <cstring>
+
+#include "atk_common.h"
+#include "atk_select.h"
+
+namespace atk {
+
+struct S1Params {
+    const void *x;
+    void *out_vals;
+    int32_t *out_idx;
+    u64 *lists;          // scratch: [row][split][column][k_b] composites
+    uint32_t *tickets;   // scratch: one counter per row (kTicketStride words apart), zero between calls
+    int64_t n;
+    int b, L, G, Gw, P, colblocks, S, rows_per_split;
+    int k, k_b;
+    int stage2, direct, use_scratch, vec_store;
+    int fence_sync;      // debugging aid: add full agent-scope fences around the ticket
+};
+
+template <int ELT, int V>
+struct RowVec {
+    static constexpr int kBytes = V * ((ELT == ATK_F32) ? 4 : 2);
+    static constexpr int kWords = (kBytes + 3) / 4;
+    uint32_t w[kWords];
+};
+
+// One load of V adjacent elements (16, 8, 4 or 2 bytes).  The data is read exactly once,
+// so the loads are marked non-temporal.
+template <int ELT, int V>
+__device__ __forceinline__ RowVec<ELT, V> load_vec(const unsigned char *p) {
+    RowVec<ELT, V> r;
+    constexpr int B = RowVec<ELT, V>::kBytes;
+    if constexpr (B == 16) {
+        typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+        v4u q = __builtin_nontemporal_load((const v4u *)p);
+        r.w[0] = q.x;
+        r.w[1] = q.y;
+        r.w[2] = q.z;
+        r.w[3] = q.w;
+    } else if constexpr (B == 8) {
+        typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+        v2u q = __builtin_nontemporal_load((const v2u *)p);
+        r.w[0] = q.x;
+        r.w[1] = q.y;
+    } else if constexpr (B == 4) {
+        r.w[0] = __builtin_nontemporal_load((const uint32_t *)p);
+    } else {
+        r.w[0] = (uint32_t)__builtin_nontemporal_load((const uint16_t *)p);
+    }
+    return r;
+}
+
+// element e of the vector as float bits (bf16 widened exactly)
+template <int ELT, int V>
+__device__ __forceinline__ uint32_t elem_bits(const RowVec<ELT, V> &r, int e) {
+    if constexpr (ELT == ATK_F32) {
+        return r.w[e];
+    } else {
+        uint32_t w = r.w[e >> 1];
+        return (e & 1) ? (w & 0xffff0000u) : (w << 16);
+    }
+}
+
+// Insert (v, t) into the descending list (val, tt); later elements never displace equal
+// earlier ones ("!(v <= slot)" is "v > slot" for numbers and true for the NaN that marks
+// an empty slot).
+template <int KB>
+__device__ __forceinline__ void insert(float (&val)[KB], int (&tt)[KB], float v, int t) {
+    bool c[KB];
+#pragma unroll
+    for (int j = 0; j < KB; ++j) c[j] = !(v <= val[j]);
+#pragma unroll
+    for (int j = KB - 1; j >= 1; --j) {
+        val[j] = c[j - 1] ? val[j - 1] : (c[j] ? v : val[j]);
+        tt[j] = c[j - 1] ? tt[j - 1] : (c[j] ? t : tt[j]);
+    }
+    val[0] = c[0] ? v : val[0];
+    tt[0] = c[0] ? t : tt[0];
+}
+
+template <int ELT, int V, int KB, int U>
+__global__ void __launch_bounds__(kMaxThreads) stage1_kernel(S1Params p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int ES = (ELT == ATK_F32) ? 4 : 2;
+    const int tid = threadIdx.x, T = blockDim.x;
+    int wg = blockIdx.x;
+    const int cb = wg % p.colblocks;
+    wg /= p.colblocks;
+    const int sp = wg % p.S;
+    const int r = wg / p.S;
+    const int cgl = tid % p.Gw, ph = tid / p.Gw;
+    const int cg = cb * p.Gw + cgl;
+    const bool active = (ph < p.P) && (cg < p.G);
+    const int t0 = sp * p.rows_per_split;
+    const int t1 = min(p.L, t0 + p.rows_per_split);
+    const int col0 = cg * V;
+
+    float val[V][KB];
+    int tt[V][KB];
+#pragma unroll
+    for (int e = 0; e < V; ++e)
+#pragma unroll
+        for (int j = 0; j < KB; ++j) {
+            val[e][j] = __uint_as_float(0x7fc00000u);
+            tt[e][j] = kEmptyT;
+        }
+
+    // ---------------------------------------------------------------- streaming scan
+    if (active) {
+        const unsigned char *base = (const unsigned char *)p.x + ((int64_t)r * p.n + (int64_t)col0) * ES;
+        const int64_t row_bytes = (int64_t)p.b * ES;
+        const int step = p.P;
+        int t = t0 + ph;
+        for (; t + (U - 1) * step < t1; t += U * step) {
+            RowVec<ELT, V> v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, V>(v[u], e)), t + u * step);
+        }
+        for (; t < t1; t += step) {
+            RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)t * row_bytes);
+#pragma unroll
+            for (int e = 0; e < V; ++e) insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, V>(v, e)), t);
+        }
+    }
+
+    // ---------------------------------------------------------------- every lane owns whole buckets
+    if (p.direct) {
+        if (!active) return;
+        const int64_t o = (int64_t)r * p.k + (int64_t)col0 * p.k_b;
+        if (p.vec_store && p.k_b == KB && (V * KB) % ((ELT == ATK_F32) ? 4 : 8) == 0) {
+            constexpr int N = V * KB;  // contiguous outputs of this lane
+            uint32_t ob[N];
+            int32_t oi[N];
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+#pragma unroll
+                for (int j = 0; j < KB; ++j) {
+                    ob[e * KB + j] = __float_as_uint(val[e][j]);
+                    oi[e * KB + j] = tt[e][j] * p.b + col0 + e;
+                }
+            typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+            v4u *pi = (v4u *)(p.out_idx + o);
+#pragma unroll
+            for (int q = 0; q < N / 4; ++q) {
+                v4u w = {(uint32_t)oi[4 * q], (uint32_t)oi[4 * q + 1], (uint32_t)oi[4 * q + 2], (uint32_t)oi[4 * q + 3]};
+                pi[q] = w;
+            }
+            if (ELT == ATK_F32) {
+                v4u *pv = (v4u *)((uint32_t *)p.out_vals + o);
+#pragma unroll
+                for (int q = 0; q < N / 4; ++q) {
+                    v4u w = {ob[4 * q], ob[4 * q + 1], ob[4 * q + 2], ob[4 * q + 3]};
+                    pv[q] = w;
+                }
+            } else {
+                v4u *pv = (v4u *)((uint16_t *)p.out_vals + o);
+#pragma unroll
+                for (int q = 0; q < N / 8; ++q) {
+                    v4u w;
+                    w.x = (ob[8 * q] >> 16) | (ob[8 * q + 1] & 0xffff0000u);
+                    w.y = (ob[8 * q + 2] >> 16) | (ob[8 * q + 3] & 0xffff0000u);
+                    w.z = (ob[8 * q + 4] >> 16) | (ob[8 * q + 5] & 0xffff0000u);
+                    w.w = (ob[8 * q + 6] >> 16) | (ob[8 * q + 7] & 0xffff0000u);
+                    pv[q] = w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j < p.k_b) {
+                        const int64_t pos = o + (int64_t)e * p.k_b + j;
+                        store_val<ELT>(p.out_vals, pos, __float_as_uint(val[e][j]));
+                        p.out_idx[pos] = tt[e][j] * p.b + col0 + e;
+                    }
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- to composites
+    u64 comp[V][KB];
+#pragma unroll
+    for (int e = 0; e < V; ++e)
+#pragma unroll
+        for (int j = 0; j < KB; ++j)
+            comp[e][j] = (tt[e][j] != kEmptyT)
+                             ? make_composite(__float_as_uint(val[e][j]), tt[e][j] * p.b + col0 + e)
+                             : 0ull;
+
+    // ---------------------------------------------------------------- merge the row phases (LDS tree)
+    if (p.P > 1) {
+        u64 *l = (u64 *)smem;  // word (j*V + e) of thread `tid` lives at l[(j*V + e)*T + tid]
+        int h = 1;
+        while (h < p.P) h <<= 1;
+        for (h >>= 1; h >= 1; h >>= 1) {
+            if (ph >= h && ph < 2 * h && active) {
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+#pragma unroll
+                    for (int j = 0; j < KB; ++j) l[(j * V + e) * T + tid] = comp[e][j];
+            }
+            __syncthreads();
+            if (ph < h && ph + h < p.P && active) {
+                const int peer = tid + h * p.Gw;
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    u64 theirs[KB];
+#pragma unroll
+                    for (int j = 0; j < KB; ++j) theirs[j] = l[(j * V + e) * T + peer];
+                    merge_topk<KB>(comp[e], theirs);
+                }
+            }
+            __syncthreads();
+        }
+    }
+    const bool owner = active && ph == 0;
+
+    u64 *cand = (u64 *)smem;
+    int n_cand = p.b * p.k_b;
+
+    if (!p.use_scratch) {
+        if (!p.stage2) {
+            if (owner) {
+                const int64_t o = (int64_t)r * p.k + (int64_t)col0 * p.k_b;
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+#pragma unroll
+                    for (int j = 0; j < KB; ++j)
+                        if (j < p.k_b) write_composite<ELT>(comp[e][j], p.out_vals, p.out_idx, o + (int64_t)e * p.k_b + j);
+            }
+            return;
+        }
+        if (owner) {
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j < p.k_b) cand[(col0 + e) * p.k_b + j] = comp[e][j];
+        }
+        __syncthreads();
+    } else {
+        // ------------------------------------------------------------ partial lists to scratch, ticket
+        // Cross-workgroup hand-over without cache-wide fences: the lists are written and later
+        // read with agent-scope atomic accesses (they go through to memory instead of staying
+        // in this XCD's L2), the barrier waits until this workgroup's stores have been
+        // acknowledged, and only then one lane takes the row's ticket.  Whoever draws the last
+        // ticket knows every other workgroup's lists are complete.
+        if (owner) {
+            u64 *dst = p.lists + (((int64_t)r * p.S + sp) * p.b + col0) * p.k_b;
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j < p.k_b)
+                        __hip_atomic_store(&dst[e * p.k_b + j], comp[e][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (p.fence_sync) __threadfence();
+        __syncthreads();
+        uint32_t *flag = (uint32_t *)smem;
+        if (tid == 0) {
+            uint32_t ticket = __hip_atomic_fetch_add(&p.tickets[(int64_t)r * kTicketStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            flag[0] = (ticket == (uint32_t)(p.S * p.colblocks - 1)) ? 1u : 0u;
+        }
+        __syncthreads();
+        const bool last = flag[0] != 0;
+        __syncthreads();  // flag word is reused below as candidate storage
+        if (!last) return;
+        if (p.fence_sync) __threadfence();
+        if (tid == 0)  // ready for the next call
+            __hip_atomic_store(&p.tickets[(int64_t)r * kTicketStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+        // the last workgroup of the row merges the splits of every column
+        const u64 *src = p.lists + (int64_t)r * p.S * p.b * p.k_b;
+        for (int col = tid; col < p.b; col += T) {
+            u64 acc[KB];
+#pragma unroll
+            for (int j = 0; j < KB; ++j) acc[j] = (j < p.k_b) ? __hip_atomic_load(&src[(int64_t)col * p.k_b + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+            for (int s = 1; s < p.S; ++s) {
+                u64 theirs[KB];
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    theirs[j] = (j < p.k_b) ? __hip_atomic_load(&src[((int64_t)s * p.b + col) * p.k_b + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+                merge_topk<KB>(acc, theirs);
+            }
+            if (p.stage2) {
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j < p.k_b) cand[col * p.k_b + j] = acc[j];
+            } else {
+                const int64_t o = (int64_t)r * p.k + (int64_t)col * p.k_b;
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j < p.k_b) write_composite<ELT>(acc[j], p.out_vals, p.out_idx, o + j);
+            }
+        }
+        if (!p.stage2) return;
+        __syncthreads();
+    }
+
+    // ---------------------------------------------------------------- Stage 2 in LDS
+    u64 *sel = cand + n_cand;
+    int kp = pow2_ceil_dev(p.k);
+    uint32_t *hist = (uint32_t *)(sel + kp);
+    select_sort_write<ELT>(cand, n_cand, p.k, sel, hist, p.out_vals, p.out_idx, (int64_t)r);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <int ELT, int V, int KB, int U>
+static hipError_t launch_one(const Plan &pl, const S1Params &prm, hipStream_t stream) {
+    hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T), (size_t)pl.lds_bytes,
+                       stream, prm);
+    return hipGetLastError();
+}
+
+hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state, void *data,
+                         hipStream_t stream) {
+    S1Params prm;
+    prm.x = x;
+    prm.out_vals = out_vals;
+    prm.out_idx = out_idx;
+    prm.tickets = (uint32_t *)state;
+    prm.lists = (u64 *)data;
+    prm.n = pl.n;
+    prm.b = (int)pl.b;
+    prm.L = (int)pl.L;
+    prm.G = (int)pl.G;
+    prm.Gw = pl.Gw;
+    prm.P = pl.P;
+    prm.colblocks = pl.colblocks;
+    prm.S = pl.S;
+    prm.rows_per_split = pl.rows_per_split;
+    prm.k = (int)pl.k;
+    prm.k_b = pl.k_b;
+    prm.stage2 = pl.stage2;
+    prm.direct = pl.direct;
+    prm.use_scratch = pl.use_scratch;
+    const uintptr_t ov = (uintptr_t)out_vals, oi = (uintptr_t)out_idx;
+    prm.vec_store = ((ov | oi) & 15u) == 0;
+    {
+        const char *e = getenv("ATK_SYNC");
+        prm.fence_sync = (e && strcmp(e, "fence") == 0) ? 1 : 0;
+    }
+    // (element type, columns per lane, slots) combinations that make_plan() can choose
+#define ATK_CASE(ELT, VV, KK, UU) \
+    if (pl.dtype == ELT && pl.V == VV && pl.KB == KK) return launch_one<ELT, VV, KK, UU>(pl, prm, stream);
+    ATK_CASE(ATK_F32, 4, 1, 8)
+    ATK_CASE(ATK_F32, 4, 2, 4)
+    ATK_CASE(ATK_F32, 4, 4, 4)
+    ATK_CASE(ATK_F32, 4, 8, 2)
+    ATK_CASE(ATK_F32, 2, 16, 2)
+    ATK_CASE(ATK_F32, 1, 1, 8)
+    ATK_CASE(ATK_F32, 1, 2, 4)
+    ATK_CASE(ATK_F32, 1, 4, 4)
+    ATK_CASE(ATK_F32, 1, 8, 4)
+    ATK_CASE(ATK_F32, 1, 16, 2)
+    ATK_CASE(ATK_BF16, 8, 1, 8)
+    ATK_CASE(ATK_BF16, 8, 2, 4)
+    ATK_CASE(ATK_BF16, 8, 4, 2)
+    ATK_CASE(ATK_BF16, 4, 8, 2)
+    ATK_CASE(ATK_BF16, 2, 16, 2)
+    ATK_CASE(ATK_BF16, 1, 1, 8)
+    ATK_CASE(ATK_BF16, 1, 2, 4)
+    ATK_CASE(ATK_BF16, 1, 4, 4)
+    ATK_CASE(ATK_BF16, 1, 8, 4)
+    ATK_CASE(ATK_BF16, 1, 16, 2)
+#undef ATK_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace atk

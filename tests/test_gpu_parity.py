@@ -1,0 +1,226 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, bit for bit.
+
+Values are compared as raw bits and indices as int32; both are unique under the tie rule
+(equal values -> lower index), so a plain array comparison is the whole test.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_04358_amd as atk
+from paper_2412_04358_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    atk.load_library()  # raises if the HIP library is not built: no fallback
+
+
+def as_bits(t):
+    a = t.detach().cpu().contiguous()
+    if a.dtype == torch.float32:
+        return a.numpy().view(np.uint32)
+    return a.view(torch.int16).numpy().view(np.uint16)
+
+
+def run_case(x_cpu, k, b, k_b, rows=None, tag=""):
+    print("case %s shape=%s dtype=%s k=%d b=%d k_b=%d plan=[%s]" % (
+        tag, tuple(x_cpu.shape), x_cpu.dtype, k, b, k_b,
+        atk.plan_describe(x_cpu.shape[0], x_cpu.shape[1], k, b, k_b,
+                          atk.ATK_F32 if x_cpu.dtype == torch.float32 else atk.ATK_BF16)), flush=True)
+    xg = x_cpu.cuda()
+    vals, idx = atk.approx_topk(xg, k, b, k_b)
+    torch.cuda.synchronize()
+    gv, gi = as_bits(vals), idx.cpu().numpy()
+    xo = workloads.as_numpy_bits(x_cpu)
+    if rows is not None:
+        xo, gv, gi = xo[rows], gv[rows], gi[rows]
+    ov, oi = oracle.approx_topk(xo, k, b, k_b, threads=THREADS)
+    ovb = ov.view(np.uint32) if ov.dtype == np.float32 else ov
+    if not np.array_equal(gi, oi):
+        bad = np.argwhere(gi != oi)
+        same_set = all(sorted(gi[r].tolist()) == sorted(oi[r].tolist()) for r in np.unique(bad[:, 0])[:8])
+        raise AssertionError("indices differ at %d places, first %s: gpu %d oracle %d (same set per row: %s)" % (
+            len(bad), bad[0], gi[tuple(bad[0])], oi[tuple(bad[0])], same_set))
+    assert np.array_equal(gv, ovb), "values differ"
+
+
+def run_exact(x_cpu, k, rows=None):
+    print("exact shape=%s dtype=%s k=%d" % (tuple(x_cpu.shape), x_cpu.dtype, k), flush=True)
+    xg = x_cpu.cuda()
+    vals, idx = atk.exact_topk(xg, k)
+    torch.cuda.synchronize()
+    gv, gi = as_bits(vals), idx.cpu().numpy()
+    xo = workloads.as_numpy_bits(x_cpu)
+    if rows is not None:
+        xo, gv, gi = xo[rows], gv[rows], gi[rows]
+    ov, oi = oracle.exact_topk(xo, k, threads=THREADS)
+    ovb = ov.view(np.uint32) if ov.dtype == np.float32 else ov
+    assert np.array_equal(gi, oi), "exact_topk indices differ"
+    assert np.array_equal(gv, ovb), "exact_topk values differ"
+
+
+# ------------------------------------------------------------------------------- the five configurations
+def test_cfg1():
+    x = workloads.config_input("cfg1")
+    for k, b, k_b in workloads.CONFIGS["cfg1"]["cases"]:
+        run_case(x, k, b, k_b, tag="cfg1")
+
+
+def test_cfg2_small_k_sweep_b():
+    x = workloads.config_input("cfg2")
+    for k, b, k_b in workloads.CONFIGS["cfg2"]["cases"]:
+        run_case(x, k, b, k_b, tag="cfg2")
+
+
+def test_cfg3_large_k_sweep_kb():
+    x = workloads.config_input("cfg3")
+    for k, b, k_b in workloads.CONFIGS["cfg3"]["cases"]:
+        run_case(x, k, b, k_b, tag="cfg3")
+
+
+def test_cfg4_long_rows():
+    x = workloads.config_input("cfg4")
+    rows = [0, 1, 17, 63, 64, 126, 127]  # the oracle checks these rows of the full-size run
+    for k, b, k_b in workloads.CONFIGS["cfg4"]["cases"]:
+        run_case(x, k, b, k_b, rows=rows, tag="cfg4")
+
+
+def test_cfg5_attention_scores_bf16():
+    x = workloads.config_input("cfg5")
+    for k, b, k_b in workloads.CONFIGS["cfg5"]["cases"]:
+        run_case(x, k, b, k_b, tag="cfg5")
+
+
+# ------------------------------------------------------------------------------- shapes spanning tiles and tails
+SHAPES = [
+    # (m, n, k, b, k_b)
+    (3, 12288, 96, 96, 1),        # b not a power of two, vector columns (96 % 4 == 0)
+    (3, 12288, 48, 96, 1),        # ... with Stage 2
+    (2, 4098, 6, 6, 1),           # scalar columns, lanes idle in the last phase
+    (2, 4098, 683, 683, 1),       # scalar columns, b > threads, ragged last column block
+    (5, 8192, 8, 8, 1),           # two column groups, 128 phases
+    (5, 8192, 4, 4, 1),           # one column group
+    (5, 8192, 2, 2, 1),
+    (5, 8192, 1, 1, 1),           # arg-max of the row
+    (2, 8192, 16, 1, 16),         # b = 1: exact top-16 through one bucket
+    (3, 20480, 320, 160, 2),
+    (3, 20480, 100, 160, 2),      # Stage 2 with k not a power of two
+    (3, 20480, 15, 5, 3),         # k_b not a power of two
+    (3, 20480, 33, 20, 3),
+    (4, 16384, 1024, 256, 4),
+    (4, 16384, 700, 256, 4),
+    (4, 16384, 512, 64, 8),
+    (4, 16384, 2048, 128, 16),
+    (4, 16384, 100, 128, 16),
+    (4, 16384, 16384, 16384, 1),  # bucket length 1: identity
+    (4, 16384, 8192, 8192, 1),
+    (4, 16384, 4096, 1024, 4),    # bucket length 16, keep 4
+    (4, 16384, 16384, 1024, 16),  # k_b = n/b: every element, each bucket sorted
+    (130, 4096, 64, 128, 1),
+    (1, 1 << 18, 64, 64, 1),      # one long row: many row splits
+    (1, 1 << 18, 64, 512, 1),
+    (1, 1 << 18, 256, 32, 8),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_shapes(dtype):
+    for i, (m, n, k, b, k_b) in enumerate(SHAPES):
+        x = workloads.normal_rows(m, n, seed=100 + i, dtype=dtype)
+        run_case(x, k, b, k_b, tag="shape%d" % i)
+
+
+@pytest.mark.parametrize("plan", ["T=64,S=1", "T=64,S=7", "T=128,S=3", "T=256,S=2", "T=256,S=64"])
+def test_forced_plans(plan, monkeypatch):
+    """The same results whatever the launch geometry (threads per workgroup, row splits)."""
+    monkeypatch.setenv("ATK_PLAN", plan)
+    for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (3, 32768, 2048, 2048, 1),
+                                           (3, 32768, 128, 64, 2), (3, 32768, 100, 32, 4), (2, 32768, 64, 8, 8),
+                                           (2, 32768, 200, 16, 16)]):
+        for dtype in ["f32", "bf16"]:
+            x = workloads.normal_rows(m, n, seed=200 + i, dtype=dtype)
+            run_case(x, k, b, k_b, tag=plan)
+
+
+# ------------------------------------------------------------------------------- ties and special values
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ties_and_specials(dtype):
+    params = [(64, 64, 1), (64, 256, 1), (96, 32, 4), (40, 64, 2), (128, 8, 16), (2048, 2048, 1)]
+    for k, b, k_b in params:
+        run_case(workloads.few_levels(3, 8192, levels=3, seed=1, dtype=dtype), k, b, k_b, tag="3 levels")
+        run_case(workloads.few_levels(3, 8192, levels=1, seed=2, dtype=dtype), k, b, k_b, tag="constant")
+        run_case(workloads.special_values(3, 8192, seed=3, dtype=dtype), k, b, k_b, tag="specials")
+    # rows of -inf only, and of -0 / +0 only
+    x = torch.full((2, 4096), float("-inf"))
+    z = torch.zeros((2, 4096))
+    z[:, ::3] = -0.0
+    for t in (x, z):
+        t = t if dtype == "f32" else t.to(torch.bfloat16)
+        run_case(t, 64, 64, 1, tag="-inf/zeros")
+        run_case(t, 50, 64, 2, tag="-inf/zeros")
+
+
+def test_repeatable():
+    x = workloads.config_input("cfg2").cuda()
+    ref = None
+    for _ in range(5):
+        vals, idx = atk.approx_topk(x, 64, 256, 1)
+        torch.cuda.synchronize()
+        cur = (as_bits(vals).copy(), idx.cpu().numpy().copy())
+        if ref is None:
+            ref = cur
+        assert np.array_equal(cur[0], ref[0]) and np.array_equal(cur[1], ref[1])
+
+
+# ------------------------------------------------------------------------------- exact_topk
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_small_rows(dtype):
+    for m, n, k in [(4, 4096, 64), (3, 1000, 1), (3, 1000, 1000), (2, 3000, 777), (5, 2048, 2048), (7, 33, 5)]:
+        run_exact(workloads.normal_rows(m, n, seed=300 + n, dtype=dtype), k)
+        run_exact(workloads.few_levels(m, n, levels=2, seed=301 + n, dtype=dtype), k)
+        run_exact(workloads.special_values(m, n, seed=302 + n, dtype=dtype), k)
+
+
+def test_b1_equals_exact():
+    x = workloads.normal_rows(3, 4096, seed=9)
+    xg = x.cuda()
+    av, ai = atk.approx_topk(xg, 16, 1, 16)
+    ev, ei = atk.exact_topk(xg, 16)
+    torch.cuda.synchronize()
+    assert torch.equal(ai, ei) and torch.equal(av, ev)
+
+
+# ------------------------------------------------------------------------------- recall (Appendix C, Eq. 1)
+def test_recall_matches_model_cfg2():
+    from oracle import recall
+
+    x = workloads.config_input("cfg2")
+    xg = x.cuda()
+    _, ei = oracle.exact_topk(workloads.as_numpy_bits(x), 64, threads=THREADS)
+    m = x.shape[0]
+    for k, b, k_b in workloads.CONFIGS["cfg2"]["cases"]:
+        _, ai = atk.approx_topk(xg, k, b, k_b)
+        ai = ai.cpu().numpy()
+        rec = np.array([len(set(ei[r].tolist()) & set(ai[r].tolist())) / k for r in range(m)])
+        se = rec.std(ddof=1) / np.sqrt(m)
+        assert abs(rec.mean() - recall.expected_recall_iid_exact(x.shape[1], k, b, k_b)) < 4.5 * se + 1e-9
+
+
+def test_alternating_sizes_share_the_scratch_pool():
+    """Calls of different shapes reuse one scratch pool; tickets must read zero for each of them."""
+    small = workloads.normal_rows(3, 32768, seed=41)
+    big = workloads.normal_rows(128, 65536, seed=42)
+    for _ in range(3):
+        run_case(small, 64, 64, 1, tag="small")
+        run_case(big, 64, 256, 1, tag="big")
+        run_case(small, 128, 64, 2, tag="small")
+        run_case(big, 64, 64, 1, tag="big")

@@ -1,0 +1,137 @@
+"""Host-side checks of the C-ABI library that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2412_04358_amd as atk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(atk.lib_path()):
+        import __graft_entry__
+
+        __graft_entry__.build()
+    return atk.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "approx_topk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted(set(n for n in names if n.startswith("atk_") or n in ("approx_topk", "exact_topk")))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert "approx_topk" in names and "exact_topk" in names and len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), "library does not export %s" % n
+
+
+OK, NULLP, SHAPE, PARAMS, UNSUP, DTYPE = 0, -1, -2, -3, -4, -5
+
+
+@pytest.mark.parametrize("args,code", [
+    ((4, 4096, 64, 64, 1, 0), OK),
+    ((128, 65536, 64, 1024, 1, 0), OK),
+    ((128, 65536, 16384, 1024, 16, 0), OK),
+    ((2048, 8192, 512, 512, 1, 1), OK),
+    ((1, 16, 16, 1, 16, 0), OK),            # b = 1: exact top-k by one bucket
+    ((0, 4096, 64, 64, 1, 0), SHAPE),
+    ((4, 0, 64, 64, 1, 0), SHAPE),
+    ((4, 4096, 0, 64, 1, 0), SHAPE),
+    ((4, 4096, 4097, 64, 1, 0), SHAPE),
+    ((1, 1 << 31, 64, 64, 1, 0), SHAPE),
+    ((4, 4096, 64, 0, 1, 0), PARAMS),
+    ((4, 4096, 64, 8192, 1, 0), PARAMS),    # b > n
+    ((4, 4096, 64, 64, 0, 0), PARAMS),
+    ((4, 4096, 64, 32, 1, 0), PARAMS),      # b*k_b < k
+    ((4, 4096, 8, 8, 16, 0), PARAMS),       # k_b > k
+    ((4, 4096, 4096, 2048, 4, 0), PARAMS),  # k_b > n/b
+    ((4, 4096, 64, 64, 1, 2), DTYPE),
+    ((4, 4096, 64, 64, 1, -1), DTYPE),
+    ((4, 4095, 64, 64, 1, 0), UNSUP),       # n not a multiple of b
+    ((4, 4096, 64, 2, 32, 0), UNSUP),       # k_b above the register-queue cap
+    ((4, 1 << 16, 64, 1 << 14, 1, 0), UNSUP),  # Stage 2 over more candidates than fit on chip
+])
+def test_check_approx(lib, args, code):
+    assert lib.atk_check_approx(*args) == code
+
+
+def test_calls_reject_before_hip(lib):
+    """No GPU here: these must return their code from the host-side checks alone."""
+    fake = 0x1000  # never dereferenced: checks fail first
+    assert lib.approx_topk(None, 4, 4096, 64, 64, 1, 0, fake, fake, None) == NULLP
+    assert lib.approx_topk(fake, 4, 4096, 64, 64, 1, 0, None, fake, None) == NULLP
+    assert lib.approx_topk(fake, 4, 4096, 64, 64, 1, 0, fake, None, None) == NULLP
+    assert lib.approx_topk(fake, 4, 4096, 64, 32, 1, 0, fake, fake, None) == PARAMS
+    assert lib.approx_topk(fake, 4, 4096, 64, 64, 1, 7, fake, fake, None) == DTYPE
+    assert lib.approx_topk(fake + 2, 4, 4096, 64, 64, 1, 0, fake, fake, None) == -7
+    assert lib.exact_topk(None, 4, 4096, 64, 0, fake, fake, None) == NULLP
+    assert lib.exact_topk(fake, 4, 4096, 5000, 0, fake, fake, None) == SHAPE
+    assert lib.exact_topk(fake, 4, 4096, 64, 3, fake, fake, None) == DTYPE
+    assert lib.atk_read_ceiling(None, 1024, fake, None) == NULLP
+    assert lib.atk_sleep(-1, None) == SHAPE
+
+
+def test_strerror(lib):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = atk.strerror(code)
+        assert s and s != "unknown error code"
+        seen.add(s)
+    assert len(seen) == 8
+    assert atk.strerror(-99) == "unknown error code"
+
+
+def parse_plan(s):
+    return {k: int(v) for k, v in (kv.split("=") for kv in s.split())}
+
+
+def test_plan_shapes(lib):
+    # every lane owns whole buckets: straight from registers, one workgroup column block per 1024 columns
+    p = parse_plan(atk.plan_describe(128, 65536, 16384, 16384, 1))
+    assert p["direct"] == 1 and p["P"] == 1 and p["S"] == 1 and p["colblocks"] == 16 and p["stage2"] == 0
+    # few buckets: lanes share columns (P > 1) and rows are split over workgroups, merged via scratch
+    p = parse_plan(atk.plan_describe(128, 65536, 64, 64, 1))
+    assert p["V"] == 4 and p["Gw"] == 16 and p["P"] == 16 and p["S"] > 1 and p["scratch"] == 1 and p["direct"] == 0
+    assert p["S"] * p["rows_per_split"] >= 1024 and (p["S"] - 1) * p["rows_per_split"] < 1024
+    assert p["rows_per_split"] % p["P"] == 0
+    # Stage 2 fused
+    p = parse_plan(atk.plan_describe(128, 65536, 64, 1024, 1))
+    assert p["stage2"] == 1 and p["lds"] >= (1024 + 64) * 8
+    # bf16 uses 8 columns per lane
+    p = parse_plan(atk.plan_describe(2048, 8192, 512, 512, 1, atk.ATK_BF16))
+    assert p["V"] == 8 and p["Gw"] == 64
+    # b not a multiple of the vector width: scalar columns
+    p = parse_plan(atk.plan_describe(2, 4098, 6, 6, 1))
+    assert p["V"] == 1
+    # the grid always covers every matrix row and column exactly once
+    for (m, n, k, b, kb) in [(1, 4096, 64, 64, 1), (3, 12288, 96, 96, 1), (7, 1 << 20, 64, 8, 8), (128, 1 << 20, 1 << 18, 1 << 15, 8)]:
+        p = parse_plan(atk.plan_describe(m, n, k, b, kb))
+        assert p["grid"] == m * p["S"] * p["colblocks"]
+        assert p["colblocks"] * p["Gw"] * p["V"] >= b
+        assert p["S"] * p["rows_per_split"] >= n // b
+
+
+def test_plan_override_env(lib, monkeypatch):
+    monkeypatch.setenv("ATK_PLAN", "T=64,S=3")
+    p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
+    assert p["T"] == 64 and p["S"] == 3
+    monkeypatch.delenv("ATK_PLAN")
+    q = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
+    assert q["T"] == 256
+
+
+def test_workspace_bytes(lib):
+    assert lib.atk_workspace_bytes(128, 65536, 16384, 16384, 1, 0) == 0
+    p = parse_plan(atk.plan_describe(128, 65536, 64, 64, 1))
+    assert lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0) == p["scratch_bytes"] > 0
+    assert lib.atk_workspace_bytes(128, 65536, 64, 32, 1, 0) == PARAMS
+    assert lib.atk_stage2_max_candidates() >= 1024
