@@ -6,6 +6,7 @@
 #include <mutex>
 
 #include "atk_common.h"
+#include "atk_select.h"
 
 namespace atk {
 
@@ -53,7 +54,7 @@ static void plan_override(int *T, int *S) {
     const char *p = strstr(e, "T=");
     if (p && T) {
         int v = atoi(p + 2);
-        if (v == 64 || v == 128 || v == 256) *T = v;
+        if (v == 64 || v == 128 || v == 256 || v == 512 || v == 1024) *T = v;
     }
     p = strstr(e, "S=");
     if (p && S) {
@@ -85,30 +86,54 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.L = n / b;
     p.stage2 = b * k_b > k;
 
-    int T = kMaxThreads, S_forced = 0;
-    plan_override(&T, &S_forced);
-    // keep the LDS merge tree (KB*V*T composites) inside 48 KB
-    while ((int64_t)p.KB * p.V * T * 8 > 48 * 1024 && T > kWave) T >>= 1;
-    p.Gw = (int)((p.G < T) ? p.G : T);
-    p.P = T / p.Gw;
-    if (p.P > p.L) p.P = (int)p.L;
-    if (p.P < 1) p.P = 1;
-    {
-        int64_t need = (int64_t)p.P * p.Gw;
-        T = (int)(ceil_div(need, kWave) * kWave);
-        if (T > kMaxThreads) T = kMaxThreads;
+    // ---- workgroup size T and row splits S
+    // Aim at about 16 vector loads per lane over the whole launch (in flight in batches), at least one workgroup per CU, and as few row splits as that allows: a split
+    // costs a trip through memory at the end.  Narrow bucket layouts (fewer column groups
+    // than lanes) take big workgroups, whose lanes merge through shuffles and LDS.
+    const int t_max = max_threads_for_kb(p.KB);
+    int T_forced = 0, S_forced = 0;
+    plan_override(&T_forced, &S_forced);
+    const int64_t n_vec = m * (n / p.V);
+    int64_t want_threads = n_vec / 16;
+    if (want_threads < 64 * (int64_t)kNumCU) want_threads = 64 * (int64_t)kNumCU;
+    if (want_threads > 2048 * (int64_t)kNumCU) want_threads = 2048 * (int64_t)kNumCU;
+    int T = 256;
+    if (p.G <= 256) {
+        T = t_max < 512 ? t_max : 512;
+        while (T > 256 && m * T * 2 > want_threads) T >>= 1;  // keep at least two splits' worth of lanes
     }
-    p.T = T;
+    if (T_forced) T = T_forced;
+    if (T > t_max) T = t_max;
+
+    int64_t lds = 0;
+    for (;;) {
+        p.Gw = (int)((p.G < T) ? p.G : T);
+        p.P = T / p.Gw;
+        if (p.P > p.L) p.P = (int)p.L;
+        if (p.P < 1) p.P = 1;
+        int t_used = (int)(ceil_div((int64_t)p.P * p.Gw, kWave) * kWave);
+        if (t_used > T) t_used = T;
+        p.T = t_used;
+        p.wave_merge = p.P > 1 && p.Gw < kWave && (p.Gw & (p.Gw - 1)) == 0;
+        p.nparts = p.wave_merge ? p.T / kWave : p.P;
+        const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * b * p.KB * 8 : 0;
+        const int64_t lds_s2 = p.stage2 ? select_lds_bytes(b * k_b, (int)pow2_ceil(k)) : 0;
+        p.lds_xch_off = 16;
+        p.lds_cand_off = (int)(16 + lds_xch);
+        lds = 16 + lds_xch + lds_s2;
+        if (lds <= kLdsBudget || T <= kWave) break;
+        T >>= 1;
+    }
+    if (p.stage2 && b * k_b > kStage2MaxCand) return ATK_ERR_UNSUPPORTED;
+    if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
+    p.lds_bytes = (int)lds;
+    T = p.T;
     p.colblocks = (int)ceil_div(p.G, p.Gw);
 
-    // row splits: enough workgroups to fill 256 CUs, every lane keeps >= 4 loads, and the
-    // partial lists stay below 1/8 of the bytes streamed
     int64_t base = m * p.colblocks;
-    int64_t target_wgs = (int64_t)kNumCU * 1024 / T;
-    int64_t S = 1;
-    if (base < target_wgs) S = ceil_div(target_wgs, base);
-    int64_t s_rows = p.L / ((int64_t)p.P * 4);
-    int64_t s_traffic = (p.L * es) / (128 * k_b);
+    int64_t S = want_threads / (base * T);
+    int64_t s_rows = p.L / ((int64_t)p.P * 4);       // every lane keeps at least 4 loads
+    int64_t s_traffic = (p.L * es) / (128 * k_b);    // partial lists below 1/8 of the bytes streamed
     if (S > s_rows) S = s_rows;
     if (S > s_traffic) S = s_traffic;
     if (S_forced) S = S_forced;
@@ -122,14 +147,6 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
 
     p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
     p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
-
-    int64_t lds_tree = (p.P > 1) ? (int64_t)p.KB * p.V * T * 8 : 0;
-    int64_t lds_s2 = p.stage2 ? (b * k_b + pow2_ceil(k)) * 8 + 264 * 4 : 0;
-    int64_t lds = lds_tree > lds_s2 ? lds_tree : lds_s2;
-    if (lds < 64) lds = 64;
-    if (p.stage2 && b * k_b > kStage2MaxCand) return ATK_ERR_UNSUPPORTED;
-    if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
-    p.lds_bytes = (int)lds;
 
     p.scratch_ticket_bytes = p.use_scratch ? m * kTicketStride * 4 : 0;
     p.scratch_lists_bytes = p.use_scratch ? m * p.S * b * k_b * 8 : 0;
@@ -285,9 +302,9 @@ int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, i
     if (rc != ATK_OK) return rc;
     snprintf(buf, (size_t)buflen,
              "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
-             "scratch=%d lds=%d scratch_bytes=%lld",
+             "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld",
              pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid,
-             (int)pl.stage2, (int)pl.direct, (int)pl.use_scratch, pl.lds_bytes,
+             (int)pl.stage2, (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
              (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes));
     return ATK_OK;
 }

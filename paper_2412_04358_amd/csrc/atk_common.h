@@ -12,8 +12,10 @@ typedef unsigned long long u64;
 namespace atk {
 
 constexpr int kWave = 64;
-constexpr int kMaxThreads = 256;          // threads per workgroup of the streaming kernels
-constexpr int kStage2MaxCand = 8192;      // composites held in LDS by the fused Stage 2
+constexpr int kMaxThreads = 256;          // threads per workgroup of the select kernels
+// largest workgroup of the streaming kernel: big register queues (k_b >= 8) keep to 256 lanes
+constexpr int max_threads_for_kb(int KB) { return KB <= 4 ? 1024 : 256; }
+constexpr int kStage2MaxCand = 4096;      // composites held in LDS by the fused Stage 2
 constexpr int kLdsBudget = 64 * 1024;     // static+dynamic LDS per workgroup we allow ourselves
 constexpr int kNumCU = 256;               // MI355X
 constexpr int kTicketStride = 32;          // words between row tickets: one 128-byte line each, so that
@@ -43,6 +45,9 @@ struct Plan {
     bool stage2;      // b*k_b > k
     bool direct;      // every lane owns whole buckets: write results straight from registers
     bool use_scratch; // partial lists go through global scratch + a per-row ticket
+    bool wave_merge;  // Gw < 64 and a power of two: lanes of a wavefront share columns, merged by shuffles
+    int nparts;       // partial lists per column left for the LDS exchange
+    int lds_xch_off, lds_cand_off;
     int64_t scratch_lists_bytes;   // composites
     int64_t scratch_ticket_bytes;  // one counter per row
     int lds_bytes;    // dynamic LDS of the launch
@@ -105,6 +110,13 @@ __device__ __forceinline__ uint32_t composite_bits(u64 c) {
 }
 
 __device__ __forceinline__ u64 umax64(u64 a, u64 b) { return a > b ? a : b; }
+
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int lane_mask) {
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = (uint32_t)__shfl_xor((int)lo, lane_mask, kWave);
+    hi = (uint32_t)__shfl_xor((int)hi, lane_mask, kWave);
+    return ((u64)hi << 32) | lo;
+}
 
 // mine <- the KB largest of (mine U theirs); both sorted descending, result sorted descending.
 template <int KB>

@@ -22,7 +22,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.chunks = 1;
     p.scratch_bytes = 0;
     p.state_bytes = 0;
-    int64_t lds = (n + pow2_ceil64(k)) * 8 + 264 * 4;
+    int64_t lds = select_lds_bytes(n, (int)pow2_ceil64(k < (1 << 20) ? k : (1 << 20)));
     p.single_wg = lds <= kLdsBudget;
     if (!p.single_wg) return ATK_ERR_UNSUPPORTED;
     if (m >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
@@ -37,18 +37,22 @@ __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x,
     extern __shared__ __align__(16) unsigned char smem[];
     u64 *cand = (u64 *)smem;
     const int r = blockIdx.x;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-        uint32_t bits;
-        if (ELT == ATK_F32)
-            bits = ((const uint32_t *)x)[(int64_t)r * n + i];
-        else
-            bits = ((uint32_t)((const uint16_t *)x)[(int64_t)r * n + i]) << 16;
-        cand[i] = make_composite(bits, i);
+    const int T = blockDim.x;
+    auto load_bits = [&](int i) -> uint32_t {
+        if (ELT == ATK_F32) return ((const uint32_t *)x)[(int64_t)r * n + i];
+        return ((uint32_t)((const uint16_t *)x)[(int64_t)r * n + i]) << 16;
+    };
+    int i = threadIdx.x;
+    for (; i + 3 * T < n; i += 4 * T) {  // four loads in flight
+        uint32_t b0 = load_bits(i), b1 = load_bits(i + T), b2 = load_bits(i + 2 * T), b3 = load_bits(i + 3 * T);
+        cand[i] = make_composite(b0, i);
+        cand[i + T] = make_composite(b1, i + T);
+        cand[i + 2 * T] = make_composite(b2, i + 2 * T);
+        cand[i + 3 * T] = make_composite(b3, i + 3 * T);
     }
+    for (; i < n; i += T) cand[i] = make_composite(load_bits(i), i);
     __syncthreads();
-    u64 *sel = cand + n;
-    uint32_t *hist = (uint32_t *)(sel + pow2_ceil_dev(k));
-    select_sort_write<ELT>(cand, n, k, sel, hist, out_vals, out_idx, (int64_t)r);
+    select_write<ELT>(cand, n, k, out_vals, out_idx, (int64_t)r);
 }
 
 hipError_t launch_exact(const ExactPlan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state,

@@ -3,8 +3,10 @@
 // exact top-k to select the k largest values") and the body of the small-row exact_topk.
 // The radix descent follows the RadixSelect scheme of Appendix D.2 (most significant
 // digit first, keep the digit bucket that contains the k-th element), with 8-bit digits
-// and an LDS histogram; because composites are distinct the descent ends as soon as the
-// chosen digit bucket holds exactly the number of elements still needed.
+// and an LDS histogram.  Two departures: the descent starts at the highest bit in which
+// the candidates differ at all (their common leading bits cannot separate anything), and,
+// because composites are distinct, it stops as soon as the chosen digit bucket holds
+// exactly the number of elements still needed.
 #pragma once
 
 #include "atk_common.h"
@@ -13,12 +15,19 @@ namespace atk {
 
 #ifdef __HIPCC__
 
-constexpr int kHistWords = 256 + 8;  // 256 bins + [256]=digit, [257]=need, [258]=bucket count, [259]=write cursor
-
-__device__ __forceinline__ int pow2_ceil_dev(int v) {
+__host__ __device__ constexpr int pow2_ceil_c(int v) {
     int p = 1;
     while (p < v) p <<= 1;
     return p;
+}
+__device__ __forceinline__ int pow2_ceil_dev(int v) { return pow2_ceil_c(v); }
+
+// ---- LDS layout behind the `count` candidates -------------------------------------------------
+constexpr int kRankMax = 256;                 // largest k ordered by all-pairs ranking (else bitonic sort)
+constexpr int kSelWredWords = 32;             // u64: per-wavefront OR / AND
+constexpr int kSelU32Words = 512 + 8 + 8 + kRankMax;  // two histograms, scan result, cursor, ranks
+__host__ __device__ constexpr int64_t select_lds_bytes(int64_t count, int kp) {
+    return (count + kp + kSelWredWords) * 8 + kSelU32Words * 4;
 }
 
 // Decode a composite and store it as output element `pos` (absolute element offset).
@@ -28,93 +37,209 @@ __device__ __forceinline__ void write_composite(u64 c, void *out_vals, int32_t *
     out_idx[pos] = composite_index(c);
 }
 
-template <int ELT>
-__device__ void select_sort_write(u64 *cand, int count, int k, u64 *sel, uint32_t *hist, void *out_vals,
-                                  int32_t *out_idx, int64_t row_out) {
-    const int tid = threadIdx.x, T = blockDim.x;
+// Number of entries of list[j0..j1) that are larger than c; eight LDS reads in flight at a time.
+__device__ __forceinline__ int count_larger(const u64 *list, int j0, int j1, u64 c) {
+    int rank = 0;
+    int j = j0;
+    for (; j + 8 <= j1; j += 8) {
+        u64 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = list[j + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) rank += (v[u] > c) ? 1 : 0;
+    }
+    for (; j < j1; ++j) rank += (list[j] > c) ? 1 : 0;
+    return rank;
+}
 
-    // ---- radix descent: find thr such that exactly k composites are >= thr
-    u64 prefix = 0;
+// ---- wavefront helpers (DPP: register-to-register, no LDS traffic) -----------------------------
+// dpp_ctrl codes: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_shr:n = 0x110+n,
+// row_mirror = 0x140, row_half_mirror = 0x141, row_bcast:15 = 0x142, row_bcast:31 = 0x143.
+template <int CTRL>
+__device__ __forceinline__ u64 dpp_u64(u64 v) {
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, 0xf, 0xf, false);
+    hi = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, 0xf, 0xf, false);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
+    return ((u64)hi << 32) | lo;
+}
+// OR and AND over the 64 lanes of a fully active wavefront (result in every lane).  The two
+// quad permutations and the two mirrors fold a row of 16 lanes; the four rows are read out.
+__device__ __forceinline__ void wave_or_and_u64(u64 &o, u64 &a) {
+    o |= dpp_u64<0xB1>(o);
+    a &= dpp_u64<0xB1>(a);
+    o |= dpp_u64<0x4E>(o);
+    a &= dpp_u64<0x4E>(a);
+    o |= dpp_u64<0x141>(o);
+    a &= dpp_u64<0x141>(a);
+    o |= dpp_u64<0x140>(o);
+    a &= dpp_u64<0x140>(a);
+    o = readlane_u64(o, 0) | readlane_u64(o, 16) | readlane_u64(o, 32) | readlane_u64(o, 48);
+    a = readlane_u64(a, 0) & readlane_u64(a, 16) & readlane_u64(a, 32) & readlane_u64(a, 48);
+}
+// Lanes without a source (row edge) or outside ROW_MASK receive 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_zero_fill(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true);
+}
+// Inclusive prefix sum over the lanes of a fully active wavefront.
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+    v += dpp_zero_fill<0x111, 0xf>(v);  // row_shr:1
+    v += dpp_zero_fill<0x112, 0xf>(v);  // row_shr:2
+    v += dpp_zero_fill<0x114, 0xf>(v);  // row_shr:4
+    v += dpp_zero_fill<0x118, 0xf>(v);  // row_shr:8  -> inclusive scan inside each row of 16
+    v += dpp_zero_fill<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    v += dpp_zero_fill<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// Exact top-k of the `count` distinct composites at cand[0..count) (LDS), written largest
+// first to row `row_out` (row stride k).  `cand` must be followed by
+// select_lds_bytes(count, pow2_ceil(k)) - count*8 bytes of free LDS.  All threads of the
+// workgroup call it; blockDim.x is a multiple of 64.
+template <int ELT>
+__device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_t *out_idx, int64_t row_out) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6, n_waves = T >> 6;
+    const int kp = pow2_ceil_dev(k);
+    u64 *sel = cand + count;                              // [kp]
+    u64 *wred = sel + kp;                                 // [32]
+    uint32_t *hist = (uint32_t *)(wred + kSelWredWords);  // [2][256]
+    uint32_t *res = hist + 512;                           // [0]=digit [1]=need [2]=bucket count
+    uint32_t *cursor = res + 8;                           // [0]
+    uint32_t *rk = cursor + 8;                            // [kRankMax]
+
+    // ---- common leading bits
+    for (int i = tid; i < kSelU32Words; i += T) hist[i] = 0;
+    u64 x_or = 0ull, x_and = ~0ull;
+    for (int i = tid; i < count; i += T) {
+        const u64 c = cand[i];
+        x_or |= c;
+        x_and &= c;
+    }
+    wave_or_and_u64(x_or, x_and);
+    if (lane == 0) {
+        wred[2 * wave] = x_or;
+        wred[2 * wave + 1] = x_and;
+    }
+    __syncthreads();
+    for (int w = 0; w < n_waves; ++w) {
+        x_or |= wred[2 * w];
+        x_and &= wred[2 * w + 1];
+    }
+    const u64 diff = x_or ^ x_and;
+    const int top = diff ? 63 - __clzll((long long)diff) : 0;
+    // the digit of a pass is bits [shift + width - 1 : shift]; bits above it are decided (prefix)
+    int shift = top > 7 ? top - 7 : 0;
+    uint32_t dmask = (1u << (top - shift + 1)) - 1u;
+    u64 hi_mask = (top >= 63) ? 0ull : (~0ull << (top + 1));
+    u64 prefix = x_and & hi_mask;
     int need = k;
-    int shift = 56;
+
+    // ---- radix descent: find prefix such that exactly k composites are >= prefix
+    int pb = 0;
     while (true) {
-        for (int i = tid; i < kHistWords; i += T) hist[i] = 0;
-        __syncthreads();
-        const u64 hi_mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
+        uint32_t *h = hist + 256 * pb;
         for (int i = tid; i < count; i += T) {
-            u64 c = cand[i];
-            if ((c & hi_mask) == prefix) atomicAdd(&hist[(uint32_t)(c >> shift) & 255u], 1u);
+            const u64 c = cand[i];
+            if ((c & hi_mask) == prefix) atomicAdd(&h[(uint32_t)(c >> shift) & dmask], 1u);
         }
         __syncthreads();
-        if (tid < kWave) {
-            // lane l owns bins 4l..4l+3; suffix sums from the top bin down
-            uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
-            uint32_t lane_sum = h0 + h1 + h2 + h3;
-            uint32_t incl = lane_sum;  // sum over lanes >= tid
-#pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                uint32_t other = __shfl_down(incl, off, kWave);
-                if (tid + off < kWave) incl += other;
-            }
-            uint32_t above = incl - lane_sum;  // elements in bins of higher lanes
-            // walk own bins from high to low
-            uint32_t hb[4] = {h0, h1, h2, h3};
+        if (wave == 0) {
+            // lane l owns the four bins 252-4l .. 255-4l, so lane order is descending bin order
+            const uint32_t *hl = &h[252 - 4 * lane];
+            const uint32_t b4[4] = {hl[0], hl[1], hl[2], hl[3]};
+            const uint32_t lane_sum = b4[0] + b4[1] + b4[2] + b4[3];
+            uint32_t above = wave_incl_scan_u32(lane_sum) - lane_sum;  // elements in higher bins
 #pragma unroll
             for (int q = 3; q >= 0; --q) {
-                uint32_t with = above + hb[q];
+                const uint32_t with = above + b4[q];
                 if (above < (uint32_t)need && with >= (uint32_t)need) {
-                    hist[256] = 4 * tid + q;
-                    hist[257] = (uint32_t)need - above;
-                    hist[258] = hb[q];
+                    res[0] = 252 - 4 * lane + q;
+                    res[1] = (uint32_t)need - above;
+                    res[2] = b4[q];
                 }
                 above = with;
             }
         }
+        // the other histogram is cleared for the next pass while wavefront 0 scans
+        if (n_waves > 1) {
+            if (wave >= 1)
+                for (int i = tid - kWave; i < 256; i += T - kWave) hist[256 * (pb ^ 1) + i] = 0;
+        } else {
+            for (int i = tid; i < 256; i += T) hist[256 * (pb ^ 1) + i] = 0;
+        }
         __syncthreads();
-        const uint32_t digit = hist[256];
-        const int bucket_count = (int)hist[258];
-        need = (int)hist[257];
+        const uint32_t digit = res[0];
+        const int bucket_count = (int)res[2];
+        need = (int)res[1];
         prefix |= (u64)digit << shift;
-        __syncthreads();  // everyone has read hist before it is cleared again
         if (bucket_count == need || shift == 0) break;
-        shift -= 8;
+        const int next = shift >= 8 ? shift - 8 : 0;  // the last digit may be narrower than 8 bits
+        hi_mask = ~0ull << shift;
+        dmask = (1u << (shift - next)) - 1u;
+        shift = next;
+        pb ^= 1;
     }
-    // every composite whose bits above `shift` are >= prefix is selected
+    // every composite >= prefix is selected (bits below `shift` of prefix are zero)
     const u64 thr = prefix;
 
-    // ---- compaction (arbitrary order)
-    if (tid == 0) hist[259] = 0;
-    __syncthreads();
-    for (int i = tid; i < count; i += T) {
-        u64 c = cand[i];
-        if (c >= thr) {
-            uint32_t pos = atomicAdd(&hist[259], 1u);
-            sel[pos] = c;
-        }
+    // ---- compaction into sel[0..k): one LDS atomic per wavefront and round
+    for (int i0 = 0; i0 < count; i0 += T) {
+        const int i = i0 + tid;
+        const u64 c = (i < count) ? cand[i] : 0ull;
+        const bool keep = (i < count) && (c >= thr);
+        const u64 mask = __ballot(keep);
+        const int n_keep = __popcll(mask);
+        uint32_t base = 0;
+        if (lane == 0 && n_keep) base = atomicAdd(&cursor[0], (uint32_t)n_keep);
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        const uint32_t pos =
+            base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (keep) sel[pos] = c;
     }
     __syncthreads();
 
     // ---- order the k survivors, largest first
-    if (k <= 256) {
-        // rank sort: position = number of larger survivors
-        for (int i = tid; i < k; i += T) {
-            u64 c = sel[i];
-            int rank = 0;
-            for (int j = 0; j < k; ++j) rank += (sel[j] > c) ? 1 : 0;
-            write_composite<ELT>(c, out_vals, out_idx, row_out * k + rank);
+    if (k <= kRankMax) {
+        // rank = number of larger survivors; iw lanes side by side take one survivor each and
+        // the T/iw groups of lanes split the range of partners
+        int iw = kWave, iw_shift = 6;
+        while (iw < k && iw < T) {
+            iw <<= 1;
+            ++iw_shift;
         }
+        const int parts = T >> iw_shift;
+        if (parts == 1) {
+            for (int i = tid; i < k; i += iw)
+                write_composite<ELT>(sel[i], out_vals, out_idx, row_out * k + count_larger(sel, 0, k, sel[i]));
+            return;
+        }
+        const int chunk = (k + parts - 1) / parts;
+        const int part = tid >> iw_shift;
+        const int j0 = part * chunk, j1 = min(k, j0 + chunk);
+        const int i = tid & (iw - 1);
+        if (i < k && j0 < j1) {
+            const int r = count_larger(sel, j0, j1, sel[i]);
+            if (r) atomicAdd(&rk[i], (uint32_t)r);
+        }
+        __syncthreads();
+        for (int q = tid; q < k; q += T) write_composite<ELT>(sel[q], out_vals, out_idx, row_out * k + (int)rk[q]);
     } else {
-        const int kp = pow2_ceil_dev(k);
         for (int i = k + tid; i < kp; i += T) sel[i] = 0;  // empties sort to the end
         __syncthreads();
         for (int size = 2; size <= kp; size <<= 1) {
             for (int stride = size >> 1; stride >= 1; stride >>= 1) {
                 for (int i = tid; i < (kp >> 1); i += T) {
-                    int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));
-                    int hi = lo + stride;
-                    bool desc = (lo & size) == 0;
-                    u64 a = sel[lo], c = sel[hi];
-                    bool sw = desc ? (c > a) : (c < a);
+                    const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));
+                    const int hi = lo + stride;
+                    const bool desc = (lo & size) == 0;
+                    const u64 a = sel[lo], c = sel[hi];
+                    const bool sw = desc ? (c > a) : (c < a);
                     if (sw) {
                         sel[lo] = c;
                         sel[hi] = a;

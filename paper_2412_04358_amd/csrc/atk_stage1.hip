@@ -30,6 +30,10 @@ struct S1Params {
     int b, L, G, Gw, P, colblocks, S, rows_per_split;
     int k, k_b;
     int stage2, direct, use_scratch, vec_store;
+    int wave_merge;      // Gw < 64 and a power of two: lanes of one wavefront share columns
+    int nparts;          // partial lists per column left after the wavefront merge
+    int lds_xch_off, lds_cand_off;  // byte offsets of the exchange and candidate areas in LDS
+    int cb_shift, s_shift, gw_shift;  // log2 of colblocks, S, Gw when those are powers of two, else -1
     int fence_sync;      // debugging aid: add full agent-scope fences around the ticket
 };
 
@@ -77,6 +81,17 @@ __device__ __forceinline__ uint32_t elem_bits(const RowVec<ELT, V> &r, int e) {
     }
 }
 
+// q = x / d, rem = x % d; shift = log2(d) when d is a power of two, else -1
+__device__ __forceinline__ void divmod(int x, int d, int shift, int &q, int &rem) {
+    if (shift >= 0) {
+        q = x >> shift;
+        rem = x & (d - 1);
+    } else {
+        q = x / d;
+        rem = x - q * d;
+    }
+}
+
 // Insert (v, t) into the descending list (val, tt); later elements never displace equal
 // earlier ones ("!(v <= slot)" is "v > slot" for numbers and true for the NaN that marks
 // an empty slot).
@@ -94,17 +109,15 @@ __device__ __forceinline__ void insert(float (&val)[KB], int (&tt)[KB], float v,
     tt[0] = c[0] ? t : tt[0];
 }
 
-template <int ELT, int V, int KB, int U>
-__global__ void __launch_bounds__(kMaxThreads) stage1_kernel(S1Params p) {
+template <int ELT, int V, int KB, int U, int MAXT>
+__global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int ES = (ELT == ATK_F32) ? 4 : 2;
     const int tid = threadIdx.x, T = blockDim.x;
-    int wg = blockIdx.x;
-    const int cb = wg % p.colblocks;
-    wg /= p.colblocks;
-    const int sp = wg % p.S;
-    const int r = wg / p.S;
-    const int cgl = tid % p.Gw, ph = tid / p.Gw;
+    int wg = blockIdx.x, cb, sp, r, cgl, ph;
+    divmod(wg, p.colblocks, p.cb_shift, wg, cb);
+    divmod(wg, p.S, p.s_shift, r, sp);
+    divmod(tid, p.Gw, p.gw_shift, ph, cgl);
     const int cg = cb * p.Gw + cgl;
     const bool active = (ph < p.P) && (cg < p.G);
     const int t0 = sp * p.rows_per_split;
@@ -209,100 +222,119 @@ __global__ void __launch_bounds__(kMaxThreads) stage1_kernel(S1Params p) {
                              ? make_composite(__float_as_uint(val[e][j]), tt[e][j] * p.b + col0 + e)
                              : 0ull;
 
-    // ---------------------------------------------------------------- merge the row phases (LDS tree)
-    if (p.P > 1) {
-        u64 *l = (u64 *)smem;  // word (j*V + e) of thread `tid` lives at l[(j*V + e)*T + tid]
-        int h = 1;
-        while (h < p.P) h <<= 1;
-        for (h >>= 1; h >= 1; h >>= 1) {
-            if (ph >= h && ph < 2 * h && active) {
+    // ---------------------------------------------------------------- merge inside the wavefront
+    // With fewer than 64 column groups the lanes l, l+Gw, l+2Gw, ... of a wavefront share
+    // their columns: a butterfly over those lane strides leaves the merged list in all of them.
+    if (p.wave_merge) {
+        for (int off = p.Gw; off < kWave; off <<= 1) {
 #pragma unroll
-                for (int e = 0; e < V; ++e)
+            for (int e = 0; e < V; ++e) {
+                u64 theirs[KB];
 #pragma unroll
-                    for (int j = 0; j < KB; ++j) l[(j * V + e) * T + tid] = comp[e][j];
+                for (int j = 0; j < KB; ++j) theirs[j] = shfl_xor_u64(comp[e][j], off);
+                merge_topk<KB>(comp[e], theirs);
             }
-            __syncthreads();
-            if (ph < h && ph + h < p.P && active) {
-                const int peer = tid + h * p.Gw;
-#pragma unroll
-                for (int e = 0; e < V; ++e) {
-                    u64 theirs[KB];
-#pragma unroll
-                    for (int j = 0; j < KB; ++j) theirs[j] = l[(j * V + e) * T + peer];
-                    merge_topk<KB>(comp[e], theirs);
-                }
-            }
-            __syncthreads();
         }
     }
-    const bool owner = active && ph == 0;
 
-    u64 *cand = (u64 *)smem;
-    int n_cand = p.b * p.k_b;
-
-    if (!p.use_scratch) {
-        if (!p.stage2) {
-            if (owner) {
-                const int64_t o = (int64_t)r * p.k + (int64_t)col0 * p.k_b;
+    // ---------------------------------------------------------------- where finished lists go
+    u64 *cand = (u64 *)(smem + p.lds_cand_off);
+    const int n_cand = p.b * p.k_b;
+    // Stage-1 result of bucket `col` of this workgroup's share of the row
+    auto emit = [&](int col, const u64(&list)[KB]) {
+        if (p.use_scratch) {
+            // agent-scope atomic stores: written through to memory, not left in this XCD's L2
+            u64 *dst = p.lists + (((int64_t)r * p.S + sp) * p.b + col) * p.k_b;
 #pragma unroll
-                for (int e = 0; e < V; ++e)
+            for (int j = 0; j < KB; ++j)
+                if (j < p.k_b) __hip_atomic_store(&dst[j], list[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if (p.stage2) {
 #pragma unroll
-                    for (int j = 0; j < KB; ++j)
-                        if (j < p.k_b) write_composite<ELT>(comp[e][j], p.out_vals, p.out_idx, o + (int64_t)e * p.k_b + j);
-            }
-            return;
+            for (int j = 0; j < KB; ++j)
+                if (j < p.k_b) cand[col * p.k_b + j] = list[j];
+        } else {
+            const int64_t o = (int64_t)r * p.k + (int64_t)col * p.k_b;
+#pragma unroll
+            for (int j = 0; j < KB; ++j)
+                if (j < p.k_b) write_composite<ELT>(list[j], p.out_vals, p.out_idx, o + j);
         }
-        if (owner) {
+    };
+
+    // ---------------------------------------------------------------- merge across wavefronts (LDS, one barrier)
+    if (p.nparts > 1) {
+        // only reached with one column block (G < T), so the workgroup's columns are 0..b-1
+        u64 *xch = (u64 *)(smem + p.lds_xch_off);  // [part][column][slot]
+        const int lane = tid & (kWave - 1);
+        const int part = p.wave_merge ? (tid >> 6) : ph;
+        const bool holder = active && (!p.wave_merge || lane < p.Gw);
+        if (holder) {
 #pragma unroll
             for (int e = 0; e < V; ++e)
 #pragma unroll
-                for (int j = 0; j < KB; ++j)
-                    if (j < p.k_b) cand[(col0 + e) * p.k_b + j] = comp[e][j];
+                for (int j = 0; j < KB; ++j) xch[((int64_t)part * p.b + col0 + e) * KB + j] = comp[e][j];
         }
         __syncthreads();
-    } else {
-        // ------------------------------------------------------------ partial lists to scratch, ticket
-        // Cross-workgroup hand-over without cache-wide fences: the lists are written and later
-        // read with agent-scope atomic accesses (they go through to memory instead of staying
-        // in this XCD's L2), the barrier waits until this workgroup's stores have been
-        // acknowledged, and only then one lane takes the row's ticket.  Whoever draws the last
-        // ticket knows every other workgroup's lists are complete.
-        if (owner) {
-            u64 *dst = p.lists + (((int64_t)r * p.S + sp) * p.b + col0) * p.k_b;
+        for (int c = tid; c < p.b; c += T) {
+            u64 acc[KB];
 #pragma unroll
-            for (int e = 0; e < V; ++e)
+            for (int j = 0; j < KB; ++j) acc[j] = xch[(int64_t)c * KB + j];
+            for (int q = 1; q < p.nparts; ++q) {
+                u64 theirs[KB];
 #pragma unroll
-                for (int j = 0; j < KB; ++j)
-                    if (j < p.k_b)
-                        __hip_atomic_store(&dst[e * p.k_b + j], comp[e][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int j = 0; j < KB; ++j) theirs[j] = xch[((int64_t)q * p.b + c) * KB + j];
+                merge_topk<KB>(acc, theirs);
+            }
+            emit(c, acc);
         }
+    } else if (active && (!p.wave_merge || (tid & (kWave - 1)) < p.Gw)) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) emit(col0 + e, comp[e]);
+    }
+
+    if (!p.use_scratch) {
+        if (!p.stage2) return;
+        __syncthreads();
+    } else {
+        // ------------------------------------------------------------ ticket
+        // Cross-workgroup hand-over without cache-wide fences: the lists were written, and are
+        // read below, with agent-scope atomic accesses (they go through to memory instead of
+        // staying in one XCD's L2); the barrier waits until this workgroup's stores have been
+        // acknowledged, and only then one lane takes the row's ticket.  Whoever draws the
+        // last ticket knows that every other workgroup's lists are complete.
         if (p.fence_sync) __threadfence();
         __syncthreads();
         uint32_t *flag = (uint32_t *)smem;
         if (tid == 0) {
-            uint32_t ticket = __hip_atomic_fetch_add(&p.tickets[(int64_t)r * kTicketStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t ticket = __hip_atomic_fetch_add(&p.tickets[(int64_t)r * kTicketStride], 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
             flag[0] = (ticket == (uint32_t)(p.S * p.colblocks - 1)) ? 1u : 0u;
         }
         __syncthreads();
-        const bool last = flag[0] != 0;
-        __syncthreads();  // flag word is reused below as candidate storage
-        if (!last) return;
+        if (flag[0] == 0) return;
         if (p.fence_sync) __threadfence();
         if (tid == 0)  // ready for the next call
             __hip_atomic_store(&p.tickets[(int64_t)r * kTicketStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-        // the last workgroup of the row merges the splits of every column
+        // the last workgroup of the row merges the splits of every column; the loads of SU
+        // splits are in flight together
+        constexpr int SU = (KB <= 2) ? 8 : (KB <= 4 ? 4 : 2);
         const u64 *src = p.lists + (int64_t)r * p.S * p.b * p.k_b;
         for (int col = tid; col < p.b; col += T) {
             u64 acc[KB];
 #pragma unroll
-            for (int j = 0; j < KB; ++j) acc[j] = (j < p.k_b) ? __hip_atomic_load(&src[(int64_t)col * p.k_b + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
-            for (int s = 1; s < p.S; ++s) {
-                u64 theirs[KB];
+            for (int j = 0; j < KB; ++j) acc[j] = 0ull;
+            for (int s0 = 0; s0 < p.S; s0 += SU) {
+                u64 th[SU][KB];
 #pragma unroll
-                for (int j = 0; j < KB; ++j)
-                    theirs[j] = (j < p.k_b) ? __hip_atomic_load(&src[((int64_t)s * p.b + col) * p.k_b + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
-                merge_topk<KB>(acc, theirs);
+                for (int u = 0; u < SU; ++u)
+#pragma unroll
+                    for (int j = 0; j < KB; ++j)
+                        th[u][j] = (s0 + u < p.S && j < p.k_b)
+                                       ? __hip_atomic_load(&src[((int64_t)(s0 + u) * p.b + col) * p.k_b + j],
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                       : 0ull;
+#pragma unroll
+                for (int u = 0; u < SU; ++u) merge_topk<KB>(acc, th[u]);
             }
             if (p.stage2) {
 #pragma unroll
@@ -320,18 +352,24 @@ __global__ void __launch_bounds__(kMaxThreads) stage1_kernel(S1Params p) {
     }
 
     // ---------------------------------------------------------------- Stage 2 in LDS
-    u64 *sel = cand + n_cand;
-    int kp = pow2_ceil_dev(p.k);
-    uint32_t *hist = (uint32_t *)(sel + kp);
-    select_sort_write<ELT>(cand, n_cand, p.k, sel, hist, p.out_vals, p.out_idx, (int64_t)r);
+    select_write<ELT>(cand, n_cand, p.k, p.out_vals, p.out_idx, (int64_t)r);
 }
 
 // ------------------------------------------------------------------------------------------------
 template <int ELT, int V, int KB, int U>
 static hipError_t launch_one(const Plan &pl, const S1Params &prm, hipStream_t stream) {
-    hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T), (size_t)pl.lds_bytes,
-                       stream, prm);
+    constexpr int MAXT = max_threads_for_kb(KB);
+    if (pl.T > MAXT) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U, MAXT>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T),
+                       (size_t)pl.lds_bytes, stream, prm);
     return hipGetLastError();
+}
+
+static int log2_exact(int v) {
+    if (v < 1 || (v & (v - 1))) return -1;
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
 }
 
 hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state, void *data,
@@ -356,6 +394,13 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.stage2 = pl.stage2;
     prm.direct = pl.direct;
     prm.use_scratch = pl.use_scratch;
+    prm.wave_merge = pl.wave_merge;
+    prm.nparts = pl.nparts;
+    prm.lds_xch_off = pl.lds_xch_off;
+    prm.lds_cand_off = pl.lds_cand_off;
+    prm.cb_shift = log2_exact(pl.colblocks);
+    prm.s_shift = log2_exact(pl.S);
+    prm.gw_shift = log2_exact(pl.Gw);
     const uintptr_t ov = (uintptr_t)out_vals, oi = (uintptr_t)out_idx;
     prm.vec_store = ((ov | oi) & 15u) == 0;
     {

@@ -139,7 +139,7 @@ def test_shapes(dtype):
         run_case(x, k, b, k_b, tag="shape%d" % i)
 
 
-@pytest.mark.parametrize("plan", ["T=64,S=1", "T=64,S=7", "T=128,S=3", "T=256,S=2", "T=256,S=64"])
+@pytest.mark.parametrize("plan", ["T=64,S=1", "T=64,S=7", "T=128,S=3", "T=256,S=2", "T=256,S=64", "T=512,S=1", "T=1024,S=2", "T=1024,S=5"])
 def test_forced_plans(plan, monkeypatch):
     """The same results whatever the launch geometry (threads per workgroup, row splits)."""
     monkeypatch.setenv("ATK_PLAN", plan)

@@ -58,7 +58,7 @@ OK, NULLP, SHAPE, PARAMS, UNSUP, DTYPE = 0, -1, -2, -3, -4, -5
     ((4, 4096, 64, 64, 1, -1), DTYPE),
     ((4, 4095, 64, 64, 1, 0), UNSUP),       # n not a multiple of b
     ((4, 4096, 64, 2, 32, 0), UNSUP),       # k_b above the register-queue cap
-    ((4, 1 << 16, 64, 1 << 14, 1, 0), UNSUP),  # Stage 2 over more candidates than fit on chip
+    ((4, 1 << 16, 64, 1 << 13, 1, 0), UNSUP),  # Stage 2 over more candidates than fit on chip
 ])
 def test_check_approx(lib, args, code):
     assert lib.atk_check_approx(*args) == code
@@ -98,9 +98,11 @@ def test_plan_shapes(lib):
     # every lane owns whole buckets: straight from registers, one workgroup column block per 1024 columns
     p = parse_plan(atk.plan_describe(128, 65536, 16384, 16384, 1))
     assert p["direct"] == 1 and p["P"] == 1 and p["S"] == 1 and p["colblocks"] == 16 and p["stage2"] == 0
-    # few buckets: lanes share columns (P > 1) and rows are split over workgroups, merged via scratch
+    # few buckets: lanes share columns (P > 1, merged inside the wavefront) and rows are split
+    # over workgroups, merged via scratch
     p = parse_plan(atk.plan_describe(128, 65536, 64, 64, 1))
-    assert p["V"] == 4 and p["Gw"] == 16 and p["P"] == 16 and p["S"] > 1 and p["scratch"] == 1 and p["direct"] == 0
+    assert p["V"] == 4 and p["Gw"] == 16 and p["P"] * p["Gw"] == p["T"] and p["wave_merge"] == 1
+    assert p["S"] > 1 and p["scratch"] == 1 and p["direct"] == 0 and p["nparts"] == p["T"] // 64
     assert p["S"] * p["rows_per_split"] >= 1024 and (p["S"] - 1) * p["rows_per_split"] < 1024
     assert p["rows_per_split"] % p["P"] == 0
     # Stage 2 fused
@@ -108,25 +110,34 @@ def test_plan_shapes(lib):
     assert p["stage2"] == 1 and p["lds"] >= (1024 + 64) * 8
     # bf16 uses 8 columns per lane
     p = parse_plan(atk.plan_describe(2048, 8192, 512, 512, 1, atk.ATK_BF16))
-    assert p["V"] == 8 and p["Gw"] == 64
+    assert p["V"] == 8 and p["Gw"] == 64 and p["wave_merge"] == 0
     # b not a multiple of the vector width: scalar columns
     p = parse_plan(atk.plan_describe(2, 4098, 6, 6, 1))
-    assert p["V"] == 1
-    # the grid always covers every matrix row and column exactly once
-    for (m, n, k, b, kb) in [(1, 4096, 64, 64, 1), (3, 12288, 96, 96, 1), (7, 1 << 20, 64, 8, 8), (128, 1 << 20, 1 << 18, 1 << 15, 8)]:
+    assert p["V"] == 1 and p["wave_merge"] == 0
+    # big register queues keep to 256 lanes
+    p = parse_plan(atk.plan_describe(128, 1 << 20, 64, 8, 8))
+    assert p["KB"] == 8 and p["T"] <= 256
+    # the grid always covers every matrix row and column exactly once, LDS stays within 64 KB
+    for (m, n, k, b, kb) in [(1, 4096, 64, 64, 1), (3, 12288, 96, 96, 1), (7, 1 << 20, 64, 8, 8),
+                             (128, 1 << 20, 1 << 18, 1 << 15, 8), (5, 8192, 1, 1, 1), (4, 16384, 100, 128, 16),
+                             (1, 1 << 18, 64, 512, 1), (130, 4096, 64, 128, 1)]:
         p = parse_plan(atk.plan_describe(m, n, k, b, kb))
         assert p["grid"] == m * p["S"] * p["colblocks"]
         assert p["colblocks"] * p["Gw"] * p["V"] >= b
-        assert p["S"] * p["rows_per_split"] >= n // b
+        assert p["S"] * p["rows_per_split"] >= n // b and (p["S"] - 1) * p["rows_per_split"] < n // b
+        assert p["T"] % 64 == 0 and p["P"] * p["Gw"] <= p["T"] and p["lds"] <= 65536
 
 
 def test_plan_override_env(lib, monkeypatch):
     monkeypatch.setenv("ATK_PLAN", "T=64,S=3")
     p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
     assert p["T"] == 64 and p["S"] == 3
+    monkeypatch.setenv("ATK_PLAN", "T=1024")
+    p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
+    assert p["T"] == 1024
     monkeypatch.delenv("ATK_PLAN")
     q = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
-    assert q["T"] == 256
+    assert q["T"] in (256, 512)
 
 
 def test_workspace_bytes(lib):
