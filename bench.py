@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also time every configuration of the paper's sweeps")
+    ap.add_argument("--probe", action="store_true",
+                    help="short run for hardware-counter passes: 20 copy launches, 20 read-only launches and 20 "
+                         "approx_topk launches per b, nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (rows shard with no exchange); "
@@ -76,6 +79,20 @@ def main():
     def step(i, cold=True):
         for j, b in enumerate(SWEEP_B):
             launch(ring[(i * len(SWEEP_B) + j) % RING] if cold else ring[0], b)
+
+    if args.probe:
+        dst = torch.empty_like(ring[0])
+        sink = torch.zeros(65536 // 8, dtype=torch.int64, device=dev)
+        for i in range(20):
+            lib.atk_copy(dst.data_ptr(), ring[i % RING].data_ptr(), M * N * 4, stream)
+        for i in range(20):
+            lib.atk_read_ceiling(ring[i % RING].data_ptr(), M * N * 4, sink.data_ptr(), stream)
+        for b in SWEEP_B:
+            for i in range(20):
+                launch(ring[i % RING], b)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "done", "copy_bytes": M * N * 4, "launches_each": 20, "b": SWEEP_B}))
+        return
 
     for i in range(args.warmup):
         step(i)
@@ -145,10 +162,16 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                 "kernel": "stage1_kernel<f32,V=4,KB=1>", "avg_launch_us": round(avg_launch_s * 1e6, 3),
                 "read_only_ceiling_GBps": {"cold": round(ceil_cold, 1), "warm": round(ceil_warm, 1)}}
-    traffic_file = os.path.join(ROOT, "profiles", "traffic_stage1_cfg2.json")
+    # HBM bytes per launch come from separate rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE scaled by a
+    # copy kernel of known size); the summary of those passes records the figure.
+    traffic_file = os.path.join(ROOT, "profiles", "stage1_kernel_cfg2_hbm_traffic.md")
     if os.path.exists(traffic_file):
+        import re
+
         with open(traffic_file) as f:
-            roofline["traffic"] = json.load(f).get("bytes_per_launch")
+            hit = re.search(r"^\s*bytes_per_launch:\s*(\d+)", f.read(), flags=re.M)
+        if hit:
+            roofline["traffic"] = int(hit.group(1))
 
     # ---- CPU baseline: the oracle, untouched, on a bounded sample of the same workload
     cpu = None

@@ -113,11 +113,15 @@ int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, i
  *   aligned) of device memory at x; every wave xors what it read into its own word of
  *   `sink`, a device buffer of ATK_CEILING_SINK_BYTES bytes.  It bounds from above what any
  *   single-pass kernel over x can reach.
+ * atk_copy: a plain device-to-device copy kernel of `bytes` bytes (multiple of 16, both pointers
+ *   16-byte aligned, buffers must not overlap).  Its read and write volumes are known exactly,
+ *   which is what hardware traffic counters are scaled against.
  * atk_sleep: a kernel that spins for about `microseconds` (one wave), used to queue work
  *   behind it so that host launch latency stays out of event timings.
  */
 #define ATK_CEILING_SINK_BYTES 65536
 int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream);
+int atk_copy(void *dst, const void *src, int64_t bytes, void *stream);
 int atk_sleep(int64_t microseconds, void *stream);
 
 #ifdef __cplusplus

@@ -62,6 +62,8 @@ def load_library():
     lib.atk_plan_describe.restype = ci
     lib.atk_read_ceiling.argtypes = [vp, i64, vp, vp]
     lib.atk_read_ceiling.restype = ci
+    lib.atk_copy.argtypes = [vp, vp, i64, vp]
+    lib.atk_copy.restype = ci
     lib.atk_sleep.argtypes = [i64, vp]
     lib.atk_sleep.restype = ci
     _lib = lib

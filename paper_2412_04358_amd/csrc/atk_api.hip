@@ -228,6 +228,12 @@ __global__ void __launch_bounds__(256) read_ceiling_kernel(const uint4 *x, int64
     if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = acc;
 }
 
+// plain copy of n_vec 16-byte words: known read and write volume, used to scale hardware counters
+__global__ void __launch_bounds__(256) copy_kernel(const uint4 *src, uint4 *dst, int64_t n_vec) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
+}
+
 __global__ void sleep_kernel(int64_t ticks, u64 *unused) {
     // wall_clock64() counts at a fixed 100 MHz; the loop ends after `ticks` of it.
     const u64 start = wall_clock64();
@@ -359,6 +365,19 @@ int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream) {
     if (wgs > ATK_CEILING_SINK_BYTES / 32) wgs = ATK_CEILING_SINK_BYTES / 32;
     hipLaunchKernelGGL(read_ceiling_kernel, dim3((unsigned)wgs), dim3(256), 0, (hipStream_t)stream, (const uint4 *)x,
                        n_vec, (u64 *)sink);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return ATK_OK;
+}
+
+int atk_copy(void *dst, const void *src, int64_t bytes, void *stream) {
+    if (!dst || !src) return ATK_ERR_NULL_PTR;
+    if (bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15u) || ((uintptr_t)dst & 15u)) return ATK_ERR_ALIGN;
+    const int64_t n_vec = bytes / 16;
+    int64_t wgs = (n_vec + 256 * 4 - 1) / (256 * 4);
+    if (wgs > kNumCU * 16) wgs = kNumCU * 16;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)wgs), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src,
+                       (uint4 *)dst, n_vec);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     return ATK_OK;
