@@ -1,16 +1,47 @@
 // exact_topk: the exact comparison point (Section 1; RadixSelect of Appendix D.2).
-// Small rows: one workgroup per row, the row's composites live in LDS and go through the
+//
+// Small rows: one workgroup per row; the row's composites live in LDS and go through the
 // same radix select + ordering as Stage 2.
+//
+// Long rows: the RadixSelect scheme on the 64-bit composite (value key, then index, so that
+// ties at the k-th value resolve to the lowest indices - the "second collect step" the
+// listing's caption mentions), most significant digit first, 11-bit digits.  One pass =
+// a histogram kernel over the whole row (every workgroup a chunk, LDS histogram flushed to a
+// global one) + a small kernel that picks the digit bucket holding the k-th element.  A row is
+// finished as soon as its bucket holds exactly the number of elements still needed.  Then one
+// more sweep collects every element at or above the threshold, and the k survivors are
+// ordered: in LDS when they fit, else by a least-significant-digit radix sort in global memory.
 #include "atk_common.h"
 #include "atk_select.h"
 
 namespace atk {
 
-static int64_t pow2_ceil64(int64_t v) {
+namespace {
+
+constexpr int kExBins = 2048;            // 11-bit digits
+constexpr int kExPasses = 6;             // 64 bits = 11+11+10 (value key) + 11+11+10 (index field)
+constexpr int kExShift[kExPasses] = {53, 42, 32, 21, 10, 0};
+constexpr int kExWidth[kExPasses] = {11, 11, 10, 11, 11, 10};
+constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps
+constexpr int kSortTile = 2048;          // elements per workgroup of the global sort
+constexpr int kSortLdsMaxK = 4096;       // survivors ordered in LDS by one workgroup
+
+struct ExRowState {  // one per row, 32 bytes
+    u64 prefix;      // decided high bits of the threshold
+    uint32_t need;   // elements still needed inside the current bucket
+    uint32_t done;   // threshold known
+    uint32_t cursor; // survivors written so far
+    uint32_t pad[3];
+};
+
+int64_t pow2_ceil64(int64_t v) {
     int64_t p = 1;
     while (p < v) p <<= 1;
     return p;
 }
+int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
 
 int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     ExactPlan p;
@@ -22,15 +53,33 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.chunks = 1;
     p.scratch_bytes = 0;
     p.state_bytes = 0;
-    int64_t lds = select_lds_bytes(n, (int)pow2_ceil64(k < (1 << 20) ? k : (1 << 20)));
-    p.single_wg = lds <= kLdsBudget;
-    if (!p.single_wg) return ATK_ERR_UNSUPPORTED;
+    p.lds_bytes = 0;
     if (m >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
-    p.lds_bytes = (int)lds;
+    const int64_t lds = select_lds_bytes(n, (int)pow2_ceil64(k < (1 << 20) ? k : (1 << 20)));
+    p.single_wg = lds <= kLdsBudget;
+    if (p.single_wg) {
+        p.lds_bytes = (int)lds;
+        *pl = p;
+        return ATK_OK;
+    }
+    p.chunks = (int)ceil_div64(n, kExChunk);
+    if (m > 65535) return ATK_ERR_UNSUPPORTED;  // rows are the grid's y dimension
+    // state pool: global histograms (left zero by every call)
+    p.state_bytes = m * kExBins * 4;
+    // data pool: row states, survivors, and for the global sort a second buffer + tile histograms
+    int64_t bytes = m * (int64_t)sizeof(ExRowState);
+    bytes = ceil_div64(bytes, 256) * 256;
+    bytes += m * k * 8;
+    if (k > kSortLdsMaxK) {
+        bytes += m * k * 8;
+        bytes += m * ceil_div64(k, kSortTile) * 256 * 4;
+    }
+    p.scratch_bytes = bytes;
     *pl = p;
     return ATK_OK;
 }
 
+// ------------------------------------------------------------------------------------ small rows
 template <int ELT>
 __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x, int n, int k, void *out_vals,
                                                                   int32_t *out_idx) {
@@ -55,17 +104,286 @@ __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x,
     select_write<ELT>(cand, n, k, out_vals, out_idx, (int64_t)r);
 }
 
+// ------------------------------------------------------------------------------------ long rows
+__global__ void ex_init_kernel(ExRowState *st, int m, uint32_t k) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < m) {
+        st[r].prefix = 0ull;
+        st[r].need = k;
+        st[r].done = 0u;
+        st[r].cursor = 0u;
+    }
+}
+
+// Calls f(composite) for every element of this workgroup's chunk of row r, 4 loads per lane in flight.
+template <int ELT, typename F>
+__device__ __forceinline__ void for_chunk(const void *x, int64_t n, int r, int chunk, F f) {
+    const int64_t e0 = (int64_t)chunk * kExChunk;
+    const int64_t e1 = (e0 + kExChunk < n) ? e0 + kExChunk : n;
+    const int T = blockDim.x;
+    auto load_bits = [&](int64_t i) -> uint32_t {
+        if (ELT == ATK_F32) return __builtin_nontemporal_load((const uint32_t *)x + (int64_t)r * n + i);
+        return ((uint32_t)__builtin_nontemporal_load((const uint16_t *)x + (int64_t)r * n + i)) << 16;
+    };
+    int64_t i = e0 + threadIdx.x;
+    for (; i + 3 * T < e1; i += 4 * T) {
+        const uint32_t b0 = load_bits(i), b1 = load_bits(i + T), b2 = load_bits(i + 2 * T), b3 = load_bits(i + 3 * T);
+        f(make_composite(b0, (int32_t)i), true);
+        f(make_composite(b1, (int32_t)(i + T)), true);
+        f(make_composite(b2, (int32_t)(i + 2 * T)), true);
+        f(make_composite(b3, (int32_t)(i + 3 * T)), true);
+    }
+    // the tail keeps whole wavefronts together (f may use wavefront-wide operations)
+    for (; i - threadIdx.x < e1; i += T) {
+        const bool ok = i < e1;
+        f(ok ? make_composite(load_bits(i), (int32_t)i) : 0ull, ok);
+    }
+}
+
+template <int ELT>
+__global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, int64_t n, const ExRowState *st,
+                                                              uint32_t *ghist, int shift, int width) {
+    __shared__ uint32_t lh[kExBins];
+    const int r = blockIdx.y;
+    if (st[r].done) return;  // uniform over the workgroup
+    const u64 prefix = st[r].prefix;
+    const u64 hi_mask = (shift + width >= 64) ? 0ull : (~0ull << (shift + width));
+    const uint32_t dmask = (1u << width) - 1u;
+    for (int i = threadIdx.x; i < kExBins; i += blockDim.x) lh[i] = 0;
+    __syncthreads();
+    for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
+        if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
+    });
+    __syncthreads();
+    uint32_t *gh = ghist + (int64_t)r * kExBins;
+    for (int i = threadIdx.x; i < kExBins; i += blockDim.x) {
+        const uint32_t v = lh[i];
+        if (v) atomicAdd(&gh[i], v);
+    }
+}
+
+// One workgroup (256 lanes) per row: pick the digit bucket that holds the need-th largest
+// element, update the row state, and leave the global histogram zeroed.
+__global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t *ghist, int shift, int last_pass) {
+    __shared__ uint32_t wave_tot[4];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    if (st[r].done) return;
+    uint32_t *gh = ghist + (int64_t)r * kExBins;
+    const uint32_t need = st[r].need;
+    // lane t owns bins 2047-8t-7 .. 2047-8t: lane order is descending bin order
+    uint32_t hb[8], s = 0;
+    const int base = kExBins - 8 - 8 * tid;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        hb[q] = gh[base + q];
+        gh[base + q] = 0;
+        s += hb[q];
+    }
+    const uint32_t incl = wave_incl_scan_u32(s);
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+    __syncthreads();
+    uint32_t above = incl - s;
+    for (int w = 0; w < (tid >> 6); ++w) above += wave_tot[w];
+#pragma unroll
+    for (int q = 7; q >= 0; --q) {
+        const uint32_t with = above + hb[q];
+        if (above < need && with >= need) {
+            const uint32_t left = need - above;
+            st[r].prefix |= (u64)(uint32_t)(base + q) << shift;
+            st[r].need = left;
+            st[r].done = (hb[q] == left || last_pass) ? 1u : 0u;
+        }
+        above = with;
+    }
+}
+
+// Every element at or above the row's threshold goes to sel[row][..] (exactly k of them, any order).
+template <int ELT>
+__global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, int64_t n, ExRowState *st, u64 *sel,
+                                                                 int64_t k) {
+    const int r = blockIdx.y;
+    const u64 thr = st[r].prefix;
+    u64 *dst = sel + (int64_t)r * k;
+    const int lane = threadIdx.x & (kWave - 1);
+    for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
+        const bool keep = ok && c >= thr;
+        const u64 mask = __ballot(keep);
+        if (mask) {  // uniform over the wavefront
+            const int n_keep = __popcll(mask);
+            const int leader = __ffsll((long long)mask) - 1;
+            uint32_t basepos = 0;
+            if (lane == leader) basepos = atomicAdd(&st[r].cursor, (uint32_t)n_keep);
+            basepos = (uint32_t)__builtin_amdgcn_readlane((int)basepos, leader);
+            const uint32_t pos = basepos + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (keep && pos < (uint32_t)k) dst[pos] = c;
+        }
+    });
+}
+
+// k <= kSortLdsMaxK: one workgroup per row orders the survivors in LDS and writes the outputs.
+template <int ELT>
+__global__ void __launch_bounds__(kMaxThreads) ex_order_lds_kernel(const u64 *sel, int k, void *out_vals,
+                                                                   int32_t *out_idx) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    u64 *s = (u64 *)smem;
+    const int kp = pow2_ceil_dev(k);
+    uint32_t *rk = (uint32_t *)(s + kp);
+    const int r = blockIdx.x;
+    for (int i = threadIdx.x; i < k; i += blockDim.x) s[i] = sel[(int64_t)r * k + i];
+    for (int i = threadIdx.x; i < kRankMax; i += blockDim.x) rk[i] = 0;
+    __syncthreads();
+    order_write<ELT>(s, k, rk, out_vals, out_idx, (int64_t)r);
+}
+
+// ---- global least-significant-digit radix sort of the survivors, descending, 8-bit digits ----
+// bin = 255 - digit, so that ascending bins are descending digits.
+__global__ void __launch_bounds__(256) sort_hist_kernel(const u64 *src, int64_t k, int tiles, uint32_t *tile_hist,
+                                                        int shift) {
+    __shared__ uint32_t lh[256];
+    const int r = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+    lh[tid] = 0;
+    __syncthreads();
+    const int64_t e0 = (int64_t)tile * kSortTile;
+    const u64 *row = src + (int64_t)r * k;
+    for (int j = 0; j < kSortTile / 256; ++j) {
+        const int64_t i = e0 + j * 256 + tid;
+        if (i < k) atomicAdd(&lh[255u - ((uint32_t)(row[i] >> shift) & 255u)], 1u);
+    }
+    __syncthreads();
+    tile_hist[((int64_t)r * tiles + tile) * 256 + tid] = lh[tid];
+}
+
+// one workgroup per row: tile_hist[tile][bin] <- number of elements of the row that sort before
+// the first element of (tile, bin): all smaller bins, and the same bin in earlier tiles
+__global__ void __launch_bounds__(256) sort_scan_kernel(uint32_t *tile_hist, int tiles) {
+    __shared__ uint32_t wave_tot[4];
+    const int r = blockIdx.x, tid = threadIdx.x;  // tid = bin
+    uint32_t *th = tile_hist + (int64_t)r * tiles * 256;
+    uint32_t total = 0;
+    for (int t = 0; t < tiles; ++t) total += th[t * 256 + tid];
+    const uint32_t incl = wave_incl_scan_u32(total);
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+    __syncthreads();
+    uint32_t run = incl - total;
+    for (int w = 0; w < (tid >> 6); ++w) run += wave_tot[w];
+    for (int t = 0; t < tiles; ++t) {
+        const uint32_t c = th[t * 256 + tid];
+        th[t * 256 + tid] = run;
+        run += c;
+    }
+}
+
+// stable scatter of one tile: the tile is walked in rounds of 256 consecutive elements; inside a
+// round an element's rank among equal bins is its rank among the lanes of its wavefront with
+// that bin (eight ballots) plus the counts of the lower wavefronts
+__global__ void __launch_bounds__(256) sort_scatter_kernel(const u64 *src, u64 *dst, int64_t k, int tiles,
+                                                           const uint32_t *tile_hist, int shift) {
+    __shared__ uint32_t running[256];
+    __shared__ uint32_t wcnt[4][256];
+    const int r = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    running[tid] = tile_hist[((int64_t)r * tiles + tile) * 256 + tid];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
+    __syncthreads();
+    const int64_t e0 = (int64_t)tile * kSortTile;
+    const u64 *row = src + (int64_t)r * k;
+    u64 *orow = dst + (int64_t)r * k;
+    for (int j = 0; j < kSortTile / 256; ++j) {
+        const int64_t i = e0 + j * 256 + tid;
+        const bool ok = i < k;
+        const u64 c = ok ? row[i] : 0ull;
+        const uint32_t bin = 255u - ((uint32_t)(c >> shift) & 255u);
+        // lanes of this wavefront with the same bin (and a valid element)
+        u64 peers = __ballot(ok);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const u64 vote = __ballot((bin >> bit) & 1u);
+            peers &= ((bin >> bit) & 1u) ? vote : ~vote;
+        }
+        const uint32_t rank_in_wave =
+            __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
+        if (ok && rank_in_wave == 0) wcnt[wave][bin] = (uint32_t)__popcll(peers);
+        __syncthreads();
+        if (ok) {
+            uint32_t pos = running[bin] + rank_in_wave;
+            for (int w = 0; w < wave; ++w) pos += wcnt[w][bin];
+            orow[pos] = c;
+        }
+        __syncthreads();
+        running[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
+        __syncthreads();
+    }
+}
+
+template <int ELT>
+__global__ void __launch_bounds__(256) ex_decode_kernel(const u64 *sorted, int64_t total, void *out_vals,
+                                                        int32_t *out_idx) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < total) write_composite<ELT>(sorted[i], out_vals, out_idx, i);
+}
+
+template <int ELT>
+static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state,
+                                 void *data, hipStream_t stream) {
+    const int64_t m = pl.m, n = pl.n, k = pl.k;
+    if (pl.single_wg) {
+        hipLaunchKernelGGL(exact_small_kernel<ELT>, dim3((unsigned)m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x, (int)n,
+                           (int)k, out_vals, out_idx);
+        return hipGetLastError();
+    }
+    uint32_t *ghist = (uint32_t *)state;
+    ExRowState *st = (ExRowState *)data;
+    const int64_t st_bytes = ceil_div64(m * (int64_t)sizeof(ExRowState), 256) * 256;
+    u64 *sel = (u64 *)((unsigned char *)data + st_bytes);
+    const dim3 sweep((unsigned)pl.chunks, (unsigned)m);
+
+    hipLaunchKernelGGL(ex_init_kernel, dim3((unsigned)ceil_div64(m, 256)), dim3(256), 0, stream, st, (int)m, (uint32_t)k);
+    for (int p = 0; p < kExPasses; ++p) {
+        hipLaunchKernelGGL(ex_hist_kernel<ELT>, sweep, dim3(kMaxThreads), 0, stream, x, n, st, ghist, kExShift[p],
+                           kExWidth[p]);
+        hipLaunchKernelGGL(ex_decide_kernel, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p],
+                           p == kExPasses - 1 ? 1 : 0);
+    }
+    hipLaunchKernelGGL(ex_collect_kernel<ELT>, sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    if (k <= kSortLdsMaxK) {
+        const size_t lds = (size_t)pow2_ceil64(k) * 8 + kRankMax * 4;
+        hipLaunchKernelGGL(ex_order_lds_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), lds, stream, sel, (int)k,
+                           out_vals, out_idx);
+        return hipGetLastError();
+    }
+    // global sort: digits that are the same for every element (high bits of the index field) are skipped
+    u64 *bufs[2] = {sel, sel + m * k};
+    uint32_t *tile_hist = (uint32_t *)(bufs[1] + m * k);
+    const int tiles = (int)ceil_div64(k, kSortTile);
+    int idx_bits = 1;  // the index field holds 0x7fffffff - idx in bits [31:1]; bit 0 is the zero-sign flag
+    while (((int64_t)1 << idx_bits) < n) ++idx_bits;
+    int cur = 0;
+    for (int shift = 0; shift < 64; shift += 8) {
+        if (shift < 32 && shift >= idx_bits + 1) continue;
+        const dim3 grid((unsigned)tiles, (unsigned)m);
+        hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(256), 0, stream, bufs[cur], k, tiles, tile_hist, shift);
+        hipLaunchKernelGGL(sort_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, tile_hist, tiles);
+        hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], k, tiles, tile_hist,
+                           shift);
+        cur ^= 1;
+    }
+    const int64_t total = m * k;
+    hipLaunchKernelGGL(ex_decode_kernel<ELT>, dim3((unsigned)ceil_div64(total, 256)), dim3(256), 0, stream, bufs[cur], total,
+                       out_vals, out_idx);
+    return hipGetLastError();
+}
+
 hipError_t launch_exact(const ExactPlan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state,
                         void *data, hipStream_t stream) {
-    (void)state;
-    (void)data;
-    if (pl.dtype == ATK_F32)
-        hipLaunchKernelGGL(exact_small_kernel<ATK_F32>, dim3((unsigned)pl.m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x,
-                           (int)pl.n, (int)pl.k, out_vals, out_idx);
-    else
-        hipLaunchKernelGGL(exact_small_kernel<ATK_BF16>, dim3((unsigned)pl.m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x,
-                           (int)pl.n, (int)pl.k, out_vals, out_idx);
-    return hipGetLastError();
+    if (pl.dtype == ATK_F32) return launch_exact_t<ATK_F32>(pl, x, out_vals, out_idx, state, data, stream);
+    return launch_exact_t<ATK_BF16>(pl, x, out_vals, out_idx, state, data, stream);
 }
 
 }  // namespace atk

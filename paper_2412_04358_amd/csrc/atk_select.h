@@ -97,6 +97,61 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
     return v;
 }
 
+// Writes the k distinct composites sel[0..k) (LDS, any order) to row `row_out`, largest first.
+// sel has room for pow2_ceil(k) words; rk: LDS, kRankMax zeroed words (used when k <= kRankMax).
+// All threads of the workgroup call it, after a barrier that made sel (and the zeroed rk) visible.
+template <int ELT>
+__device__ void order_write(u64 *sel, int k, uint32_t *rk, void *out_vals, int32_t *out_idx, int64_t row_out) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int kp = pow2_ceil_dev(k);
+    if (k <= kRankMax) {
+        // rank = number of larger survivors; iw lanes side by side take one survivor each and
+        // the T/iw groups of lanes split the range of partners
+        int iw = kWave, iw_shift = 6;
+        while (iw < k && iw < T) {
+            iw <<= 1;
+            ++iw_shift;
+        }
+        const int parts = T >> iw_shift;
+        if (parts == 1) {
+            for (int i = tid; i < k; i += iw)
+                write_composite<ELT>(sel[i], out_vals, out_idx, row_out * k + count_larger(sel, 0, k, sel[i]));
+            return;
+        }
+        const int chunk = (k + parts - 1) / parts;
+        const int part = tid >> iw_shift;
+        const int j0 = part * chunk, j1 = min(k, j0 + chunk);
+        const int i = tid & (iw - 1);
+        if (i < k && j0 < j1) {
+            const int r = count_larger(sel, j0, j1, sel[i]);
+            if (r) atomicAdd(&rk[i], (uint32_t)r);
+        }
+        __syncthreads();
+        for (int q = tid; q < k; q += T) write_composite<ELT>(sel[q], out_vals, out_idx, row_out * k + (int)rk[q]);
+    } else {
+        for (int i = k + tid; i < kp; i += T) sel[i] = 0;  // empties sort to the end
+        __syncthreads();
+        for (int size = 2; size <= kp; size <<= 1) {
+            for (int stride = size >> 1; stride >= 1; stride >>= 1) {
+                for (int i = tid; i < (kp >> 1); i += T) {
+                    const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));
+                    const int hi = lo + stride;
+                    const bool desc = (lo & size) == 0;
+                    const u64 a = sel[lo], c = sel[hi];
+                    const bool sw = desc ? (c > a) : (c < a);
+                    if (sw) {
+                        sel[lo] = c;
+                        sel[hi] = a;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        for (int i = tid; i < k; i += T) write_composite<ELT>(sel[i], out_vals, out_idx, row_out * k + i);
+    }
+}
+
+
 // Exact top-k of the `count` distinct composites at cand[0..count) (LDS), written largest
 // first to row `row_out` (row stride k).  `cand` must be followed by
 // select_lds_bytes(count, pow2_ceil(k)) - count*8 bytes of free LDS.  All threads of the
@@ -204,52 +259,7 @@ __device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_
     }
     __syncthreads();
 
-    // ---- order the k survivors, largest first
-    if (k <= kRankMax) {
-        // rank = number of larger survivors; iw lanes side by side take one survivor each and
-        // the T/iw groups of lanes split the range of partners
-        int iw = kWave, iw_shift = 6;
-        while (iw < k && iw < T) {
-            iw <<= 1;
-            ++iw_shift;
-        }
-        const int parts = T >> iw_shift;
-        if (parts == 1) {
-            for (int i = tid; i < k; i += iw)
-                write_composite<ELT>(sel[i], out_vals, out_idx, row_out * k + count_larger(sel, 0, k, sel[i]));
-            return;
-        }
-        const int chunk = (k + parts - 1) / parts;
-        const int part = tid >> iw_shift;
-        const int j0 = part * chunk, j1 = min(k, j0 + chunk);
-        const int i = tid & (iw - 1);
-        if (i < k && j0 < j1) {
-            const int r = count_larger(sel, j0, j1, sel[i]);
-            if (r) atomicAdd(&rk[i], (uint32_t)r);
-        }
-        __syncthreads();
-        for (int q = tid; q < k; q += T) write_composite<ELT>(sel[q], out_vals, out_idx, row_out * k + (int)rk[q]);
-    } else {
-        for (int i = k + tid; i < kp; i += T) sel[i] = 0;  // empties sort to the end
-        __syncthreads();
-        for (int size = 2; size <= kp; size <<= 1) {
-            for (int stride = size >> 1; stride >= 1; stride >>= 1) {
-                for (int i = tid; i < (kp >> 1); i += T) {
-                    const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));
-                    const int hi = lo + stride;
-                    const bool desc = (lo & size) == 0;
-                    const u64 a = sel[lo], c = sel[hi];
-                    const bool sw = desc ? (c > a) : (c < a);
-                    if (sw) {
-                        sel[lo] = c;
-                        sel[hi] = a;
-                    }
-                }
-                __syncthreads();
-            }
-        }
-        for (int i = tid; i < k; i += T) write_composite<ELT>(sel[i], out_vals, out_idx, row_out * k + i);
-    }
+    order_write<ELT>(sel, k, rk, out_vals, out_idx, row_out);
 }
 
 #endif  // __HIPCC__

@@ -190,6 +190,25 @@ def test_exact_small_rows(dtype):
         run_exact(workloads.special_values(m, n, seed=302 + n, dtype=dtype), k)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_long_rows(dtype):
+    """Rows that do not fit one workgroup: global radix select, then LDS or global ordering."""
+    for m, n, k in [(3, 20000, 64), (2, 50000, 1), (2, 50000, 3000), (2, 100000, 5000), (1, 70001, 70001),
+                    (2, 300000, 40000)]:
+        run_exact(workloads.normal_rows(m, n, seed=400 + n % 97, dtype=dtype), k)
+    # ties at the threshold: the index decides (index digits of the radix select)
+    run_exact(workloads.few_levels(3, 30000, levels=2, seed=5, dtype=dtype), 777)
+    run_exact(workloads.few_levels(2, 30000, levels=1, seed=6, dtype=dtype), 9000)
+    run_exact(workloads.special_values(2, 40000, seed=7, dtype=dtype), 6000)
+
+
+def test_exact_cfg4():
+    x = workloads.config_input("cfg4")
+    rows = [0, 1, 64, 127]
+    run_exact(x, 64, rows=rows)
+    run_exact(x, 1 << 18, rows=rows)
+
+
 def test_b1_equals_exact():
     x = workloads.normal_rows(3, 4096, seed=9)
     xg = x.cuda()
