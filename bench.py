@@ -258,6 +258,24 @@ def detail(atk, workloads, torch, dev):
             res["%s k=%d b=%d k_b=%d" % (name, k, b, k_b)] = {
                 "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
                 "plan": atk.plan_describe(m, n, k, b, k_b, dt)}
+        if name == "cfg4":
+            # the exact comparison point on the same rows (Section 4.1 compares against exact top-k)
+            for k in (64, 1 << 18):
+                ov = torch.empty((m, k), dtype=ring[0].dtype, device=dev)
+                oi = torch.empty((m, k), dtype=torch.int32, device=dev)
+                for i in range(2):
+                    assert atk.exact_topk_raw(ring[0].data_ptr(), m, n, k, dt, ov.data_ptr(), oi.data_ptr(), stream) == 0
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(10):
+                    atk.exact_topk_raw(ring[0].data_ptr(), m, n, k, dt, ov.data_ptr(), oi.data_ptr(), stream)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 10
+                nbytes = m * n * es + m * k * (es + 4)
+                res["cfg4 exact_topk k=%d" % k] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                                                   "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4), "plan": "exact"}
         del ring
         torch.cuda.empty_cache()
     return res
