@@ -65,8 +65,11 @@ enum {
  *   out_vals  device, m x k, element type `dtype`.
  *   out_idx   device, m x k int32 column indices (0-based, within the row).
  *
- * ATK_ERR_UNSUPPORTED: n not a multiple of b; k_b > ATK_MAX_KB; a Stage 2 whose
- * b*k_b candidates exceed the on-chip limit reported by atk_stage2_max_candidates().
+ * n need not be a multiple of b: bucket j holds the indices j, j+b, ... below n (the short
+ * buckets of Figure 2); k_b <= floor(n/b) keeps every bucket long enough.
+ *
+ * ATK_ERR_UNSUPPORTED: k_b > ATK_MAX_KB; a Stage 2 whose b*k_b candidates exceed the
+ * on-chip limit reported by atk_stage2_max_candidates().
  */
 int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
                 void *out_vals, int32_t *out_idx, void *stream);

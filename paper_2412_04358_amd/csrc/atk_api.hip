@@ -41,7 +41,6 @@ static int check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b,
     if (b < 1 || b > n || k_b < 1) return ATK_ERR_BAD_PARAMS;
     if (k_b > k || k_b > n / b) return ATK_ERR_BAD_PARAMS;
     if (b * k_b < k) return ATK_ERR_BAD_PARAMS;
-    if (n % b != 0) return ATK_ERR_UNSUPPORTED;
     if (k_b > ATK_MAX_KB) return ATK_ERR_UNSUPPORTED;
     return ATK_OK;
 }
@@ -81,7 +80,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         vmax = (p.KB <= 8) ? 4 : 2;
     else
         vmax = (p.KB <= 4) ? 8 : (p.KB == 8 ? 4 : 2);
-    p.V = (ptr16 && b % vmax == 0) ? vmax : 1;
+    // vector loads need every matrix row to start on a 16-byte boundary
+    p.V = (ptr16 && b % vmax == 0 && n % vmax == 0) ? vmax : 1;
     p.G = b / p.V;
     p.L = n / b;
     p.stage2 = b * k_b > k;
@@ -99,8 +99,14 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (want_threads > 2048 * (int64_t)kNumCU) want_threads = 2048 * (int64_t)kNumCU;
     int T = 256;
     if (p.G <= 256) {
-        T = t_max < 512 ? t_max : 512;
-        while (T > 256 && m * T * 2 > want_threads) T >>= 1;  // keep at least two splits' worth of lanes
+        const int t_cols = (int)(ceil_div(p.G, kWave) * kWave);  // lanes that give every column group one lane
+        if (m * t_cols * 2 >= want_threads) {
+            // enough rows to fill the chip with one lane per column group: no merging at all
+            T = t_cols;
+        } else {
+            T = t_max < 512 ? t_max : 512;
+            while (T > 256 && m * T * 2 > want_threads) T >>= 1;  // keep at least two splits' worth of lanes
+        }
     }
     if (T_forced) T = T_forced;
     if (T > t_max) T = t_max;

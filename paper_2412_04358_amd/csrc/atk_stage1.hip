@@ -28,6 +28,7 @@ struct S1Params {
     uint32_t *tickets;   // scratch: one counter per row (kTicketStride words apart), zero between calls
     int64_t n;
     int b, L, G, Gw, P, colblocks, S, rows_per_split;
+    int rem, extra_ph;   // n mod b, and the row phase that takes the ragged last matrix row
     int k, k_b;
     int stage2, direct, use_scratch, vec_store;
     int wave_merge;      // Gw < 64 and a power of two: lanes of one wavefront share columns
@@ -109,6 +110,25 @@ __device__ __forceinline__ void insert(float (&val)[KB], int (&tt)[KB], float v,
     tt[0] = c[0] ? t : tt[0];
 }
 
+// Feed the V elements of one load into the lane's V queues.  With k_b > 1 the insertion costs
+// about 5*k_b lane operations per element, so it is skipped whenever no lane of the wavefront
+// holds an element that beats the last slot of its queue (one compare per element and a
+// wavefront-uniform branch): on long buckets almost every load is rejected that way.
+template <int ELT, int V, int KB>
+__device__ __forceinline__ void scan_vec(float (&val)[V][KB], int (&tt)[V][KB], const RowVec<ELT, V> &v, int t) {
+    float x[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) x[e] = __uint_as_float(elem_bits<ELT, V>(v, e));
+    if (KB > 1) {
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < V; ++e) any = any || !(x[e] <= val[e][KB - 1]);
+        if (__ballot(any) == 0ull) return;
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) insert<KB>(val[e], tt[e], x[e], t);
+}
+
 template <int ELT, int V, int KB, int U, int MAXT>
 __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -145,15 +165,27 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 #pragma unroll
             for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int e = 0; e < V; ++e)
-                    insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, V>(v[u], e)), t + u * step);
+            for (int u = 0; u < U; ++u) scan_vec<ELT, V, KB>(val, tt, v[u], t + u * step);
         }
         for (; t < t1; t += step) {
             RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)t * row_bytes);
+            scan_vec<ELT, V, KB>(val, tt, v, t);
+        }
+        // n not a multiple of b: the last matrix row holds only the first `rem` columns (the
+        // short buckets of Figure 2).  It has the highest indices, so it is fed last.
+        if (p.rem > 0 && sp == p.S - 1 && ph == p.extra_ph && col0 < p.rem) {
+            const unsigned char *last = base + (int64_t)p.L * row_bytes;
+            if (col0 + V <= p.rem) {
+                RowVec<ELT, V> v = load_vec<ELT, V>(last);
+                scan_vec<ELT, V, KB>(val, tt, v, p.L);
+            } else {
 #pragma unroll
-            for (int e = 0; e < V; ++e) insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, V>(v, e)), t);
+                for (int e = 0; e < V; ++e)
+                    if (col0 + e < p.rem) {
+                        RowVec<ELT, 1> one = load_vec<ELT, 1>(last + e * ES);
+                        insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, 1>(one, 0)), p.L);
+                    }
+            }
         }
     }
 
@@ -389,6 +421,8 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.colblocks = pl.colblocks;
     prm.S = pl.S;
     prm.rows_per_split = pl.rows_per_split;
+    prm.rem = (int)(pl.n % pl.b);
+    prm.extra_ph = (int)(pl.L % pl.P);
     prm.k = (int)pl.k;
     prm.k_b = pl.k_b;
     prm.stage2 = pl.stage2;

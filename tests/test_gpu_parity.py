@@ -129,6 +129,18 @@ SHAPES = [
     (1, 1 << 18, 64, 64, 1),      # one long row: many row splits
     (1, 1 << 18, 64, 512, 1),
     (1, 1 << 18, 256, 32, 8),
+    # n not a multiple of b: short buckets (Figure 2), vector and scalar columns
+    (3, 4100, 64, 64, 1),         # remainder 4: one whole vector of the ragged row
+    (3, 4102, 64, 64, 1),         # n % 4 != 0: scalar columns
+    (3, 4136, 48, 64, 1),         # remainder 40, n % 8 == 0, Stage 2
+    (2, 20000, 192, 96, 2),       # remainder 32
+    (2, 20004, 100, 96, 3),       # remainder 36 with Stage 2, k_b not a power of two
+    (5, 1000, 30, 30, 1),         # small odd shapes
+    (5, 1001, 45, 15, 3),
+    (2, 70001, 250, 250, 1),      # b > 64 column groups, scalar
+    (2, 66000, 512, 128, 4),      # remainder 80 of 128 columns: partial vectors
+    (1, 128256, 256, 512, 1),     # vocabulary-sized row, b*k_b/k = 2
+    (1, 128256, 256, 1000, 2),    # b does not divide n
 ]
 
 

@@ -56,7 +56,8 @@ OK, NULLP, SHAPE, PARAMS, UNSUP, DTYPE = 0, -1, -2, -3, -4, -5
     ((4, 4096, 4096, 2048, 4, 0), PARAMS),  # k_b > n/b
     ((4, 4096, 64, 64, 1, 2), DTYPE),
     ((4, 4096, 64, 64, 1, -1), DTYPE),
-    ((4, 4095, 64, 64, 1, 0), UNSUP),       # n not a multiple of b
+    ((4, 4095, 64, 64, 1, 0), OK),          # n not a multiple of b: short buckets
+    ((4, 4095, 64, 64, 64, 0), PARAMS),     # k_b above floor(n/b)
     ((4, 4096, 64, 2, 32, 0), UNSUP),       # k_b above the register-queue cap
     ((4, 1 << 16, 64, 1 << 13, 1, 0), UNSUP),  # Stage 2 over more candidates than fit on chip
 ])
