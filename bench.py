@@ -224,12 +224,14 @@ def detail(atk, workloads, torch, dev):
     """Every configuration of the other sweeps: us per launch (cold where a ring fits), GB/s."""
     res = {}
     stream = torch.cuda.current_stream().cuda_stream
-    for name in ["cfg3", "cfg4", "cfg5"]:
+    for name in ["cfg3", "cfg4", "cfg5", "vocab", "kg"]:
         c = workloads.CONFIGS[name]
         m, n = c["m"], c["n"]
         es = 4 if c["dtype"] == "f32" else 2
         dt = atk.ATK_F32 if c["dtype"] == "f32" else atk.ATK_BF16
-        nring = 1 if name == "cfg4" else 10  # 537 MB rows are cold by size
+        nring = 1 if name in ("cfg4", "kg") else 10  # 537 MB / 679 MB inputs are cold by size
+        if name == "vocab":
+            nring = 20  # 16 MB each
         if name == "cfg5":
             ring = [workloads.attention_scores(seed=s).to(dev) for s in range(nring)]
         else:
@@ -243,7 +245,7 @@ def detail(atk, workloads, torch, dev):
                                          stream)
                 assert rc == 0, atk.strerror(rc)
 
-            reps = 50 if name == "cfg4" else 200
+            reps = 50 if name in ("cfg4", "kg") else 200
             for i in range(5):
                 launch(i)
             torch.cuda.synchronize()

@@ -153,6 +153,14 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
 
     p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
     p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
+    if (p.use_scratch && p.stage2) {
+        // the candidates are gathered by the last workgroup of the row, after its exchange area
+        // is dead, so the two share LDS (without splits emit() fills one while the other is read)
+        const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * b * p.KB * 8 : 0;
+        const int64_t lds_s2 = select_lds_bytes(b * k_b, (int)pow2_ceil(k));
+        p.lds_cand_off = 16;
+        p.lds_bytes = (int)(16 + (lds_xch > lds_s2 ? lds_xch : lds_s2));
+    }
 
     p.scratch_ticket_bytes = p.use_scratch ? m * kTicketStride * 4 : 0;
     p.scratch_lists_bytes = p.use_scratch ? m * p.S * b * k_b * 8 : 0;

@@ -30,6 +30,13 @@ CONFIGS = {
                  cases=[(64, 64, 1), (64, 1024, 1), (64, 8, 8), (64, 128, 8),
                         (1 << 18, 1 << 18, 1), (1 << 18, 1 << 15, 8)]),
     "cfg5": dict(m=2048, n=8192, dtype="bf16", seed=0, cases=[(512, 512, 1)]),
+    # Shapes of the paper's two small-k downstream tasks (Section 4.2, Figure 4), as synthetic
+    # stand-ins: the Llama 3 logits and the PharMeBINet scores themselves are not available.
+    # n is not a power of two and most b do not divide it.
+    "vocab": dict(m=64, n=128256, dtype="bf16", seed=0,
+                  cases=[(256, 256, 1), (256, 512, 1), (256, 1024, 1), (256, 256, 2), (256, 512, 2)]),
+    "kg": dict(m=128, n=2653751, dtype="bf16", seed=0,
+               cases=[(100, 100, 1), (100, 256, 1), (100, 1024, 1), (100, 128, 2), (100, 512, 2)]),
 }
 
 

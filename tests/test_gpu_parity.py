@@ -100,6 +100,19 @@ def test_cfg5_attention_scores_bf16():
         run_case(x, k, b, k_b, tag="cfg5")
 
 
+def test_vocab_shape_bf16():
+    x = workloads.config_input("vocab")
+    for k, b, k_b in workloads.CONFIGS["vocab"]["cases"]:
+        run_case(x, k, b, k_b, tag="vocab")
+
+
+def test_kg_shape_bf16():
+    x = workloads.config_input("kg")
+    rows = [0, 1, 77, 127]
+    for k, b, k_b in workloads.CONFIGS["kg"]["cases"]:
+        run_case(x, k, b, k_b, rows=rows, tag="kg")
+
+
 # ------------------------------------------------------------------------------- shapes spanning tiles and tails
 SHAPES = [
     # (m, n, k, b, k_b)
