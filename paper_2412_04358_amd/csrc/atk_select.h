@@ -6,7 +6,9 @@
 // and an LDS histogram.  Two departures: the descent starts at the highest bit in which
 // the candidates differ at all (their common leading bits cannot separate anything), and,
 // because composites are distinct, it stops as soon as the chosen digit bucket holds
-// exactly the number of elements still needed.
+// exactly the number of elements still needed.  When few candidates per lane remain and they
+// spread well over their range, a single histogram pass plus exact in-bin ranking replaces
+// the descent, the compaction and the ordering altogether (select_write).
 #pragma once
 
 #include "atk_common.h"
@@ -26,8 +28,14 @@ __device__ __forceinline__ int pow2_ceil_dev(int v) { return pow2_ceil_c(v); }
 constexpr int kRankMax = 256;                 // largest k ordered by all-pairs ranking (else bitonic sort)
 constexpr int kSelWredWords = 32;             // u64: per-wavefront OR / AND
 constexpr int kSelU32Words = 512 + 8 + 8 + kRankMax;  // two histograms, scan result, cursor, ranks
+constexpr int kBkBins = 2048;                 // bucket-rank path: bins over the candidates' range
+constexpr int kBkBinMax = 32;                 // fullest bin it accepts
+constexpr int kBkSlots = 4;                   // candidates per lane it holds in registers
+constexpr int kBkU32Words = kBkBins + (kBkBins + 8) + 32;  // counts, offsets (+sentinel), flag and wavefront totals
 __host__ __device__ constexpr int64_t select_lds_bytes(int64_t count, int kp) {
-    return (count + kp + kSelWredWords) * 8 + kSelU32Words * 4;
+    const int64_t radix = (int64_t)(kp + kSelWredWords) * 8 + kSelU32Words * 4;
+    const int64_t bucket = 16 + (int64_t)kBkU32Words * 4;
+    return count * 8 + (radix > bucket ? radix : bucket);
 }
 
 // Decode a composite and store it as output element `pos` (absolute element offset).
@@ -81,6 +89,51 @@ __device__ __forceinline__ void wave_or_and_u64(u64 &o, u64 &a) {
     o = readlane_u64(o, 0) | readlane_u64(o, 16) | readlane_u64(o, 32) | readlane_u64(o, 48);
     a = readlane_u64(a, 0) & readlane_u64(a, 16) & readlane_u64(a, 32) & readlane_u64(a, 48);
 }
+// Minimum and maximum over the 64 lanes of a fully active wavefront (result in every lane).
+__device__ __forceinline__ void wave_min_max_u64(u64 &lo, u64 &hi) {
+    u64 t;
+    t = dpp_u64<0xB1>(lo);  lo = t < lo ? t : lo;
+    t = dpp_u64<0xB1>(hi);  hi = t > hi ? t : hi;
+    t = dpp_u64<0x4E>(lo);  lo = t < lo ? t : lo;
+    t = dpp_u64<0x4E>(hi);  hi = t > hi ? t : hi;
+    t = dpp_u64<0x141>(lo); lo = t < lo ? t : lo;
+    t = dpp_u64<0x141>(hi); hi = t > hi ? t : hi;
+    t = dpp_u64<0x140>(lo); lo = t < lo ? t : lo;
+    t = dpp_u64<0x140>(hi); hi = t > hi ? t : hi;
+    u64 a = readlane_u64(lo, 0), b = readlane_u64(lo, 16), c = readlane_u64(lo, 32), d = readlane_u64(lo, 48);
+    a = a < b ? a : b;
+    c = c < d ? c : d;
+    lo = a < c ? a : c;
+    a = readlane_u64(hi, 0), b = readlane_u64(hi, 16), c = readlane_u64(hi, 32), d = readlane_u64(hi, 48);
+    a = a > b ? a : b;
+    c = c > d ? c : d;
+    hi = a > c ? a : c;
+}
+
+// Minimum / maximum of a 32-bit value over the 64 lanes of a fully active wavefront.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, dpp_u32<0xB1>(v));
+    v = min(v, dpp_u32<0x4E>(v));
+    v = min(v, dpp_u32<0x141>(v));
+    v = min(v, dpp_u32<0x140>(v));
+    const uint32_t a = min((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16));
+    const uint32_t b = min((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48));
+    return min(a, b);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, dpp_u32<0xB1>(v));
+    v = max(v, dpp_u32<0x4E>(v));
+    v = max(v, dpp_u32<0x141>(v));
+    v = max(v, dpp_u32<0x140>(v));
+    const uint32_t a = max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16));
+    const uint32_t b = max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48));
+    return max(a, b);
+}
+
 // Lanes without a source (row edge) or outside ROW_MASK receive 0.
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint32_t dpp_zero_fill(uint32_t v) {
@@ -152,12 +205,11 @@ __device__ void order_write(u64 *sel, int k, uint32_t *rk, void *out_vals, int32
 }
 
 
-// Exact top-k of the `count` distinct composites at cand[0..count) (LDS), written largest
-// first to row `row_out` (row stride k).  `cand` must be followed by
-// select_lds_bytes(count, pow2_ceil(k)) - count*8 bytes of free LDS.  All threads of the
-// workgroup call it; blockDim.x is a multiple of 64.
+// Radix-descent selection: exact top-k of the `count` distinct composites at cand[0..count)
+// (LDS), written largest first to row `row_out`.  Needs (pow2_ceil(k) + kSelWredWords) * 8 +
+// kSelU32Words * 4 bytes of LDS behind cand.
 template <int ELT>
-__device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_t *out_idx, int64_t row_out) {
+__device__ void select_radix_write(u64 *cand, int count, int k, void *out_vals, int32_t *out_idx, int64_t row_out) {
     const int tid = threadIdx.x, T = blockDim.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6, n_waves = T >> 6;
     const int kp = pow2_ceil_dev(k);
@@ -260,6 +312,148 @@ __device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_
     __syncthreads();
 
     order_write<ELT>(sel, k, rk, out_vals, out_idx, row_out);
+}
+
+// Exact top-k of the `count` distinct composites at cand[0..count) (LDS), written largest
+// first to row `row_out` (row stride k).  `cand` must be followed by
+// select_lds_bytes(count, pow2_ceil(k)) - count*8 bytes of free LDS.  All threads of the
+// workgroup call it, after a barrier that made cand visible; blockDim.x is a multiple of 64.
+//
+// Fast path ("bucket rank", at most kBkSlots candidates per lane): the candidates move into
+// registers; one histogram over 2048 bins that are linear in (composite - minimum); a
+// descending prefix sum over the bins; then every candidate that can still be among the k
+// largest is filed into its bin's segment (in place of cand) and finds its exact rank as
+// (elements in higher bins) + (larger elements of its own bin), which is its output slot.
+// No digit-by-digit descent, no compaction, no separate ordering.  If some bin is too full
+// for the in-bin count to stay cheap (heavy ties, values clustered far below the maximum)
+// the radix descent takes over.
+template <int ELT>
+__device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_t *out_idx, int64_t row_out) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    if (count > kBkSlots * T || T > kBkBins) {
+        select_radix_write<ELT>(cand, count, k, out_vals, out_idx, row_out);
+        return;
+    }
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const int lane = tid & (kWave - 1), n_waves = T >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // LDS behind the candidates (16-byte aligned pieces): counts, "above" table, small words
+    uint32_t *cnt = (uint32_t *)(((uintptr_t)(cand + count) + 15) & ~(uintptr_t)15);  // [2048]
+    uint32_t *abv = cnt + kBkBins;   // abv[b + 4] = elements in bins above b, for b = -1 .. 2047
+    uint32_t *misc = abv + kBkBins + 8;  // [0] overflow flag, [1] min key, [2] max key, [8..24) wavefront totals
+
+    // ---- candidates into registers (0 = none); clear the counts
+    u64 c[kBkSlots];
+    uint32_t k_min = 0xffffffffu, k_max = 0u;
+#pragma unroll
+    for (int e = 0; e < kBkSlots; ++e) {
+        const int i = tid + e * T;
+        c[e] = (i < count) ? cand[i] : 0ull;
+    }
+    {
+        const v4u zero = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < kBkBins / 4; i += T) ((v4u *)cnt)[i] = zero;
+        if (tid == 0) {
+            misc[0] = 0u;
+            misc[1] = 0xffffffffu;
+            misc[2] = 0u;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < kBkSlots; ++e)
+        if (c[e]) {
+            const uint32_t key = (uint32_t)(c[e] >> 32);
+            k_min = key < k_min ? key : k_min;
+            k_max = key > k_max ? key : k_max;
+        }
+    __syncthreads();
+    // ---- range of the value keys: fold inside the wavefront, one LDS atomic pair per wavefront
+    k_min = wave_min_u32(k_min);
+    k_max = wave_max_u32(k_max);
+    if (lane == 0) {
+        atomicMin(&misc[1], k_min);
+        atomicMax(&misc[2], k_max);
+    }
+    __syncthreads();
+    k_min = misc[1];
+    k_max = misc[2];
+    // bins are linear in (composite - minimum key), 2048 of them over the range; when the keys
+    // span fewer than 2048 values the index bits below them join in and spread equal values
+    const u64 base = (u64)k_min << 32;
+    const int rbits = 32 + (32 - __clz(k_max - k_min + 1u | 1u)) ;  // range of (composite - base) < 2^rbits
+    const int bshift = rbits > 11 ? rbits - 11 : 0;
+    uint32_t bin[kBkSlots];
+#pragma unroll
+    for (int e = 0; e < kBkSlots; ++e) {
+        bin[e] = (uint32_t)((c[e] - base) >> bshift);
+        if (c[e]) atomicAdd(&cnt[bin[e]], 1u);
+    }
+    __syncthreads();
+
+    // ---- descending exclusive prefix over the bins: thread t owns the q bins below 2048 - t*q
+    const int q = kBkBins / T;  // T is a multiple of 64 and at most 2048; q*T may fall short of 2048
+    {
+        // general q: walk the own bins from the top; q is 2, 4, 8 ... for the usual workgroup sizes
+        const int hi = kBkBins - 1 - tid * q;
+        uint32_t s = 0, mx = 0;
+        for (int j = 0; j < q; ++j) {
+            const uint32_t v = cnt[hi - j];
+            s += v;
+            mx = v > mx ? v : mx;
+        }
+        // bins not covered because 2048 is not a multiple of T go to the last thread
+        if (tid == T - 1)
+            for (int bb = hi - q; bb >= 0; --bb) {
+                const uint32_t v = cnt[bb];
+                s += v;
+                mx = v > mx ? v : mx;
+            }
+        const uint32_t incl = wave_incl_scan_u32(s);
+        if (lane == kWave - 1) misc[8 + wave] = incl;
+        if (mx > (uint32_t)kBkBinMax) misc[0] = 1u;
+        __syncthreads();
+        const uint32_t tot = (lane < n_waves) ? misc[8 + lane] : 0u;
+        const uint32_t tot_incl = wave_incl_scan_u32(tot);
+        uint32_t run = incl - s;
+        if (wave > 0) run += (uint32_t)__builtin_amdgcn_readlane((int)tot_incl, wave - 1);
+        for (int j = 0; j < q; ++j) {
+            abv[hi - j + 4] = run;
+            run += cnt[hi - j];
+        }
+        if (tid == T - 1) {
+            for (int bb = hi - q; bb >= 0; --bb) {
+                abv[bb + 4] = run;
+                run += cnt[bb];
+            }
+            abv[3] = (uint32_t)count;  // "bin -1" starts behind everything
+        }
+    }
+    __syncthreads();
+    if (misc[0] != 0u) {
+        // A bin is too full: cand still holds the candidates, take the radix descent.  Every
+        // lane reads the same flag; the barrier keeps the descent from reusing this area
+        // before all of them have.
+        __syncthreads();
+        select_radix_write<ELT>(cand, count, k, out_vals, out_idx, row_out);
+        return;
+    }
+
+    // ---- file the possible winners by bin, in place of cand (every lane has its own in registers)
+    uint32_t start[kBkSlots];
+#pragma unroll
+    for (int e = 0; e < kBkSlots; ++e) {
+        start[e] = c[e] ? abv[bin[e] + 4] : 0xffffffffu;
+        if (start[e] < (uint32_t)k) cand[start[e] + atomicSub(&cnt[bin[e]], 1u) - 1u] = c[e];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kBkSlots; ++e)
+        if (start[e] < (uint32_t)k) {
+            const uint32_t end = abv[bin[e] + 3];  // start of the next lower bin
+            uint32_t r = start[e];
+            for (uint32_t j = start[e]; j < end; ++j) r += (cand[j] > c[e]) ? 1u : 0u;
+            if (r < (uint32_t)k) write_composite<ELT>(c[e], out_vals, out_idx, row_out * k + r);
+        }
 }
 
 #endif  // __HIPCC__

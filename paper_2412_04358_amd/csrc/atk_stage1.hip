@@ -449,9 +449,9 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     ATK_CASE(ATK_F32, 4, 4, 4)
     ATK_CASE(ATK_F32, 4, 8, 2)
     ATK_CASE(ATK_F32, 2, 16, 2)
-    ATK_CASE(ATK_F32, 1, 1, 8)
-    ATK_CASE(ATK_F32, 1, 2, 4)
-    ATK_CASE(ATK_F32, 1, 4, 4)
+    ATK_CASE(ATK_F32, 1, 1, 16)
+    ATK_CASE(ATK_F32, 1, 2, 8)
+    ATK_CASE(ATK_F32, 1, 4, 8)
     ATK_CASE(ATK_F32, 1, 8, 4)
     ATK_CASE(ATK_F32, 1, 16, 2)
     ATK_CASE(ATK_BF16, 8, 1, 8)
@@ -459,9 +459,9 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     ATK_CASE(ATK_BF16, 8, 4, 2)
     ATK_CASE(ATK_BF16, 4, 8, 2)
     ATK_CASE(ATK_BF16, 2, 16, 2)
-    ATK_CASE(ATK_BF16, 1, 1, 8)
-    ATK_CASE(ATK_BF16, 1, 2, 4)
-    ATK_CASE(ATK_BF16, 1, 4, 4)
+    ATK_CASE(ATK_BF16, 1, 1, 16)
+    ATK_CASE(ATK_BF16, 1, 2, 8)
+    ATK_CASE(ATK_BF16, 1, 4, 8)
     ATK_CASE(ATK_BF16, 1, 8, 4)
     ATK_CASE(ATK_BF16, 1, 16, 2)
 #undef ATK_CASE
