@@ -95,7 +95,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     plan_override(&T_forced, &S_forced);
     const int64_t n_vec = m * (n / p.V);
     int64_t want_threads = n_vec / 16;
-    if (want_threads < 64 * (int64_t)kNumCU) want_threads = 64 * (int64_t)kNumCU;
+    if (want_threads < 512 * (int64_t)kNumCU) want_threads = 512 * (int64_t)kNumCU;
     if (want_threads > 2048 * (int64_t)kNumCU) want_threads = 2048 * (int64_t)kNumCU;
     int T = 256;
     if (p.G <= 256) {
@@ -139,9 +139,10 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int64_t base = m * p.colblocks;
     int64_t S = want_threads / (base * T);
     int64_t s_rows = p.L / ((int64_t)p.P * 4);       // every lane keeps at least 4 loads
-    int64_t s_traffic = (p.L * es) / (128 * k_b);    // partial lists below 1/8 of the bytes streamed
+    int64_t s_traffic = (p.L * es) / (32 * k_b);     // partial lists (written + read back) below half the bytes streamed
+    int64_t s_fill = ceil_div(kNumCU, base);         // splits that give every CU a workgroup
+    if (S > s_traffic) S = s_traffic > s_fill ? s_traffic : (S < s_fill ? S : s_fill);  // filling the chip comes first
     if (S > s_rows) S = s_rows;
-    if (S > s_traffic) S = s_traffic;
     if (S_forced) S = S_forced;
     if (S > p.L / p.P) S = p.L / p.P;
     if (S < 1) S = 1;

@@ -101,7 +101,9 @@ __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x,
     }
     for (; i < n; i += T) cand[i] = make_composite(load_bits(i), i);
     __syncthreads();
-    select_write<ELT>(cand, n, k, out_vals, out_idx, (int64_t)r);
+    int idx_bits = 1;
+    while ((1 << idx_bits) < n) ++idx_bits;
+    select_write<ELT>(cand, n, k, idx_bits, out_vals, out_idx, (int64_t)r);
 }
 
 // ------------------------------------------------------------------------------------ long rows

@@ -124,6 +124,14 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
     const uint32_t b = min((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48));
     return min(a, b);
 }
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t v) {
+    v |= dpp_u32<0xB1>(v);
+    v |= dpp_u32<0x4E>(v);
+    v |= dpp_u32<0x141>(v);
+    v |= dpp_u32<0x140>(v);
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) | (uint32_t)__builtin_amdgcn_readlane((int)v, 16) |
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) | (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     v = max(v, dpp_u32<0xB1>(v));
     v = max(v, dpp_u32<0x4E>(v));
@@ -327,8 +335,12 @@ __device__ void select_radix_write(u64 *cand, int count, int k, void *out_vals, 
 // No digit-by-digit descent, no compaction, no separate ordering.  If some bin is too full
 // for the in-bin count to stay cheap (heavy ties, values clustered far below the maximum)
 // the radix descent takes over.
+//
+// idx_bits: the candidates' column indices are below 2^idx_bits (1..31); it tells which index
+// bits vary, so that equal values can be spread over bins by index.
 template <int ELT>
-__device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_t *out_idx, int64_t row_out) {
+__device__ void select_write(u64 *cand, int count, int k, int idx_bits, void *out_vals, int32_t *out_idx,
+                             int64_t row_out) {
     const int tid = threadIdx.x, T = blockDim.x;
     if (count > kBkSlots * T || T > kBkBins) {
         select_radix_write<ELT>(cand, count, k, out_vals, out_idx, row_out);
@@ -340,11 +352,11 @@ __device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_
     // LDS behind the candidates (16-byte aligned pieces): counts, "above" table, small words
     uint32_t *cnt = (uint32_t *)(((uintptr_t)(cand + count) + 15) & ~(uintptr_t)15);  // [2048]
     uint32_t *abv = cnt + kBkBins;   // abv[b + 4] = elements in bins above b, for b = -1 .. 2047
-    uint32_t *misc = abv + kBkBins + 8;  // [0] overflow flag, [1] min key, [2] max key, [8..24) wavefront totals
+    uint32_t *misc = abv + kBkBins + 8;  // [0] overflow flag, [1] min key, [2] max key, [3] OR of keys, [8..24) wavefront totals
 
     // ---- candidates into registers (0 = none); clear the counts
     u64 c[kBkSlots];
-    uint32_t k_min = 0xffffffffu, k_max = 0u;
+    uint32_t k_min = 0xffffffffu, k_max = 0u, k_or = 0u;
 #pragma unroll
     for (int e = 0; e < kBkSlots; ++e) {
         const int i = tid + e * T;
@@ -357,6 +369,7 @@ __device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_
             misc[0] = 0u;
             misc[1] = 0xffffffffu;
             misc[2] = 0u;
+            misc[3] = 0u;
         }
     }
 #pragma unroll
@@ -365,27 +378,36 @@ __device__ void select_write(u64 *cand, int count, int k, void *out_vals, int32_
             const uint32_t key = (uint32_t)(c[e] >> 32);
             k_min = key < k_min ? key : k_min;
             k_max = key > k_max ? key : k_max;
+            k_or |= key;
         }
     __syncthreads();
-    // ---- range of the value keys: fold inside the wavefront, one LDS atomic pair per wavefront
+    // ---- range of the value keys: fold inside the wavefront, one set of LDS atomics per wavefront
     k_min = wave_min_u32(k_min);
     k_max = wave_max_u32(k_max);
+    k_or = wave_or_u32(k_or);
     if (lane == 0) {
         atomicMin(&misc[1], k_min);
         atomicMax(&misc[2], k_max);
+        atomicOr(&misc[3], k_or);
     }
     __syncthreads();
     k_min = misc[1];
     k_max = misc[2];
-    // bins are linear in (composite - minimum key), 2048 of them over the range; when the keys
-    // span fewer than 2048 values the index bits below them join in and spread equal values
-    const u64 base = (u64)k_min << 32;
-    const int rbits = 32 + (32 - __clz(k_max - k_min + 1u | 1u)) ;  // range of (composite - base) < 2^rbits
+    k_or = misc[3];
+    // Bin key: the value key relative to the minimum, with the low bits that are zero in every
+    // key squeezed out (bf16 values widened to f32 have 16 of them), followed by the varying
+    // index bits; 2048 bins, linear over that range.  Equal values thus spread over bins by
+    // index when the values alone do not fill the bins.
+    const int tz = k_or ? __builtin_ctz(k_or) : 0;
+    const uint32_t imask = (idx_bits >= 31) ? 0x7fffffffu : ((1u << idx_bits) - 1u);
+    const u64 span = ((u64)((k_max - k_min) >> tz) + 1ull) << idx_bits;  // bin keys are below span
+    const int rbits = 64 - __clzll((long long)span);
     const int bshift = rbits > 11 ? rbits - 11 : 0;
     uint32_t bin[kBkSlots];
 #pragma unroll
     for (int e = 0; e < kBkSlots; ++e) {
-        bin[e] = (uint32_t)((c[e] - base) >> bshift);
+        const u64 bk = ((u64)(((uint32_t)(c[e] >> 32) - k_min) >> tz) << idx_bits) | (((uint32_t)c[e] >> 1) & imask);
+        bin[e] = (uint32_t)(bk >> bshift);
         if (c[e]) atomicAdd(&cnt[bin[e]], 1u);
     }
     __syncthreads();

@@ -29,6 +29,7 @@ struct S1Params {
     int64_t n;
     int b, L, G, Gw, P, colblocks, S, rows_per_split;
     int rem, extra_ph;   // n mod b, and the row phase that takes the ragged last matrix row
+    int idx_bits;        // column indices are below 2^idx_bits
     int k, k_b;
     int stage2, direct, use_scratch, vec_store;
     int wave_merge;      // Gw < 64 and a power of two: lanes of one wavefront share columns
@@ -384,7 +385,7 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     }
 
     // ---------------------------------------------------------------- Stage 2 in LDS
-    select_write<ELT>(cand, n_cand, p.k, p.out_vals, p.out_idx, (int64_t)r);
+    select_write<ELT>(cand, n_cand, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -423,6 +424,8 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.rows_per_split = pl.rows_per_split;
     prm.rem = (int)(pl.n % pl.b);
     prm.extra_ph = (int)(pl.L % pl.P);
+    prm.idx_bits = 1;
+    while (((int64_t)1 << prm.idx_bits) < pl.n) ++prm.idx_bits;
     prm.k = (int)pl.k;
     prm.k_b = pl.k_b;
     prm.stage2 = pl.stage2;
