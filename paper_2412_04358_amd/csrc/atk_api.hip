@@ -46,8 +46,8 @@ static int check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b,
 }
 
 // ------------------------------------------------------------------------------------ plan override
-// ATK_PLAN="T=128,S=4": tuning knobs for sweeps; values are clamped to what the kernels accept.
-static void plan_override(int *T, int *S) {
+// ATK_PLAN="T=128,S=4,V=2": tuning knobs for sweeps; values are clamped to what the kernels accept.
+static void plan_override(int *T, int *S, int *V) {
     const char *e = getenv("ATK_PLAN");
     if (!e) return;
     const char *p = strstr(e, "T=");
@@ -59,6 +59,11 @@ static void plan_override(int *T, int *S) {
     if (p && S) {
         int v = atoi(p + 2);
         if (v >= 1 && v <= 4096) *S = v;
+    }
+    p = strstr(e, "V=");
+    if (p && V) {
+        int v = atoi(p + 2);
+        if (v == 1 || v == 2 || v == 4 || v == 8) *V = v;
     }
 }
 
@@ -75,13 +80,11 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.b = b;
     p.k_b = (int)k_b;
     p.KB = (int)pow2_ceil(k_b);
-    int vmax;
-    if (dtype == ATK_F32)
-        vmax = (p.KB <= 8) ? 4 : 2;
-    else
-        vmax = (p.KB <= 4) ? 8 : (p.KB == 8 ? 4 : 2);
-    // vector loads need every matrix row to start on a 16-byte boundary
-    p.V = (ptr16 && b % vmax == 0 && n % vmax == 0) ? vmax : 1;
+    // columns per lane: the default instance for (dtype, KB), or the widest one within V_forced
+    int T_forced = 0, S_forced = 0, V_forced = 0;
+    plan_override(&T_forced, &S_forced, &V_forced);
+    // (vector loads need a 16-byte aligned x and every matrix row starting on a multiple of V)
+    p.V = stage1_pick_v(dtype, p.KB, !ptr16 ? 1 : V_forced, b, n);
     p.G = b / p.V;
     p.L = n / b;
     p.stage2 = b * k_b > k;
@@ -91,8 +94,6 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // costs a trip through memory at the end.  Narrow bucket layouts (fewer column groups
     // than lanes) take big workgroups, whose lanes merge through shuffles and LDS.
     const int t_max = max_threads_for_kb(p.KB);
-    int T_forced = 0, S_forced = 0;
-    plan_override(&T_forced, &S_forced);
     const int64_t n_vec = m * (n / p.V);
     int64_t want_threads = n_vec / 16;
     if (want_threads < 512 * (int64_t)kNumCU) want_threads = 512 * (int64_t)kNumCU;

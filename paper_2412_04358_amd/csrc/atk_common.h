@@ -15,6 +15,33 @@ constexpr int kWave = 64;
 constexpr int kMaxThreads = 256;          // threads per workgroup of the select kernels
 // largest workgroup of the streaming kernel: big register queues (k_b >= 8) keep to 256 lanes
 constexpr int max_threads_for_kb(int KB) { return KB <= 4 ? 1024 : 256; }
+// Streaming-kernel instances: X(element type, columns per lane V, slots KB, load batches U).
+// One lane owns V adjacent buckets and reads them with one V-element load per matrix row.
+// For every (type, KB) the first entry is the planner's default; the others can be asked
+// for with ATK_PLAN="V=..", and V=1 serves rows whose layout rules out vector loads.
+// Wide lanes pay off only for KB = 1: with more slots the per-lane register queues
+// (V*KB values and rows) cut the waves per CU, and narrower lanes are faster.
+#define ATK_STAGE1_INSTANCES(X) \
+    X(ATK_F32, 4, 1, 8)   X(ATK_F32, 2, 1, 8)   X(ATK_F32, 1, 1, 16)  \
+    X(ATK_F32, 2, 2, 8)   X(ATK_F32, 4, 2, 4)   X(ATK_F32, 1, 2, 8)   \
+    X(ATK_F32, 2, 4, 8)   X(ATK_F32, 4, 4, 4)   X(ATK_F32, 1, 4, 8)   \
+    X(ATK_F32, 2, 8, 4)   X(ATK_F32, 4, 8, 2)   X(ATK_F32, 1, 8, 4)   \
+    X(ATK_F32, 2, 16, 2)  X(ATK_F32, 1, 16, 2)                        \
+    X(ATK_BF16, 8, 1, 8)  X(ATK_BF16, 4, 1, 8)  X(ATK_BF16, 1, 1, 16) \
+    X(ATK_BF16, 4, 2, 8)  X(ATK_BF16, 8, 2, 4)  X(ATK_BF16, 2, 2, 8)  X(ATK_BF16, 1, 2, 8) \
+    X(ATK_BF16, 2, 4, 8)  X(ATK_BF16, 4, 4, 8)  X(ATK_BF16, 8, 4, 2)  X(ATK_BF16, 1, 4, 8) \
+    X(ATK_BF16, 2, 8, 4)  X(ATK_BF16, 4, 8, 2)  X(ATK_BF16, 1, 8, 4)  \
+    X(ATK_BF16, 2, 16, 2) X(ATK_BF16, 1, 16, 2)
+
+// Columns per lane for (dtype, KB): the first listed instance whose V divides both b and n, so
+// that every V-element load is naturally aligned (and equals `want`, when that is not 0).
+inline int stage1_pick_v(int dtype, int KB, int want, int64_t b, int64_t n) {
+#define ATK_X(ELT, VV, KK, UU) \
+    if (dtype == ELT && KB == KK && (want == 0 || VV == want) && b % VV == 0 && n % VV == 0) return VV;
+    ATK_STAGE1_INSTANCES(ATK_X)
+#undef ATK_X
+    return want ? stage1_pick_v(dtype, KB, 0, b, n) : 1;
+}
 constexpr int kStage2MaxCand = 4096;      // composites held in LDS by the fused Stage 2
 constexpr int kLdsBudget = 64 * 1024;     // static+dynamic LDS per workgroup we allow ourselves
 constexpr int kNumCU = 256;               // MI355X

@@ -444,29 +444,9 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
         const char *e = getenv("ATK_SYNC");
         prm.fence_sync = (e && strcmp(e, "fence") == 0) ? 1 : 0;
     }
-    // (element type, columns per lane, slots) combinations that make_plan() can choose
 #define ATK_CASE(ELT, VV, KK, UU) \
     if (pl.dtype == ELT && pl.V == VV && pl.KB == KK) return launch_one<ELT, VV, KK, UU>(pl, prm, stream);
-    ATK_CASE(ATK_F32, 4, 1, 8)
-    ATK_CASE(ATK_F32, 4, 2, 4)
-    ATK_CASE(ATK_F32, 4, 4, 4)
-    ATK_CASE(ATK_F32, 4, 8, 2)
-    ATK_CASE(ATK_F32, 2, 16, 2)
-    ATK_CASE(ATK_F32, 1, 1, 16)
-    ATK_CASE(ATK_F32, 1, 2, 8)
-    ATK_CASE(ATK_F32, 1, 4, 8)
-    ATK_CASE(ATK_F32, 1, 8, 4)
-    ATK_CASE(ATK_F32, 1, 16, 2)
-    ATK_CASE(ATK_BF16, 8, 1, 8)
-    ATK_CASE(ATK_BF16, 8, 2, 4)
-    ATK_CASE(ATK_BF16, 8, 4, 2)
-    ATK_CASE(ATK_BF16, 4, 8, 2)
-    ATK_CASE(ATK_BF16, 2, 16, 2)
-    ATK_CASE(ATK_BF16, 1, 1, 16)
-    ATK_CASE(ATK_BF16, 1, 2, 8)
-    ATK_CASE(ATK_BF16, 1, 4, 8)
-    ATK_CASE(ATK_BF16, 1, 8, 4)
-    ATK_CASE(ATK_BF16, 1, 16, 2)
+    ATK_STAGE1_INSTANCES(ATK_CASE)
 #undef ATK_CASE
     return hipErrorInvalidValue;
 }

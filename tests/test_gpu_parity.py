@@ -176,6 +176,19 @@ def test_forced_plans(plan, monkeypatch):
             run_case(x, k, b, k_b, tag=plan)
 
 
+@pytest.mark.parametrize("lanes", ["V=1", "V=2", "V=4", "V=8"])
+def test_forced_lane_widths(lanes, monkeypatch):
+    """Every compiled (type, columns per lane, slots) instance gives the same results."""
+    monkeypatch.setenv("ATK_PLAN", lanes)
+    for i, (m, n, k, b, k_b) in enumerate([(3, 16384, 2048, 2048, 1), (3, 16384, 64, 64, 1), (3, 16384, 100, 256, 1),
+                                           (3, 16384, 2048, 1024, 2), (3, 16384, 128, 64, 2), (3, 16384, 2048, 512, 4),
+                                           (3, 16384, 96, 32, 4), (3, 16384, 2048, 256, 8), (2, 16384, 64, 8, 8),
+                                           (2, 16384, 2048, 128, 16), (2, 16384, 200, 16, 16), (2, 16392, 64, 64, 3)]):
+        for dtype in ["f32", "bf16"]:
+            x = workloads.normal_rows(m, n, seed=300 + i, dtype=dtype)
+            run_case(x, k, b, k_b, tag=lanes)
+
+
 # ------------------------------------------------------------------------------- ties and special values
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ties_and_specials(dtype):

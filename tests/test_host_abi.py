@@ -112,9 +112,14 @@ def test_plan_shapes(lib):
     # bf16 uses 8 columns per lane
     p = parse_plan(atk.plan_describe(2048, 8192, 512, 512, 1, atk.ATK_BF16))
     assert p["V"] == 8 and p["Gw"] == 64 and p["wave_merge"] == 0
-    # b not a multiple of the vector width: scalar columns
+    # b not a multiple of the vector width: the widest lanes that still divide b and n, else scalar columns
     p = parse_plan(atk.plan_describe(2, 4098, 6, 6, 1))
+    assert p["V"] == 2 and p["wave_merge"] == 0
+    p = parse_plan(atk.plan_describe(2, 4095, 7, 7, 1))
     assert p["V"] == 1 and p["wave_merge"] == 0
+    # several slots per bucket: narrower lanes than for k_b = 1
+    p = parse_plan(atk.plan_describe(128, 65536, 16384, 4096, 4))
+    assert p["V"] == 2 and p["KB"] == 4 and p["direct"] == 1
     # big register queues keep to 256 lanes
     p = parse_plan(atk.plan_describe(128, 1 << 20, 64, 8, 8))
     assert p["KB"] == 8 and p["T"] <= 256
@@ -136,6 +141,12 @@ def test_plan_override_env(lib, monkeypatch):
     monkeypatch.setenv("ATK_PLAN", "T=1024")
     p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
     assert p["T"] == 1024
+    monkeypatch.setenv("ATK_PLAN", "V=1")
+    p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
+    assert p["V"] == 1
+    monkeypatch.setenv("ATK_PLAN", "V=4")
+    p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 4))
+    assert p["V"] == 4
     monkeypatch.delenv("ATK_PLAN")
     q = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
     assert q["T"] in (256, 512)
