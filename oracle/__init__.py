@@ -22,6 +22,8 @@ _LIB = os.path.join(_HERE, "libtopk_oracle.so")
 
 F32 = 0
 BF16 = 1
+INTERLEAVED = 0  # bucket of element i is i mod b (Appendix A.1; the paper's experiments)
+CONTIGUOUS = 1   # bucket of element i is floor(b*i/n) (Appendix A.1)
 
 _lib = None
 
@@ -44,6 +46,8 @@ def _load():
         i64, vp, i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         lib.orc_approx_topk.argtypes = [vp, i64, i64, i64, i64, i64, i32, vp, vp, vp, vp, i32]
         lib.orc_approx_topk.restype = i32
+        lib.orc_approx_topk_assign.argtypes = [vp, i64, i64, i64, i64, i64, i32, i32, vp, vp, vp, vp, i32]
+        lib.orc_approx_topk_assign.restype = i32
         lib.orc_exact_topk.argtypes = [vp, i64, i64, i64, i32, vp, vp, i32]
         lib.orc_exact_topk.restype = i32
         _lib = lib
@@ -62,8 +66,10 @@ def _prep(x):
     raise TypeError("x must be float32, or uint16 holding bf16 bit patterns")
 
 
-def approx_topk(x, k, b, k_b, threads=1, return_candidates=False):
+def approx_topk(x, k, b, k_b, threads=1, return_candidates=False, assignment=INTERLEAVED):
     """Bucketed approximate top-k of every row of x.
+
+    assignment: INTERLEAVED (i mod b) or CONTIGUOUS (floor(b*i/n)), Appendix A.1.
 
     Returns (vals, idx), each (m, k); vals has x's dtype and carries the original
     bits, idx is int32.  With return_candidates also returns the Stage-1 output
@@ -79,8 +85,8 @@ def approx_topk(x, k, b, k_b, threads=1, return_candidates=False):
         cv = np.empty((m, b * k_b), dtype=x.dtype)
         ci = np.empty((m, b * k_b), dtype=np.int32)
         cvp, cip = cv.ctypes.data, ci.ctypes.data
-    rc = _load().orc_approx_topk(x.ctypes.data, m, n, k, b, k_b, dt, vals.ctypes.data, idx.ctypes.data,
-                                 cvp, cip, int(threads))
+    rc = _load().orc_approx_topk_assign(x.ctypes.data, m, n, k, b, k_b, dt, int(assignment), vals.ctypes.data,
+                                        idx.ctypes.data, cvp, cip, int(threads))
     if rc != 0:
         raise ValueError("oracle approx_topk rejected its arguments (code %d)" % rc)
     if return_candidates:

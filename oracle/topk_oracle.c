@@ -9,8 +9,10 @@
  * design choices", Stage 1 / Stage 2, and Figure 2 left):
  *
  *   Stage 1  element i belongs to bucket i mod b (Appendix A.1, interleaved
- *            assignment).  Each bucket is sorted and its k_b largest elements are
- *            kept; the b lists are concatenated in bucket order (b*k_b candidates).
+ *            assignment, the one used throughout the paper's experiments) or to
+ *            bucket floor(b*i/n) (Appendix A.1, contiguous assignment).  Each bucket
+ *            is sorted and its k_b largest elements are kept; the b lists are
+ *            concatenated in bucket order (b*k_b candidates).
  *   Stage 2  only when b*k_b > k: the k largest of the candidates are kept.
  *
  * Conventions the paper leaves open and this build fixes:
@@ -20,9 +22,11 @@
  *     Rows must be NaN-free.
  *   - output order: without Stage 2, slot j*k_b + t holds the t-th largest of
  *     bucket j; with Stage 2 the k survivors are listed largest first.
- *   - n need not be a multiple of b: bucket j simply holds the indices
- *     j, j+b, j+2b, ... below n (the short buckets of Figure 2, whose pad cell is
- *     never selected); k_b <= floor(n/b) keeps every bucket long enough.
+ *   - n need not be a multiple of b: bucket j simply holds the indices that the
+ *     assignment formula sends there (interleaved: j, j+b, j+2b, ... below n, the
+ *     short buckets of Figure 2, whose pad cell is never selected); every bucket
+ *     then has floor(n/b) or ceil(n/b) elements, and k_b <= floor(n/b) keeps each
+ *     one long enough.
  *   - out_vals carries the element's own bits (the sign of a zero survives).
  *
  * exact top-k (the comparison point, Section 1): sort the whole row by the same
@@ -33,6 +37,7 @@
 #include <string.h>
 
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_INTERLEAVED = 0, ORC_CONTIGUOUS = 1 };
 enum { ORC_OK = 0, ORC_BAD_ARG = -1, ORC_NO_MEM = -2 };
 
 typedef struct {
@@ -76,24 +81,44 @@ static int by_rank(const void *pa, const void *pb)
     return 0;
 }
 
+/* Appendix A.1: the bucket of element i */
+static int64_t bucket_of(int64_t i, int64_t n, int64_t b, int assignment)
+{
+    if (assignment == ORC_CONTIGUOUS)
+        return (b * i) / n;
+    return i % b;
+}
+
 static int approx_row(const void *x, int64_t row, int64_t n, int64_t k, int64_t b, int64_t k_b,
-                      int dtype, void *out_vals, int32_t *out_idx,
+                      int dtype, int assignment, void *out_vals, int32_t *out_idx,
                       void *cand_vals, int32_t *cand_idx)
 {
-    int64_t max_len = (n + b - 1) / b;
-    item_t *bucket = (item_t *)malloc((size_t)max_len * sizeof(item_t));
+    /* the row's elements grouped by bucket, each group in increasing index order:
+       start[j] .. start[j+1] is bucket j */
+    item_t *grouped = (item_t *)malloc((size_t)n * sizeof(item_t));
+    int64_t *start = (int64_t *)calloc((size_t)b + 1, sizeof(int64_t));
+    int64_t *fill = (int64_t *)malloc((size_t)b * sizeof(int64_t));
     item_t *cand = (item_t *)malloc((size_t)(b * k_b) * sizeof(item_t));
-    if (!bucket || !cand) { free(bucket); free(cand); return ORC_NO_MEM; }
+    if (!grouped || !start || !fill || !cand) {
+        free(grouped); free(start); free(fill); free(cand);
+        return ORC_NO_MEM;
+    }
+    for (int64_t i = 0; i < n; ++i)
+        start[bucket_of(i, n, b, assignment) + 1] += 1;
+    for (int64_t j = 0; j < b; ++j) {
+        start[j + 1] += start[j];
+        fill[j] = start[j];
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        item_t *e = &grouped[fill[bucket_of(i, n, b, assignment)]++];
+        e->v = widen(x, row * n + i, dtype, &e->raw);
+        e->i = (int32_t)i;
+    }
 
     /* Stage 1 */
     for (int64_t j = 0; j < b; ++j) {
-        int64_t len = 0;
-        for (int64_t i = j; i < n; i += b) {
-            bucket[len].v = widen(x, row * n + i, dtype, &bucket[len].raw);
-            bucket[len].i = (int32_t)i;
-            ++len;
-        }
-        qsort(bucket, (size_t)len, sizeof(item_t), by_rank);
+        item_t *bucket = grouped + start[j];
+        qsort(bucket, (size_t)(start[j + 1] - start[j]), sizeof(item_t), by_rank);
         for (int64_t t = 0; t < k_b; ++t)
             cand[j * k_b + t] = bucket[t];
     }
@@ -110,7 +135,9 @@ static int approx_row(const void *x, int64_t row, int64_t n, int64_t k, int64_t 
         put_val(out_vals, row * k + s, dtype, cand[s].raw);
         out_idx[row * k + s] = cand[s].i;
     }
-    free(bucket);
+    free(grouped);
+    free(start);
+    free(fill);
     free(cand);
     return ORC_OK;
 }
@@ -140,10 +167,11 @@ static int exact_row(const void *x, int64_t row, int64_t n, int64_t k, int dtype
  * threads: rows are independent and are split over this many OpenMP threads.
  * Constraints (Section 2): 1 <= b <= n, 1 <= k_b <= min(k, floor(n/b)), b*k_b >= k.
  */
-int orc_approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b,
-                    int dtype, void *out_vals, int32_t *out_idx,
-                    void *cand_vals, int32_t *cand_idx, int threads)
+int orc_approx_topk_assign(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b,
+                           int dtype, int assignment, void *out_vals, int32_t *out_idx,
+                           void *cand_vals, int32_t *cand_idx, int threads)
 {
+    if (assignment != ORC_INTERLEAVED && assignment != ORC_CONTIGUOUS) return ORC_BAD_ARG;
     if (!x || !out_vals || !out_idx) return ORC_BAD_ARG;
     if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_BAD_ARG;
     if (m < 1 || n < 1 || n > INT32_MAX || k < 1 || k > n) return ORC_BAD_ARG;
@@ -152,13 +180,22 @@ int orc_approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, i
     int status = ORC_OK;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
     for (int64_t r = 0; r < m; ++r) {
-        int rc = approx_row(x, r, n, k, b, k_b, dtype, out_vals, out_idx, cand_vals, cand_idx);
+        int rc = approx_row(x, r, n, k, b, k_b, dtype, assignment, out_vals, out_idx, cand_vals, cand_idx);
         if (rc != ORC_OK) {
 #pragma omp critical
             status = rc;
         }
     }
     return status;
+}
+
+/* the interleaved assignment, as in all of the paper's experiments */
+int orc_approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b,
+                    int dtype, void *out_vals, int32_t *out_idx,
+                    void *cand_vals, int32_t *cand_idx, int threads)
+{
+    return orc_approx_topk_assign(x, m, n, k, b, k_b, dtype, ORC_INTERLEAVED, out_vals, out_idx,
+                                  cand_vals, cand_idx, threads);
 }
 
 int orc_exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype,

@@ -48,6 +48,25 @@ def normal_rows(m: int, n: int, seed: int = 0, dtype: str = "f32") -> torch.Tens
     return x if dtype == "f32" else x.to(torch.bfloat16)
 
 
+def correlated_rows(m: int, n: int, rho: float, seed: int = 0, shuffle: bool = False) -> torch.Tensor:
+    """m x n f32 rows of N(0, Sigma) with Sigma_ij = rho^|i-j| (Appendix A.1's correlated-sequence
+    simulation), drawn as the stationary AR(1) sequence x_0 = z_0, x_i = rho*x_{i-1} +
+    sqrt(1-rho^2)*z_i, which has exactly that covariance.  shuffle=True applies one random
+    permutation per row afterwards (the figure's right panel)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    z = torch.randn((m, n), generator=g, dtype=torch.float64)
+    x = torch.empty_like(z)
+    x[:, 0] = z[:, 0]
+    c = math.sqrt(1.0 - rho * rho)
+    for i in range(1, n):
+        x[:, i] = rho * x[:, i - 1] + c * z[:, i]
+    if shuffle:
+        for r in range(m):
+            x[r] = x[r, torch.randperm(n, generator=g)]
+    return x.to(torch.float32)
+
+
 def attention_scores(heads: int = 32, queries: int = 64, keys: int = 8192, d: int = 128,
                      seed: int = 0) -> torch.Tensor:
     """(heads*queries) x keys bf16 score rows: (q . K^T) / sqrt(d), f32 matmul, then bf16."""

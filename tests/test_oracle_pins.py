@@ -17,8 +17,9 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
 # ----------------------------------------------------------------------------- helpers
-def brute_force(row, k, b, k_b):
+def brute_force(row, k, b, k_b, bucket=None):
     """O(n^2) definition by rank counting; returns the selected index list in output order.
+    bucket(i): the bucket of element i (default: i mod b).
 
     rank_in_bucket(i) = #{j in bucket(i) : x_j ranks before x_i}; i is a candidate iff
     that rank is below k_b.  Without Stage 2 the output slot of candidate i is
@@ -26,20 +27,26 @@ def brute_force(row, k, b, k_b):
     """
     n = len(row)
     row = [float(v) for v in row]
+    if bucket is None:
+        bucket = lambda i: i % b
+    members = {}
+    for i in range(n):
+        members.setdefault(bucket(i), []).append(i)
+    assert sorted(members) == list(range(b))
 
     def before(j, i):  # does element j rank before element i ?
         return row[j] > row[i] or (row[j] == row[i] and j < i)
 
     cand = {}
     for i in range(n):
-        r = sum(1 for j in range(i % b, n, b) if before(j, i))
+        r = sum(1 for j in members[bucket(i)] if before(j, i))
         if r < k_b:
             cand[i] = r
     assert len(cand) == b * k_b
     out = [None] * k
     if b * k_b == k:
         for i, r in cand.items():
-            out[(i % b) * k_b + r] = i
+            out[bucket(i) * k_b + r] = i
     else:
         for i in cand:
             r = sum(1 for j in cand if before(j, i))
@@ -127,6 +134,83 @@ def test_brute_force_small(kind):
             assert np.array_equal(bits(vals[0]), bits(row[want])), (n, k, b, k_b)
             checked += 1
     assert checked > 500
+
+
+@pytest.mark.parametrize("kind", ["normal", "two_valued"])
+def test_brute_force_contiguous(kind):
+    """Contiguous assignment (Appendix A.1): bucket of i is floor(b*i/n), any n and b."""
+    rng = np.random.default_rng(11)
+    checked = 0
+    for n in list(range(1, 19)) + [24, 30, 33, 48, 64]:
+        row = rng.standard_normal(n).astype(np.float32) if kind == "normal" else rng.integers(0, 2, n).astype(np.float32)
+        params = list(legal_params(n))
+        if n > 18:
+            sel = rng.choice(len(params), size=min(40, len(params)), replace=False)
+            params = [params[i] for i in sel]
+        for k, b, k_b in params:
+            vals, idx = oracle.approx_topk(row[None, :], k, b, k_b, assignment=oracle.CONTIGUOUS)
+            want = brute_force(row, k, b, k_b, bucket=lambda i: (b * i) // n)
+            assert idx[0].tolist() == want, (n, k, b, k_b)
+            assert np.array_equal(bits(vals[0]), bits(row[want])), (n, k, b, k_b)
+            checked += 1
+    assert checked > 400
+
+
+def test_contiguous_is_interleaved_of_the_transposed_row():
+    """With b | n the row is a b x L matrix whose rows are the contiguous buckets; read column by
+    column (transposed) the same buckets are interleaved.  Tie-free rows, so that Stage 2 does not
+    depend on how indices are numbered."""
+    for (n, k, b, k_b) in [(4096, 64, 64, 1), (4096, 48, 64, 1), (4096, 256, 64, 4), (6000, 100, 40, 3), (512, 512, 64, 8)]:
+        L = n // b
+        x = workloads.normal_rows(3, n, seed=n + k).numpy()
+        xt = np.ascontiguousarray(x.reshape(3, b, L).transpose(0, 2, 1)).reshape(3, n)
+        v1, i1 = oracle.approx_topk(x, k, b, k_b, assignment=oracle.CONTIGUOUS)
+        v2, i2 = oracle.approx_topk(xt, k, b, k_b)
+        # transposed index l*b + j  <->  original index j*L + l
+        back = (i2 % b) * L + i2 // b
+        assert np.array_equal(i1, back.astype(np.int32))
+        assert np.array_equal(bits(v1), bits(v2))
+
+
+def test_b1_and_b_equal_n_do_not_depend_on_the_assignment():
+    x = workloads.normal_rows(2, 1000, seed=5).numpy()
+    for (k, b, k_b) in [(10, 1, 10), (1000, 1000, 1), (300, 1000, 1)]:
+        a = oracle.approx_topk(x, k, b, k_b)
+        c = oracle.approx_topk(x, k, b, k_b, assignment=oracle.CONTIGUOUS)
+        assert np.array_equal(a[1], c[1]) and np.array_equal(bits(a[0]), bits(c[0]))
+
+
+def _recall(idx, exact_idx):
+    return np.mean([len(set(a.tolist()) & set(e.tolist())) / len(e) for a, e in zip(idx, exact_idx)])
+
+
+def test_correlated_sequences_hurt_contiguous_not_interleaved():
+    """Appendix A.1's simulation: n = 2048, k = 256, x ~ N(0, Sigma), Sigma_ij = rho^|i-j|.  As rho
+    grows the contiguous assignment loses recall (also for larger k_b), the interleaved one keeps
+    it, and shuffling the row first brings the contiguous one back to the interleaved level."""
+    n, k, rows = 2048, 256, 96
+    for k_b in (1, 2, 4):
+        b = k // k_b
+        iid = recall.expected_recall_iid_exact(n, k, b, k_b)
+        got = {}
+        for rho in (0.0, 0.9, 0.99):
+            x = workloads.correlated_rows(rows, n, rho, seed=17).numpy()
+            xs = workloads.correlated_rows(rows, n, rho, seed=17, shuffle=True).numpy()
+            ex = oracle.exact_topk(x, k)[1]
+            exs = oracle.exact_topk(xs, k)[1]
+            got[rho] = (
+                _recall(oracle.approx_topk(x, k, b, k_b)[1], ex),
+                _recall(oracle.approx_topk(x, k, b, k_b, assignment=oracle.CONTIGUOUS)[1], ex),
+                _recall(oracle.approx_topk(xs, k, b, k_b, assignment=oracle.CONTIGUOUS)[1], exs),
+            )
+        inter0, contig0, shuf0 = got[0.0]
+        assert abs(inter0 - iid) < 0.02 and abs(contig0 - iid) < 0.02 and abs(shuf0 - iid) < 0.02
+        for rho in (0.9, 0.99):
+            inter, contig, shuf = got[rho]
+            assert inter > iid - 0.02          # interleaving keeps (or improves on) the i.i.d. recall
+            assert abs(shuf - iid) < 0.02      # a shuffled row is exchangeable: the i.i.d. value again
+            assert contig < inter - 0.05       # contiguous buckets share the runs of large values
+        assert got[0.99][1] < got[0.9][1] < got[0.0][1] + 0.02
 
 
 def test_brute_force_bf16_ties():
