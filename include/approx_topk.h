@@ -40,6 +40,12 @@ extern "C" {
 /* element types of x / out_vals */
 enum { ATK_F32 = 0, ATK_BF16 = 1 };
 
+/* bucket assignment functions of Appendix A.1 */
+enum {
+    ATK_INTERLEAVED = 0, /* element i goes to bucket i mod b: what the paper uses in all experiments */
+    ATK_CONTIGUOUS = 1   /* element i goes to bucket floor(b*i/n): runs of n/b adjacent elements */
+};
+
 /* return codes */
 enum {
     ATK_OK = 0,
@@ -75,6 +81,17 @@ int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64
                 void *out_vals, int32_t *out_idx, void *stream);
 
 /*
+ * The same with the bucket assignment as an argument (Appendix A.1, "Bucket assignment"):
+ * ATK_INTERLEAVED is approx_topk itself; ATK_CONTIGUOUS makes bucket j the run of elements
+ * ceil(j*n/b) <= i < ceil((j+1)*n/b) (lengths floor(n/b) or ceil(n/b)).  Output order, ties and
+ * errors as for approx_topk; any other `assignment` is ATK_ERR_BAD_PARAMS.  Contiguous buckets
+ * lose recall on sequences whose neighbours are correlated (the appendix's simulation); they
+ * are here to reproduce that comparison.
+ */
+int approx_topk_assign(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
+                       int assignment, void *out_vals, int32_t *out_idx, void *stream);
+
+/*
  * Exact top-k of every row, the comparison point (Section 1; the radix-select listing of
  * Appendix D.2 is the algorithm family): the k largest elements, largest first.
  * Arguments as for approx_topk.
@@ -108,6 +125,9 @@ int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype);
  */
 int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
                       int64_t buflen);
+/* The same for approx_topk_assign (for ATK_CONTIGUOUS: lanes per bucket Gs, workgroups across the buckets, splits). */
+int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
+                             char *buf, int64_t buflen);
 
 /*
  * Measurement utilities (Appendix B.1 protocol, and the roofline's empirical ceiling).

@@ -5,9 +5,12 @@ library is loaded on first use and a missing build raises, there is no CPU fallb
 """
 from .binding import (  # noqa: F401
     ATK_BF16,
+    ATK_CONTIGUOUS,
     ATK_F32,
+    ATK_INTERLEAVED,
     ApproxTopkError,
     approx_topk,
+    approx_topk_assign_raw,
     approx_topk_raw,
     exact_topk,
     exact_topk_raw,

@@ -15,6 +15,8 @@ _LIB_PATH = os.path.join(_HERE, "lib", "libapprox_topk.so")
 
 ATK_F32 = 0
 ATK_BF16 = 1
+ATK_INTERLEAVED = 0
+ATK_CONTIGUOUS = 1
 
 _lib = None
 
@@ -42,6 +44,10 @@ def load_library():
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.approx_topk.argtypes = [vp, i64, i64, i64, i64, i64, ci, vp, vp, vp]
     lib.approx_topk.restype = ci
+    lib.approx_topk_assign.argtypes = [vp, i64, i64, i64, i64, i64, ci, ci, vp, vp, vp]
+    lib.approx_topk_assign.restype = ci
+    lib.atk_plan_describe_assign.argtypes = [i64, i64, i64, i64, i64, ci, ci, ctypes.c_char_p, i64]
+    lib.atk_plan_describe_assign.restype = ci
     lib.exact_topk.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
     lib.exact_topk.restype = ci
     lib.atk_strerror.argtypes = [ci]
@@ -88,6 +94,11 @@ def approx_topk_raw(x_ptr, m, n, k, b, k_b, dtype, out_vals_ptr, out_idx_ptr, st
     return load_library().approx_topk(x_ptr, m, n, k, b, k_b, dtype, out_vals_ptr, out_idx_ptr, stream_ptr)
 
 
+def approx_topk_assign_raw(x_ptr, m, n, k, b, k_b, dtype, assignment, out_vals_ptr, out_idx_ptr, stream_ptr=0) -> int:
+    return load_library().approx_topk_assign(x_ptr, m, n, k, b, k_b, dtype, assignment, out_vals_ptr, out_idx_ptr,
+                                             stream_ptr)
+
+
 def exact_topk_raw(x_ptr, m, n, k, dtype, out_vals_ptr, out_idx_ptr, stream_ptr=0) -> int:
     return load_library().exact_topk(x_ptr, m, n, k, dtype, out_vals_ptr, out_idx_ptr, stream_ptr)
 
@@ -112,11 +123,12 @@ def _tensor_args(x):
     return torch, x.shape[0], x.shape[1], _dtype_code(x)
 
 
-def approx_topk(x, k, b, k_b, out=None):
+def approx_topk(x, k, b, k_b, out=None, assignment=None):
     """Bucketed approximate top-k of every row of a GPU tensor x (m, n), f32 or bf16.
 
     Returns (vals, idx): vals (m, k) of x's dtype, idx (m, k) int32.  Runs on torch's
-    current stream of x's device.
+    current stream of x's device.  assignment: None calls approx_topk (interleaved buckets);
+    ATK_INTERLEAVED / ATK_CONTIGUOUS call approx_topk_assign.
     """
     torch, m, n, dt = _tensor_args(x)
     with torch.cuda.device(x.device):
@@ -126,7 +138,11 @@ def approx_topk(x, k, b, k_b, out=None):
         else:
             vals, idx = out
         stream = torch.cuda.current_stream(x.device).cuda_stream
-        _check(approx_topk_raw(x.data_ptr(), m, n, k, b, k_b, dt, vals.data_ptr(), idx.data_ptr(), stream))
+        if assignment is None:
+            _check(approx_topk_raw(x.data_ptr(), m, n, k, b, k_b, dt, vals.data_ptr(), idx.data_ptr(), stream))
+        else:
+            _check(approx_topk_assign_raw(x.data_ptr(), m, n, k, b, k_b, dt, int(assignment), vals.data_ptr(),
+                                          idx.data_ptr(), stream))
     return vals, idx
 
 
@@ -144,7 +160,7 @@ def exact_topk(x, k, out=None):
     return vals, idx
 
 
-def plan_describe(m, n, k, b, k_b, dtype=ATK_F32) -> str:
+def plan_describe(m, n, k, b, k_b, dtype=ATK_F32, assignment=ATK_INTERLEAVED) -> str:
     buf = ctypes.create_string_buffer(512)
-    _check(load_library().atk_plan_describe(m, n, k, b, k_b, dtype, buf, 512))
+    _check(load_library().atk_plan_describe_assign(m, n, k, b, k_b, dtype, assignment, buf, 512))
     return buf.value.decode()

@@ -172,6 +172,79 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     return ATK_OK;
 }
 
+// ------------------------------------------------------------------------------------ contiguous plan
+// Gs lanes per bucket, chosen so that a lane has about 8 loads while the launch still has
+// enough lanes for the chip; buckets longer than a workgroup can chew are also split.
+int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, bool ptr16, Plan *pl) {
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    Plan p;
+    memset(&p, 0, sizeof p);
+    p.assignment = ATK_CONTIGUOUS;
+    p.dtype = dtype;
+    p.m = m;
+    p.n = n;
+    p.k = k;
+    p.b = b;
+    p.k_b = (int)k_b;
+    p.KB = (int)pow2_ceil(k_b);
+    p.L = n / b;
+    p.stage2 = b * k_b > k;
+    const int vfull = 16 / es;
+    p.V = (ptr16 && n % b == 0 && p.L % vfull == 0) ? vfull : 1;
+    int T_forced = 0, S_forced = 0, V_forced = 0;
+    plan_override(&T_forced, &S_forced, &V_forced);
+    if (V_forced == 1) p.V = 1;
+    const int t_max = max_threads_for_kb(p.KB);
+    const int64_t chunks = ceil_div(n, b) / p.V;  // of the longest bucket (V > 1: of every bucket)
+    const int64_t want_lanes = 512 * (int64_t)kNumCU;
+    int64_t Gs = 1;
+    while (Gs * 2 <= t_max && Gs * 16 <= chunks) Gs <<= 1;                          // about 8..16 loads per lane
+    while (Gs * 2 <= t_max && Gs * 2 <= chunks && m * b * Gs < want_lanes) Gs <<= 1;  // more lanes, down to one load each
+    if (T_forced && Gs > T_forced) Gs = T_forced;
+    if (Gs > kWave && Gs < 256 && !T_forced) Gs = (chunks >= 256 && t_max >= 256) ? 256 : kWave;
+    int T;
+    if (Gs > kWave) {
+        T = (int)Gs;  // a whole workgroup per bucket
+    } else {
+        T = T_forced ? T_forced : 256;
+        if (T > t_max) T = t_max;
+        const int64_t need = ceil_div(b * Gs, kWave) * kWave;  // lanes that cover one row's buckets
+        if (need < T) T = (int)need;
+    }
+    p.Gs = (int)Gs;
+    p.T = T;
+    const int bpw = T / p.Gs;
+    p.bblocks = (int)ceil_div(b, bpw);
+    int64_t S = 1;
+    if (p.Gs == T) {
+        S = want_lanes / (m * b * T);
+        const int64_t s_loads = chunks / ((int64_t)T * 4);  // every lane keeps at least 4 loads
+        if (S > s_loads) S = s_loads;
+    }
+    if (S_forced && p.Gs == T) S = S_forced;
+    if (S > chunks) S = chunks;
+    if (S < 1) S = 1;
+    int64_t cps = ceil_div(chunks, S);
+    S = ceil_div(chunks, cps);
+    p.S = (int)S;
+    p.chunks_per_split = (int)cps;
+    p.use_scratch = (S > 1) || (p.stage2 && p.bblocks > 1);
+    p.direct = false;
+    if (p.stage2 && b * k_b > kStage2MaxCand) return ATK_ERR_UNSUPPORTED;
+    const int64_t lds_xch = (p.Gs > kWave) ? (int64_t)(T / kWave) * p.KB * 8 : 0;
+    const int64_t lds_s2 = p.stage2 ? select_lds_bytes(b * k_b, (int)pow2_ceil(k)) : 0;
+    p.lds_xch_off = 16;
+    p.lds_cand_off = (int)(16 + lds_xch);
+    p.lds_bytes = (int)(16 + lds_xch + lds_s2);
+    if (p.lds_bytes > kLdsBudget) return ATK_ERR_UNSUPPORTED;
+    p.scratch_ticket_bytes = p.use_scratch ? m * kTicketStride * 4 : 0;
+    p.scratch_lists_bytes = p.use_scratch ? m * p.S * b * k_b * 8 : 0;
+    p.grid = m * p.S * p.bblocks;
+    if (p.grid >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
+    *pl = p;
+    return ATK_OK;
+}
+
 int make_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, Plan *pl) {
     return make_plan_aligned(m, n, k, b, k_b, dtype, true, pl);
 }
@@ -328,6 +401,53 @@ int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, i
              pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid,
              (int)pl.stage2, (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
              (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes));
+    return ATK_OK;
+}
+
+int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
+                             char *buf, int64_t buflen) {
+    if (assignment == ATK_INTERLEAVED) return atk_plan_describe(m, n, k, b, k_b, dtype, buf, buflen);
+    if (!buf || buflen < 1) return ATK_ERR_NULL_PTR;
+    if (assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    Plan pl;
+    rc = make_contig_plan(m, n, k, b, k_b, dtype, true, &pl);
+    if (rc != ATK_OK) return rc;
+    snprintf(buf, (size_t)buflen,
+             "contiguous V=%d KB=%d T=%d Gs=%d bblocks=%d S=%d chunks_per_split=%d grid=%lld stage2=%d scratch=%d "
+             "lds=%d scratch_bytes=%lld",
+             pl.V, pl.KB, pl.T, pl.Gs, pl.bblocks, pl.S, pl.chunks_per_split, (long long)pl.grid, (int)pl.stage2,
+             (int)pl.use_scratch, pl.lds_bytes, (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes));
+    return ATK_OK;
+}
+
+int approx_topk_assign(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
+                       int assignment, void *out_vals, int32_t *out_idx, void *stream) {
+    if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    if (assignment != ATK_INTERLEAVED && assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
+    if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
+    Plan pl;
+    const bool ptr16 = ((uintptr_t)x & 15u) == 0;
+    if (assignment == ATK_CONTIGUOUS)
+        rc = make_contig_plan(m, n, k, b, k_b, dtype, ptr16, &pl);
+    else
+        rc = make_plan_aligned(m, n, k, b, k_b, dtype, ptr16, &pl);
+    if (rc != ATK_OK) return rc;
+    void *state = nullptr, *data = nullptr;
+    hipError_t e = get_pool(kPoolState, (size_t)pl.scratch_ticket_bytes, &state);
+    if (e != hipSuccess) return hip_fail(e);
+    e = get_pool(kPoolData, (size_t)pl.scratch_lists_bytes, &data);
+    if (e != hipSuccess) return hip_fail(e);
+    if (assignment == ATK_CONTIGUOUS)
+        e = launch_approx_contig(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
+    else
+        e = launch_approx(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
     return ATK_OK;
 }
 

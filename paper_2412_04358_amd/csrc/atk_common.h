@@ -33,6 +33,14 @@ constexpr int max_threads_for_kb(int KB) { return KB <= 4 ? 1024 : 256; }
     X(ATK_BF16, 2, 8, 4)  X(ATK_BF16, 4, 8, 2)  X(ATK_BF16, 1, 8, 4)  \
     X(ATK_BF16, 2, 16, 2) X(ATK_BF16, 1, 16, 2)
 
+// Instances of the contiguous-assignment kernel: X(element type, elements per load V, slots KB,
+// load batches U).  V is a full 16-byte load when the buckets allow it, else 1.
+#define ATK_CONTIG_INSTANCES(X) \
+    X(ATK_F32, 4, 1, 8)  X(ATK_F32, 4, 2, 4)  X(ATK_F32, 4, 4, 4)  X(ATK_F32, 4, 8, 2)  X(ATK_F32, 4, 16, 2)  \
+    X(ATK_F32, 1, 1, 16) X(ATK_F32, 1, 2, 8)  X(ATK_F32, 1, 4, 8)  X(ATK_F32, 1, 8, 4)  X(ATK_F32, 1, 16, 2)  \
+    X(ATK_BF16, 8, 1, 8) X(ATK_BF16, 8, 2, 4) X(ATK_BF16, 8, 4, 4) X(ATK_BF16, 8, 8, 2) X(ATK_BF16, 8, 16, 2) \
+    X(ATK_BF16, 1, 1, 16) X(ATK_BF16, 1, 2, 8) X(ATK_BF16, 1, 4, 8) X(ATK_BF16, 1, 8, 4) X(ATK_BF16, 1, 16, 2)
+
 // Columns per lane for (dtype, KB): the first listed instance whose V divides both b and n, so
 // that every V-element load is naturally aligned (and equals `want`, when that is not 0).
 inline int stage1_pick_v(int dtype, int KB, int want, int64_t b, int64_t n) {
@@ -75,6 +83,11 @@ struct Plan {
     bool wave_merge;  // Gw < 64 and a power of two: lanes of a wavefront share columns, merged by shuffles
     int nparts;       // partial lists per column left for the LDS exchange
     int lds_xch_off, lds_cand_off;
+    // contiguous assignment (floor(b*i/n)) only
+    int assignment;   // ATK_INTERLEAVED / ATK_CONTIGUOUS
+    int Gs;           // lanes side by side on one bucket (a power of two)
+    int bblocks;      // workgroups side by side across the b buckets
+    int chunks_per_split;  // V-element chunks of a bucket per row split
     int64_t scratch_lists_bytes;   // composites
     int64_t scratch_ticket_bytes;  // one counter per row
     int lds_bytes;    // dynamic LDS of the launch
@@ -82,11 +95,15 @@ struct Plan {
 };
 
 int make_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, Plan *plan);
+int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, bool ptr16, Plan *plan);
 
 // Enqueue the fused Stage 1 (+ merge, + Stage 2) kernel for `plan`.
 // state: zeroed words (tickets); data: partial lists.
 hipError_t launch_approx(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state, void *data,
                          hipStream_t stream);
+// The same for a plan of make_contig_plan().
+hipError_t launch_approx_contig(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state,
+                                void *data, hipStream_t stream);
 
 // ------------------------------------------------------------------------------------
 // exact_topk plan

@@ -169,7 +169,7 @@ __device__ void order_write(u64 *sel, int k, uint32_t *rk, void *out_vals, int32
         // rank = number of larger survivors; iw lanes side by side take one survivor each and
         // the T/iw groups of lanes split the range of partners
         int iw = kWave, iw_shift = 6;
-        while (iw < k && iw < T) {
+        while (iw < k && iw * 2 <= T) {  // iw divides into T, also when T is not a power of two
             iw <<= 1;
             ++iw_shift;
         }

@@ -37,6 +37,11 @@ struct S1Params {
     int lds_xch_off, lds_cand_off;  // byte offsets of the exchange and candidate areas in LDS
     int cb_shift, s_shift, gw_shift;  // log2 of colblocks, S, Gw when those are powers of two, else -1
     int fence_sync;      // debugging aid: add full agent-scope fences around the ticket
+    int wgs_per_row;     // workgroups that share one row's ticket
+    // contiguous assignment only
+    int Gs, gs_shift;    // lanes per bucket (a power of two) and its log2
+    int bblocks;         // workgroups side by side across the b buckets
+    int chunks_per_split;
 };
 
 template <int ELT, int V>
@@ -128,6 +133,99 @@ __device__ __forceinline__ void scan_vec(float (&val)[V][KB], int (&tt)[V][KB], 
     }
 #pragma unroll
     for (int e = 0; e < V; ++e) insert<KB>(val[e], tt[e], x[e], t);
+}
+
+// Stage-1 result of bucket `col`, as seen by row split `sp` of row r: to the scratch lists (when
+// several workgroups share the row), to the candidate area in LDS (Stage 2 inside this
+// workgroup), or straight to the output.
+template <int ELT, int KB>
+__device__ __forceinline__ void emit_list(const S1Params &p, int r, int sp, int col, const u64 (&list)[KB], u64 *cand) {
+    if (p.use_scratch) {
+        // agent-scope atomic stores: written through to memory, not left in this XCD's L2
+        u64 *dst = p.lists + (((int64_t)r * p.S + sp) * p.b + col) * p.k_b;
+#pragma unroll
+        for (int j = 0; j < KB; ++j)
+            if (j < p.k_b) __hip_atomic_store(&dst[j], list[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (p.stage2) {
+#pragma unroll
+        for (int j = 0; j < KB; ++j)
+            if (j < p.k_b) cand[col * p.k_b + j] = list[j];
+    } else {
+        const int64_t o = (int64_t)r * p.k + (int64_t)col * p.k_b;
+#pragma unroll
+        for (int j = 0; j < KB; ++j)
+            if (j < p.k_b) write_composite<ELT>(list[j], p.out_vals, p.out_idx, o + j);
+    }
+}
+
+// What follows the last emit_list() of a workgroup: the hand-over between the workgroups of a
+// row (ticket; the last one merges the row splits) and Stage 2.  Every thread calls it.
+template <int ELT, int KB>
+__device__ __forceinline__ void row_tail(const S1Params &p, int r, unsigned char *smem) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    u64 *cand = (u64 *)(smem + p.lds_cand_off);
+    if (!p.use_scratch) {
+        if (!p.stage2) return;
+        __syncthreads();
+    } else {
+        // ------------------------------------------------------------ ticket
+        // Cross-workgroup hand-over without cache-wide fences: the lists were written, and are
+        // read below, with agent-scope atomic accesses (they go through to memory instead of
+        // staying in one XCD's L2); the barrier waits until this workgroup's stores have been
+        // acknowledged, and only then one lane takes the row's ticket.  Whoever draws the
+        // last ticket knows that every other workgroup's lists are complete.
+        if (p.fence_sync) __threadfence();
+        __syncthreads();
+        uint32_t *flag = (uint32_t *)smem;
+        if (tid == 0) {
+            uint32_t ticket = __hip_atomic_fetch_add(&p.tickets[(int64_t)r * kTicketStride], 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+            flag[0] = (ticket == (uint32_t)(p.wgs_per_row - 1)) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (flag[0] == 0) return;
+        if (p.fence_sync) __threadfence();
+        if (tid == 0)  // ready for the next call
+            __hip_atomic_store(&p.tickets[(int64_t)r * kTicketStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+        // the last workgroup of the row merges the splits of every column; the loads of SU
+        // splits are in flight together
+        constexpr int SU = (KB <= 2) ? 8 : (KB <= 4 ? 4 : 2);
+        const u64 *src = p.lists + (int64_t)r * p.S * p.b * p.k_b;
+        for (int col = tid; col < p.b; col += T) {
+            u64 acc[KB];
+#pragma unroll
+            for (int j = 0; j < KB; ++j) acc[j] = 0ull;
+            for (int s0 = 0; s0 < p.S; s0 += SU) {
+                u64 th[SU][KB];
+#pragma unroll
+                for (int u = 0; u < SU; ++u)
+#pragma unroll
+                    for (int j = 0; j < KB; ++j)
+                        th[u][j] = (s0 + u < p.S && j < p.k_b)
+                                       ? __hip_atomic_load(&src[((int64_t)(s0 + u) * p.b + col) * p.k_b + j],
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                       : 0ull;
+#pragma unroll
+                for (int u = 0; u < SU; ++u) merge_topk<KB>(acc, th[u]);
+            }
+            if (p.stage2) {
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j < p.k_b) cand[col * p.k_b + j] = acc[j];
+            } else {
+                const int64_t o = (int64_t)r * p.k + (int64_t)col * p.k_b;
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j < p.k_b) write_composite<ELT>(acc[j], p.out_vals, p.out_idx, o + j);
+            }
+        }
+        if (!p.stage2) return;
+        __syncthreads();
+    }
+
+    // ---------------------------------------------------------------- Stage 2 in LDS
+    select_write<ELT>(cand, p.b * p.k_b, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r);
 }
 
 template <int ELT, int V, int KB, int U, int MAXT>
@@ -272,26 +370,7 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 
     // ---------------------------------------------------------------- where finished lists go
     u64 *cand = (u64 *)(smem + p.lds_cand_off);
-    const int n_cand = p.b * p.k_b;
-    // Stage-1 result of bucket `col` of this workgroup's share of the row
-    auto emit = [&](int col, const u64(&list)[KB]) {
-        if (p.use_scratch) {
-            // agent-scope atomic stores: written through to memory, not left in this XCD's L2
-            u64 *dst = p.lists + (((int64_t)r * p.S + sp) * p.b + col) * p.k_b;
-#pragma unroll
-            for (int j = 0; j < KB; ++j)
-                if (j < p.k_b) __hip_atomic_store(&dst[j], list[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else if (p.stage2) {
-#pragma unroll
-            for (int j = 0; j < KB; ++j)
-                if (j < p.k_b) cand[col * p.k_b + j] = list[j];
-        } else {
-            const int64_t o = (int64_t)r * p.k + (int64_t)col * p.k_b;
-#pragma unroll
-            for (int j = 0; j < KB; ++j)
-                if (j < p.k_b) write_composite<ELT>(list[j], p.out_vals, p.out_idx, o + j);
-        }
-    };
+    auto emit = [&](int col, const u64(&list)[KB]) { emit_list<ELT, KB>(p, r, sp, col, list, cand); };
 
     // ---------------------------------------------------------------- merge across wavefronts (LDS, one barrier)
     if (p.nparts > 1) {
@@ -324,68 +403,112 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
         for (int e = 0; e < V; ++e) emit(col0 + e, comp[e]);
     }
 
-    if (!p.use_scratch) {
-        if (!p.stage2) return;
-        __syncthreads();
-    } else {
-        // ------------------------------------------------------------ ticket
-        // Cross-workgroup hand-over without cache-wide fences: the lists were written, and are
-        // read below, with agent-scope atomic accesses (they go through to memory instead of
-        // staying in one XCD's L2); the barrier waits until this workgroup's stores have been
-        // acknowledged, and only then one lane takes the row's ticket.  Whoever draws the
-        // last ticket knows that every other workgroup's lists are complete.
-        if (p.fence_sync) __threadfence();
-        __syncthreads();
-        uint32_t *flag = (uint32_t *)smem;
-        if (tid == 0) {
-            uint32_t ticket = __hip_atomic_fetch_add(&p.tickets[(int64_t)r * kTicketStride], 1u, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-            flag[0] = (ticket == (uint32_t)(p.S * p.colblocks - 1)) ? 1u : 0u;
-        }
-        __syncthreads();
-        if (flag[0] == 0) return;
-        if (p.fence_sync) __threadfence();
-        if (tid == 0)  // ready for the next call
-            __hip_atomic_store(&p.tickets[(int64_t)r * kTicketStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    row_tail<ELT, KB>(p, r, smem);
+}
 
-        // the last workgroup of the row merges the splits of every column; the loads of SU
-        // splits are in flight together
-        constexpr int SU = (KB <= 2) ? 8 : (KB <= 4 ? 4 : 2);
-        const u64 *src = p.lists + (int64_t)r * p.S * p.b * p.k_b;
-        for (int col = tid; col < p.b; col += T) {
-            u64 acc[KB];
+// ------------------------------------------------------------------------------------------------
+// Contiguous assignment (Appendix A.1): bucket j is the run of elements i with floor(b*i/n) = j,
+// that is [ceil(j*n/b), ceil((j+1)*n/b)).  Gs lanes side by side share a bucket: lane q reads the
+// V-element chunks q, q+Gs, q+2Gs, ... of the run (consecutive lanes, consecutive addresses) into
+// one queue, and the Gs queues are merged by a butterfly of shuffles (and, when a bucket takes
+// more than one wavefront, once through LDS).  Long buckets of small batches are also split
+// over S workgroups.  From the finished per-bucket lists on, everything is shared with the
+// interleaved kernel (emit_list, row_tail).
+// V > 1 is used only when every bucket has the same length L = n/b, V divides L and the rows
+// are aligned; otherwise V = 1 and the runs may differ in length by one.
+template <int ELT, int V, int KB, int U, int MAXT>
+__global__ void __launch_bounds__(MAXT) contig_kernel(S1Params p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int ES = (ELT == ATK_F32) ? 4 : 2;
+    const int tid = threadIdx.x, T = blockDim.x;
+    int wg = blockIdx.x, bb, sp, r;
+    divmod(wg, p.bblocks, -1, wg, bb);
+    divmod(wg, p.S, p.s_shift, r, sp);
+    const int g = tid >> p.gs_shift, q = tid & (p.Gs - 1);
+    const int bpw = T >> p.gs_shift;  // buckets per workgroup
+    const int j = bb * bpw + g;       // this lane's bucket
+    const bool active = j < p.b;
+
+    float val[KB];
+    int tt[KB];
 #pragma unroll
-            for (int j = 0; j < KB; ++j) acc[j] = 0ull;
-            for (int s0 = 0; s0 < p.S; s0 += SU) {
-                u64 th[SU][KB];
-#pragma unroll
-                for (int u = 0; u < SU; ++u)
-#pragma unroll
-                    for (int j = 0; j < KB; ++j)
-                        th[u][j] = (s0 + u < p.S && j < p.k_b)
-                                       ? __hip_atomic_load(&src[((int64_t)(s0 + u) * p.b + col) * p.k_b + j],
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                       : 0ull;
-#pragma unroll
-                for (int u = 0; u < SU; ++u) merge_topk<KB>(acc, th[u]);
-            }
-            if (p.stage2) {
-#pragma unroll
-                for (int j = 0; j < KB; ++j)
-                    if (j < p.k_b) cand[col * p.k_b + j] = acc[j];
-            } else {
-                const int64_t o = (int64_t)r * p.k + (int64_t)col * p.k_b;
-#pragma unroll
-                for (int j = 0; j < KB; ++j)
-                    if (j < p.k_b) write_composite<ELT>(acc[j], p.out_vals, p.out_idx, o + j);
-            }
-        }
-        if (!p.stage2) return;
-        __syncthreads();
+    for (int i = 0; i < KB; ++i) {
+        val[i] = __uint_as_float(0x7fc00000u);
+        tt[i] = kEmptyT;
     }
+    // the run of bucket j, in elements of the row
+    int64_t run0 = 0, run1 = 0;
+    if (active) {
+        run0 = ((int64_t)j * p.n + p.b - 1) / p.b;
+        run1 = ((int64_t)(j + 1) * p.n + p.b - 1) / p.b;
+    }
+    if (active) {
+        const int chunks = (int)((run1 - run0) / V);
+        const int c0 = sp * p.chunks_per_split;
+        const int c1 = min(chunks, c0 + p.chunks_per_split);
+        const unsigned char *base = (const unsigned char *)p.x + ((int64_t)r * p.n + run0) * ES;
+        auto feed = [&](const RowVec<ELT, V> &v, int c) {
+            float x[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) x[e] = __uint_as_float(elem_bits<ELT, V>(v, e));
+            if (KB > 1) {
+                bool any = false;
+#pragma unroll
+                for (int e = 0; e < V; ++e) any = any || !(x[e] <= val[KB - 1]);
+                if (__ballot(any) == 0ull) return;
+            }
+#pragma unroll
+            for (int e = 0; e < V; ++e) insert<KB>(val, tt, x[e], c * V + e);
+        };
+        int c = c0 + q;
+        for (; c + (U - 1) * p.Gs < c1; c += U * p.Gs) {
+            RowVec<ELT, V> v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(c + u * p.Gs) * (V * ES));
+#pragma unroll
+            for (int u = 0; u < U; ++u) feed(v[u], c + u * p.Gs);
+        }
+        for (; c < c1; c += p.Gs) {
+            RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)c * (V * ES));
+            feed(v, c);
+        }
+    }
+    u64 comp[KB];
+#pragma unroll
+    for (int i = 0; i < KB; ++i)
+        comp[i] = (tt[i] != kEmptyT) ? make_composite(__float_as_uint(val[i]), (int32_t)(run0 + tt[i])) : 0ull;
 
-    // ---------------------------------------------------------------- Stage 2 in LDS
-    select_write<ELT>(cand, n_cand, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r);
+    // ---- merge the Gs queues of a bucket: butterfly inside the wavefront ...
+    const int span = p.Gs < kWave ? p.Gs : kWave;
+    for (int off = 1; off < span; off <<= 1) {
+        u64 theirs[KB];
+#pragma unroll
+        for (int i = 0; i < KB; ++i) theirs[i] = shfl_xor_u64(comp[i], off);
+        merge_topk<KB>(comp, theirs);
+    }
+    // ... and across the wavefronts of the workgroup when the bucket owns all of it
+    if (p.Gs > kWave) {
+        u64 *xch = (u64 *)(smem + p.lds_xch_off);  // [wavefront][slot]
+        const int lane = tid & (kWave - 1), wave = tid >> 6, n_waves = T >> 6;
+        if (lane == 0) {
+#pragma unroll
+            for (int i = 0; i < KB; ++i) xch[wave * KB + i] = comp[i];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int i = 0; i < KB; ++i) comp[i] = (lane < n_waves) ? xch[lane * KB + i] : 0ull;
+            for (int off = 1; off < n_waves; off <<= 1) {
+                u64 theirs[KB];
+#pragma unroll
+                for (int i = 0; i < KB; ++i) theirs[i] = shfl_xor_u64(comp[i], off);
+                merge_topk<KB>(comp, theirs);
+            }
+        }
+    }
+    u64 *cand = (u64 *)(smem + p.lds_cand_off);
+    if (active && q == 0) emit_list<ELT, KB>(p, r, sp, j, comp, cand);
+    row_tail<ELT, KB>(p, r, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -408,6 +531,7 @@ static int log2_exact(int v) {
 hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state, void *data,
                          hipStream_t stream) {
     S1Params prm;
+    memset(&prm, 0, sizeof prm);
     prm.x = x;
     prm.out_vals = out_vals;
     prm.out_idx = out_idx;
@@ -435,6 +559,7 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.nparts = pl.nparts;
     prm.lds_xch_off = pl.lds_xch_off;
     prm.lds_cand_off = pl.lds_cand_off;
+    prm.wgs_per_row = pl.S * pl.colblocks;
     prm.cb_shift = log2_exact(pl.colblocks);
     prm.s_shift = log2_exact(pl.S);
     prm.gw_shift = log2_exact(pl.Gw);
@@ -447,6 +572,54 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
 #define ATK_CASE(ELT, VV, KK, UU) \
     if (pl.dtype == ELT && pl.V == VV && pl.KB == KK) return launch_one<ELT, VV, KK, UU>(pl, prm, stream);
     ATK_STAGE1_INSTANCES(ATK_CASE)
+#undef ATK_CASE
+    return hipErrorInvalidValue;
+}
+
+template <int ELT, int V, int KB, int U>
+static hipError_t launch_contig_one(const Plan &pl, const S1Params &prm, hipStream_t stream) {
+    constexpr int MAXT = max_threads_for_kb(KB);
+    if (pl.T > MAXT) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((contig_kernel<ELT, V, KB, U, MAXT>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T),
+                       (size_t)pl.lds_bytes, stream, prm);
+    return hipGetLastError();
+}
+
+hipError_t launch_approx_contig(const Plan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state,
+                                void *data, hipStream_t stream) {
+    S1Params prm;
+    memset(&prm, 0, sizeof prm);
+    prm.x = x;
+    prm.out_vals = out_vals;
+    prm.out_idx = out_idx;
+    prm.tickets = (uint32_t *)state;
+    prm.lists = (u64 *)data;
+    prm.n = pl.n;
+    prm.b = (int)pl.b;
+    prm.L = (int)pl.L;
+    prm.S = pl.S;
+    prm.s_shift = log2_exact(pl.S);
+    prm.idx_bits = 1;
+    while (((int64_t)1 << prm.idx_bits) < pl.n) ++prm.idx_bits;
+    prm.k = (int)pl.k;
+    prm.k_b = pl.k_b;
+    prm.stage2 = pl.stage2;
+    prm.use_scratch = pl.use_scratch;
+    prm.lds_xch_off = pl.lds_xch_off;
+    prm.lds_cand_off = pl.lds_cand_off;
+    prm.wgs_per_row = pl.S * pl.bblocks;
+    prm.Gs = pl.Gs;
+    prm.gs_shift = log2_exact(pl.Gs);
+    prm.bblocks = pl.bblocks;
+    prm.chunks_per_split = pl.chunks_per_split;
+    {
+        const char *e = getenv("ATK_SYNC");
+        prm.fence_sync = (e && strcmp(e, "fence") == 0) ? 1 : 0;
+    }
+    if (prm.gs_shift < 0) return hipErrorInvalidValue;
+#define ATK_CASE(ELT, VV, KK, UU) \
+    if (pl.dtype == ELT && pl.V == VV && pl.KB == KK) return launch_contig_one<ELT, VV, KK, UU>(pl, prm, stream);
+    ATK_CONTIG_INSTANCES(ATK_CASE)
 #undef ATK_CASE
     return hipErrorInvalidValue;
 }

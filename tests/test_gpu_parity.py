@@ -31,19 +31,21 @@ def as_bits(t):
     return a.view(torch.int16).numpy().view(np.uint16)
 
 
-def run_case(x_cpu, k, b, k_b, rows=None, tag=""):
+def run_case(x_cpu, k, b, k_b, rows=None, tag="", assignment=None):
     print("case %s shape=%s dtype=%s k=%d b=%d k_b=%d plan=[%s]" % (
         tag, tuple(x_cpu.shape), x_cpu.dtype, k, b, k_b,
         atk.plan_describe(x_cpu.shape[0], x_cpu.shape[1], k, b, k_b,
-                          atk.ATK_F32 if x_cpu.dtype == torch.float32 else atk.ATK_BF16)), flush=True)
+                          atk.ATK_F32 if x_cpu.dtype == torch.float32 else atk.ATK_BF16,
+                          assignment or atk.ATK_INTERLEAVED)), flush=True)
     xg = x_cpu.cuda()
-    vals, idx = atk.approx_topk(xg, k, b, k_b)
+    vals, idx = atk.approx_topk(xg, k, b, k_b, assignment=assignment)
     torch.cuda.synchronize()
     gv, gi = as_bits(vals), idx.cpu().numpy()
     xo = workloads.as_numpy_bits(x_cpu)
     if rows is not None:
         xo, gv, gi = xo[rows], gv[rows], gi[rows]
-    ov, oi = oracle.approx_topk(xo, k, b, k_b, threads=THREADS)
+    ov, oi = oracle.approx_topk(xo, k, b, k_b, threads=THREADS,
+                                assignment=oracle.CONTIGUOUS if assignment == atk.ATK_CONTIGUOUS else oracle.INTERLEAVED)
     ovb = ov.view(np.uint32) if ov.dtype == np.float32 else ov
     if not np.array_equal(gi, oi):
         bad = np.argwhere(gi != oi)
@@ -187,6 +189,87 @@ def test_forced_lane_widths(lanes, monkeypatch):
         for dtype in ["f32", "bf16"]:
             x = workloads.normal_rows(m, n, seed=300 + i, dtype=dtype)
             run_case(x, k, b, k_b, tag=lanes)
+
+
+# ------------------------------------------------------------------------------- contiguous assignment
+CONTIG_SHAPES = [
+    # (m, n, k, b, k_b)
+    (4, 4096, 64, 64, 1),          # a wavefront's worth of vector chunks per bucket
+    (4, 4096, 48, 64, 1),          # ... with Stage 2
+    (128, 65536, 64, 64, 1),       # cfg2's shape
+    (128, 65536, 64, 1024, 1),
+    (64, 65536, 16384, 16384, 1),  # bucket = one 16-byte load
+    (64, 65536, 16384, 4096, 4),
+    (8, 65536, 16384, 1024, 16),
+    (3, 12288, 96, 96, 1),         # b not a power of two
+    (2, 4098, 6, 6, 1),            # n % b != 0: runs of unequal length, scalar loads
+    (2, 4098, 683, 683, 1),
+    (5, 1001, 45, 15, 3),
+    (2, 70001, 250, 250, 1),
+    (2, 20004, 100, 96, 3),
+    (5, 8192, 1, 1, 1),            # one bucket: the whole workgroup on it
+    (2, 8192, 16, 1, 16),
+    (1, 1 << 20, 64, 8, 8),        # long buckets, split over workgroups
+    (1, 1 << 20, 64, 64, 1),
+    (1, 1 << 20, 50, 64, 2),
+    (3, 1 << 18, 256, 32, 8),
+    (2, 16384, 16384, 1024, 16),   # k_b = n/b: every bucket fully sorted
+    (2, 16384, 16384, 16384, 1),   # identity
+    (1, 128256, 256, 512, 1),      # vocabulary-sized row
+    (1, 128256, 256, 1000, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_contiguous_assignment(dtype):
+    for i, (m, n, k, b, k_b) in enumerate(CONTIG_SHAPES):
+        x = workloads.normal_rows(m, n, seed=400 + i, dtype=dtype)
+        run_case(x, k, b, k_b, tag="contig%d" % i, assignment=atk.ATK_CONTIGUOUS)
+    # ties: the lowest index wins inside a run and in Stage 2
+    for k, b, k_b in [(64, 64, 1), (40, 64, 2), (128, 8, 16)]:
+        run_case(workloads.few_levels(3, 8192, levels=3, seed=1, dtype=dtype), k, b, k_b, tag="contig 3 levels",
+                 assignment=atk.ATK_CONTIGUOUS)
+        run_case(workloads.special_values(3, 8192, seed=3, dtype=dtype), k, b, k_b, tag="contig specials",
+                 assignment=atk.ATK_CONTIGUOUS)
+
+
+@pytest.mark.parametrize("plan", ["T=64", "T=128,S=3", "T=256,S=16", "T=1024,S=2", "V=1"])
+def test_contiguous_forced_plans(plan, monkeypatch):
+    monkeypatch.setenv("ATK_PLAN", plan)
+    for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (2, 1 << 17, 16, 4, 4),
+                                           (2, 1 << 17, 10, 2, 8), (3, 32768, 2048, 2048, 1)]):
+        for dtype in ["f32", "bf16"]:
+            x = workloads.normal_rows(m, n, seed=500 + i, dtype=dtype)
+            run_case(x, k, b, k_b, tag="contig " + plan, assignment=atk.ATK_CONTIGUOUS)
+
+
+def test_correlated_sequence_simulation_on_the_gpu():
+    """Appendix A.1's simulation (n = 2048, k = 256, Sigma_ij = rho^|i-j|) through the library:
+    recall against the library's exact_topk, equal to what the oracle gives on the same rows."""
+    n, k, rows, rho = 2048, 256, 64, 0.99
+    x = workloads.correlated_rows(rows, n, rho, seed=23)
+    xg = x.cuda()
+    ex = atk.exact_topk(xg, k)[1].cpu().numpy()
+    ex_o = oracle.exact_topk(x.numpy(), k, threads=THREADS)[1]
+    assert np.array_equal(ex, ex_o)
+
+    def rec(idx):
+        return float(np.mean([len(set(a.tolist()) & set(e.tolist())) / k for a, e in zip(idx, ex)]))
+
+    for k_b in (1, 2, 4):
+        b = k // k_b
+        inter = atk.approx_topk(xg, k, b, k_b)[1].cpu().numpy()
+        contig = atk.approx_topk(xg, k, b, k_b, assignment=atk.ATK_CONTIGUOUS)[1].cpu().numpy()
+        assert np.array_equal(contig, oracle.approx_topk(x.numpy(), k, b, k_b, assignment=oracle.CONTIGUOUS)[1])
+        print("rho=%.2f k_b=%d recall interleaved %.3f contiguous %.3f" % (rho, k_b, rec(inter), rec(contig)), flush=True)
+        assert rec(contig) < rec(inter) - 0.3
+
+
+def test_interleaved_flag_is_approx_topk():
+    x = workloads.config_input("cfg1").cuda()
+    a = atk.approx_topk(x, 64, 64, 1)
+    c = atk.approx_topk(x, 64, 64, 1, assignment=atk.ATK_INTERLEAVED)
+    assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
 
 
 # ------------------------------------------------------------------------------- ties and special values

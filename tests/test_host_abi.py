@@ -24,12 +24,12 @@ def declared_functions():
     text = open(os.path.join(ROOT, "include", "approx_topk.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
-    return sorted(set(n for n in names if n.startswith("atk_") or n in ("approx_topk", "exact_topk")))
+    return sorted(set(n for n in names if n.startswith("atk_") or n in ("approx_topk", "approx_topk_assign", "exact_topk")))
 
 
 def test_exports_every_declared_symbol(lib):
     names = declared_functions()
-    assert "approx_topk" in names and "exact_topk" in names and len(names) >= 10
+    assert "approx_topk" in names and "exact_topk" in names and "approx_topk_assign" in names and len(names) >= 12
     for n in names:
         assert hasattr(lib, n), "library does not export %s" % n
 
@@ -132,6 +132,53 @@ def test_plan_shapes(lib):
         assert p["colblocks"] * p["Gw"] * p["V"] >= b
         assert p["S"] * p["rows_per_split"] >= n // b and (p["S"] - 1) * p["rows_per_split"] < n // b
         assert p["T"] % 64 == 0 and p["P"] * p["Gw"] <= p["T"] and p["lds"] <= 65536
+
+
+def parse_contig_plan(s):
+    assert s.startswith("contiguous ")
+    return parse_plan(s[len("contiguous "):])
+
+
+def test_contiguous_plan_shapes(lib):
+    """Launch geometry of the contiguous-assignment kernel covers every bucket and every chunk."""
+    C = atk.ATK_CONTIGUOUS
+    shapes = [(4, 4096, 64, 64, 1), (128, 65536, 64, 64, 1), (128, 65536, 64, 1024, 1), (128, 65536, 16384, 16384, 1),
+              (128, 65536, 16384, 1024, 16), (2, 4098, 6, 6, 1), (2, 4098, 683, 683, 1), (5, 8192, 1, 1, 1),
+              (1, 1 << 20, 64, 8, 8), (1, 1 << 20, 64, 64, 1), (3, 1 << 18, 256, 32, 8), (1, 128256, 256, 1000, 2),
+              (128, 1 << 20, 64, 64, 1), (2048, 8192, 512, 512, 1), (7, 1000, 30, 30, 1), (1, 2653751, 100, 128, 2)]
+    for dt, vfull in ((atk.ATK_F32, 4), (atk.ATK_BF16, 8)):
+        for (m, n, k, b, kb) in shapes:
+            p = parse_contig_plan(atk.plan_describe(m, n, k, b, kb, dt, C))
+            T, Gs = p["T"], p["Gs"]
+            assert T % 64 == 0 and 64 <= T <= 1024 and Gs >= 1 and (Gs & (Gs - 1)) == 0
+            assert Gs <= 64 or Gs == T
+            assert p["V"] in (1, vfull)
+            if p["V"] > 1:
+                assert n % b == 0 and (n // b) % p["V"] == 0
+            chunks = -(-n // b) // p["V"]
+            assert p["bblocks"] * (T // Gs) >= b
+            assert p["S"] * p["chunks_per_split"] >= chunks and (p["S"] - 1) * p["chunks_per_split"] < chunks
+            assert p["S"] == 1 or Gs == T
+            assert p["grid"] == m * p["S"] * p["bblocks"]
+            assert p["lds"] <= 65536
+            assert p["scratch"] == int(p["S"] > 1 or (p["stage2"] == 1 and p["bblocks"] > 1))
+    # a short run per bucket: one lane each, written straight out
+    p = parse_contig_plan(atk.plan_describe(128, 65536, 16384, 16384, 1, atk.ATK_F32, C))
+    assert p["Gs"] == 1 and p["V"] == 4 and p["scratch"] == 0
+    # one long row, few buckets: whole workgroups per bucket and row splits
+    p = parse_contig_plan(atk.plan_describe(1, 1 << 20, 64, 8, 8, atk.ATK_F32, C))
+    assert p["Gs"] == p["T"] and p["S"] > 1 and p["scratch"] == 1
+
+
+def test_assign_argument_checks(lib):
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.approx_topk_assign(fake, 4, 4096, 64, 64, 1, 0, 2, fake, fake, None) == PARAMS
+    assert lib.approx_topk_assign(fake, 4, 4096, 64, 64, 1, 0, -1, fake, fake, None) == PARAMS
+    assert lib.approx_topk_assign(None, 4, 4096, 64, 64, 1, 0, 1, fake, fake, None) == NULLP
+    assert lib.approx_topk_assign(fake, 4, 4096, 64, 32, 1, 0, 1, fake, fake, None) == PARAMS
+    buf = ctypes.create_string_buffer(256)
+    assert lib.atk_plan_describe_assign(4, 4096, 64, 64, 1, 0, 3, buf, 256) == PARAMS
+    assert lib.atk_plan_describe_assign(4, 4096, 64, 64, 1, 0, 0, buf, 256) == OK and buf.value.startswith(b"V=")
 
 
 def test_plan_override_env(lib, monkeypatch):
