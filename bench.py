@@ -189,9 +189,14 @@ def main():
                 oracle.approx_topk(xs, K, b, 1, threads=threads)
             reps += 1
         dt = time.perf_counter() - t0
+        t1 = time.perf_counter()
+        for b in SWEEP_B:  # the same on one core, 4 rows
+            oracle.approx_topk(xs[:4], K, b, 1, threads=1)
+        dt1 = time.perf_counter() - t1
         cpu = {"value": round(reps * len(SWEEP_B) * min_bytes(rows, N, K) / dt / 1e9, 4), "unit": "GB/s",
                "cores": threads, "kind": "oracle",
-               "sample": "%d of the %d rows, the same 5-value b sweep, %d repetitions in %.1f s" % (rows, M, reps, dt)}
+               "sample": "%d of the %d rows, the same 5-value b sweep, %d repetitions in %.1f s" % (rows, M, reps, dt),
+               "single_core_value": round(len(SWEEP_B) * min_bytes(4, N, K) / dt1 / 1e9, 4)}
 
     out = {
         "metric": "total bandwidth GB/s (min bytes / runtime), m=128 float32",
@@ -220,6 +225,41 @@ def main():
     print(json.dumps(out))
 
 
+def _time_us(torch, launch, reps, warm=5):
+    """Average microseconds per launch of `reps` back-to-back launch(i) calls between two events."""
+    for i in range(warm):
+        launch(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        launch(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def _approx_entry(atk, torch, dev, ring, m, n, k, b, k_b, dt, es, reps, assignment=None):
+    ov = torch.empty((m, k), dtype=ring[0].dtype, device=dev)
+    oi = torch.empty((m, k), dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def launch(i):
+        x = ring[i % len(ring)]
+        if assignment is None:
+            rc = atk.approx_topk_raw(x.data_ptr(), m, n, k, b, k_b, dt, ov.data_ptr(), oi.data_ptr(), stream)
+        else:
+            rc = atk.approx_topk_assign_raw(x.data_ptr(), m, n, k, b, k_b, dt, assignment, ov.data_ptr(), oi.data_ptr(),
+                                            stream)
+        assert rc == 0, atk.strerror(rc)
+
+    us = _time_us(torch, launch, reps)
+    nbytes = m * n * es + m * k * (es + 4)
+    return {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+            "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+            "plan": atk.plan_describe(m, n, k, b, k_b, dt, assignment if assignment is not None else atk.ATK_INTERLEAVED)}
+
+
 def detail(atk, workloads, torch, dev):
     """Every configuration of the other sweeps: us per launch (cold where a ring fits), GB/s."""
     res = {}
@@ -236,50 +276,114 @@ def detail(atk, workloads, torch, dev):
             ring = [workloads.attention_scores(seed=s).to(dev) for s in range(nring)]
         else:
             ring = [workloads.normal_rows(m, n, seed=s, dtype=c["dtype"]).to(dev) for s in range(nring)]
+        reps = 50 if name in ("cfg4", "kg") else 200
         for (k, b, k_b) in c["cases"]:
-            ov = torch.empty((m, k), dtype=ring[0].dtype, device=dev)
-            oi = torch.empty((m, k), dtype=torch.int32, device=dev)
-
-            def launch(i):
-                rc = atk.approx_topk_raw(ring[i % nring].data_ptr(), m, n, k, b, k_b, dt, ov.data_ptr(), oi.data_ptr(),
-                                         stream)
-                assert rc == 0, atk.strerror(rc)
-
-            reps = 50 if name in ("cfg4", "kg") else 200
-            for i in range(5):
-                launch(i)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for i in range(reps):
-                launch(i)
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / reps
-            nbytes = m * n * es + m * k * (es + 4)
-            res["%s k=%d b=%d k_b=%d" % (name, k, b, k_b)] = {
-                "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
-                "plan": atk.plan_describe(m, n, k, b, k_b, dt)}
+            res["%s k=%d b=%d k_b=%d" % (name, k, b, k_b)] = _approx_entry(atk, torch, dev, ring, m, n, k, b, k_b, dt, es, reps)
         if name == "cfg4":
             # the exact comparison point on the same rows (Section 4.1 compares against exact top-k)
             for k in (64, 1 << 18):
                 ov = torch.empty((m, k), dtype=ring[0].dtype, device=dev)
                 oi = torch.empty((m, k), dtype=torch.int32, device=dev)
-                for i in range(2):
+
+                def launch(i):
                     assert atk.exact_topk_raw(ring[0].data_ptr(), m, n, k, dt, ov.data_ptr(), oi.data_ptr(), stream) == 0
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in range(10):
-                    atk.exact_topk_raw(ring[0].data_ptr(), m, n, k, dt, ov.data_ptr(), oi.data_ptr(), stream)
-                e1.record()
-                torch.cuda.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / 10
+
+                us = _time_us(torch, launch, 10, warm=2)
                 nbytes = m * n * es + m * k * (es + 4)
                 res["cfg4 exact_topk k=%d" % k] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
                                                    "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4), "plan": "exact"}
         del ring
         torch.cuda.empty_cache()
+
+    # ---- row length sweep at the headline setting (Figure 1 left: k=64, k_b=1, b*k_b/k = 1 and 16)
+    for lg in (16, 17, 18, 19, 20):
+        n = 1 << lg
+        nring = max(1, min(12, (420 << 20) // (M * n * 4)))
+        ring = [workloads.normal_rows(M, n, seed=s).to(dev) for s in range(nring)]
+        for b in (64, 1024):
+            res["n=2^%d m=128 k=64 b=%d k_b=1" % (lg, b)] = _approx_entry(atk, torch, dev, ring, M, n, 64, b, 1, atk.ATK_F32, 4, 100)
+        del ring
+        torch.cuda.empty_cache()
+
+    # ---- small batches (Section 5 leaves the batch size open; SparQ decodes with m = 1)
+    for m in (1, 8, 32):
+        for n in (1 << 16, 1 << 20):
+            nring = max(2, min(64, (420 << 20) // (m * n * 4)))
+            ring = [workloads.normal_rows(m, n, seed=s).to(dev) for s in range(nring)]
+            for (k, b, k_b) in [(64, 64, 1), (64, 1024, 1), (n // 8, n // 8, 1), (n // 8, n // 16, 2)]:
+                res["m=%d n=%d k=%d b=%d k_b=%d" % (m, n, k, b, k_b)] = _approx_entry(
+                    atk, torch, dev, ring, m, n, k, b, k_b, atk.ATK_F32, 4, 100)
+            del ring
+            torch.cuda.empty_cache()
+
+    # ---- bf16 versions of the two 128 x 65536 sweeps (Appendix B.1, bfloat16 figure)
+    ring = [workloads.normal_rows(M, N, seed=s, dtype="bf16").to(dev) for s in range(24)]
+    for (k, b, k_b) in workloads.CONFIGS["cfg2"]["cases"] + workloads.CONFIGS["cfg3"]["cases"]:
+        res["bf16 m=128 n=65536 k=%d b=%d k_b=%d" % (k, b, k_b)] = _approx_entry(
+            atk, torch, dev, ring, M, N, k, b, k_b, atk.ATK_BF16, 2, 200)
+    del ring
+    torch.cuda.empty_cache()
+
+    # ---- contiguous against interleaved buckets (Appendix A.1 reports a runtime edge for contiguous)
+    ring = [workloads.normal_rows(M, N, seed=s).to(dev) for s in range(RING)]
+    for (k, b, k_b) in [(64, 64, 1), (64, 1024, 1), (16384, 16384, 1), (16384, 4096, 4)]:
+        res["contiguous m=128 n=65536 k=%d b=%d k_b=%d" % (k, b, k_b)] = _approx_entry(
+            atk, torch, dev, ring, M, N, k, b, k_b, atk.ATK_F32, 4, 200, assignment=atk.ATK_CONTIGUOUS)
+
+    # ---- the paper's timing protocol (Appendix B.1): per launch a sleep kernel, a start event, the call,
+    # a stop event, all queued; 16 warm-up and 512 timed launches; median, minimum and standard error
+    lib = atk.load_library()
+    ov = torch.empty((M, K), dtype=torch.float32, device=dev)
+    oi = torch.empty((M, K), dtype=torch.int32, device=dev)
+    for b in SWEEP_B:
+        def call(i):
+            assert atk.approx_topk_raw(ring[i % RING].data_ptr(), M, N, K, b, 1, atk.ATK_F32, ov.data_ptr(), oi.data_ptr(),
+                                       stream) == 0
+        for i in range(16):
+            call(i)
+        torch.cuda.synchronize()
+        times = []
+        for chunk in range(8):  # 8 x 64 launches, each chunk queued behind its sleep kernels
+            evs = []
+            for i in range(64):
+                lib.atk_sleep(20, stream)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                call(chunk * 64 + i)
+                e1.record()
+                evs.append((e0, e1))
+            torch.cuda.synchronize()
+            times += [a.elapsed_time(z) * 1e3 for a, z in evs]
+        times.sort()
+        mean = sum(times) / len(times)
+        var = sum((t - mean) ** 2 for t in times) / (len(times) - 1)
+        res["protocol b=%d" % b] = {"launches": len(times), "median_us": round(times[len(times) // 2], 2),
+                                    "min_us": round(times[0], 2), "mean_us": round(mean, 2),
+                                    "se_over_mean": round((var / len(times)) ** 0.5 / mean, 5)}
+
+    # ---- the step replayed from a HIP graph (the paper's CUDA-graph variant): launch gaps removed
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        cs = side.cuda_stream
+        for b in SWEEP_B:  # the scratch pool must have its size before capture starts
+            assert atk.approx_topk_raw(ring[0].data_ptr(), M, N, K, b, 1, atk.ATK_F32, ov.data_ptr(), oi.data_ptr(), cs) == 0
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for rep in range(2):
+                for j, b in enumerate(SWEEP_B):
+                    assert atk.approx_topk_raw(ring[(rep * 5 + j) % RING].data_ptr(), M, N, K, b, 1, atk.ATK_F32,
+                                               ov.data_ptr(), oi.data_ptr(), side.cuda_stream) == 0
+    ref = None
+    for rep in range(3):  # every replay gives the last call's result again
+        g.replay()
+        torch.cuda.synchronize()
+        cur = (ov.clone(), oi.clone())
+        assert ref is None or (torch.equal(ref[0], cur[0]) and torch.equal(ref[1], cur[1]))
+        ref = cur
+    us = _time_us(torch, lambda i: g.replay(), 100)
+    res["graph replay"] = {"launches_per_replay": 10, "us_per_launch": round(us / 10, 2),
+                           "GBps": round(min_bytes(M, N, K) / (us / 10) / 1e3, 1)}
     return res
 
 

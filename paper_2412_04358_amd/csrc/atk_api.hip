@@ -1,5 +1,6 @@
 // C ABI of the library (include/approx_topk.h): argument checks, launch planning, the
 // per-device scratch pool, and the measurement utilities.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -109,6 +110,9 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
             while (T > 256 && m * T * 2 > want_threads) T >>= 1;  // keep at least two splits' worth of lanes
         }
     }
+    // many column groups but few rows: smaller workgroups rather than row splits
+    if (p.G > 256)
+        while (T > kWave && m * ceil_div(p.G, T) < (int64_t)kNumCU) T >>= 1;
     if (T_forced) T = T_forced;
     if (T > t_max) T = t_max;
 
@@ -144,6 +148,16 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int64_t s_fill = ceil_div(kNumCU, base);         // splits that give every CU a workgroup
     if (S > s_traffic) S = s_traffic > s_fill ? s_traffic : (S < s_fill ? S : s_fill);  // filling the chip comes first
     if (S > s_rows) S = s_rows;
+    {
+        // The workgroup that draws the last ticket merges S lists per column, SU splits per batch
+        // of loads, tpc lanes per column: keep that serial tail to about four batches.
+        const int64_t tail_cols = p.stage2 ? b : std::min<int64_t>(b, (int64_t)p.Gw * p.V);
+        auto batches = [&](int64_t s) {
+            const int64_t tpc = tail_lanes_per_column(tail_cols, T, p.KB, s);
+            return ceil_div(tail_cols, T / tpc) * ceil_div(s, tpc * tail_split_batch(p.KB));
+        };
+        while (S > 1 && batches(S) > 4) S = (S + 1) / 2;
+    }
     if (S_forced) S = S_forced;
     if (S > p.L / p.P) S = p.L / p.P;
     if (S < 1) S = 1;
@@ -153,6 +167,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.S = (int)S;
     p.rows_per_split = (int)rps;
 
+    p.tail_tpc = tail_lanes_per_column(p.stage2 ? b : std::min<int64_t>(b, (int64_t)p.Gw * p.V), p.T, p.KB, p.S);
     p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
     p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
     if (p.use_scratch && p.stage2) {
@@ -164,7 +179,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         p.lds_bytes = (int)(16 + (lds_xch > lds_s2 ? lds_xch : lds_s2));
     }
 
-    p.scratch_ticket_bytes = p.use_scratch ? m * kTicketStride * 4 : 0;
+    // one ticket per row with Stage 2, else one per (row, column block)
+    p.scratch_ticket_bytes = p.use_scratch ? m * (p.stage2 ? 1 : p.colblocks) * kTicketStride * 4 : 0;
     p.scratch_lists_bytes = p.use_scratch ? m * p.S * b * k_b * 8 : 0;
     p.grid = m * p.S * p.colblocks;
     if (p.grid >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
@@ -229,6 +245,7 @@ int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, in
     p.S = (int)S;
     p.chunks_per_split = (int)cps;
     p.use_scratch = (S > 1) || (p.stage2 && p.bblocks > 1);
+    p.tail_tpc = tail_lanes_per_column(p.stage2 ? b : std::min<int64_t>(b, bpw), T, p.KB, S);
     p.direct = false;
     if (p.stage2 && b * k_b > kStage2MaxCand) return ATK_ERR_UNSUPPORTED;
     const int64_t lds_xch = (p.Gs > kWave) ? (int64_t)(T / kWave) * p.KB * 8 : 0;
@@ -237,7 +254,7 @@ int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, in
     p.lds_cand_off = (int)(16 + lds_xch);
     p.lds_bytes = (int)(16 + lds_xch + lds_s2);
     if (p.lds_bytes > kLdsBudget) return ATK_ERR_UNSUPPORTED;
-    p.scratch_ticket_bytes = p.use_scratch ? m * kTicketStride * 4 : 0;
+    p.scratch_ticket_bytes = p.use_scratch ? m * (p.stage2 ? 1 : p.bblocks) * kTicketStride * 4 : 0;
     p.scratch_lists_bytes = p.use_scratch ? m * p.S * b * k_b * 8 : 0;
     p.grid = m * p.S * p.bblocks;
     if (p.grid >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;

@@ -55,6 +55,15 @@ constexpr int kLdsBudget = 64 * 1024;     // static+dynamic LDS per workgroup we
 constexpr int kNumCU = 256;               // MI355X
 constexpr int kTicketStride = 32;          // words between row tickets: one 128-byte line each, so that
                                           // atomics of different rows do not queue up on one line
+// Row splits whose lists the merging workgroup loads together (per lane), by slots per column.
+constexpr int tail_split_batch(int KB) { return KB <= 2 ? 8 : (KB <= 4 ? 4 : 2); }
+// Lanes side by side on one column in that merge: a power of two up to 64 such that all
+// `cols` columns still fit the T lanes, and no more than there are batches of splits.
+inline int tail_lanes_per_column(int64_t cols, int T, int KB, int64_t S) {
+    int tpc = 1;
+    while (tpc * 2 <= kWave && (int64_t)tpc * 2 * cols <= T && (int64_t)tpc * tail_split_batch(KB) < S) tpc <<= 1;
+    return tpc;
+}
 constexpr int kEmptyT = 0x7fffffff;       // "no element yet" row marker of a register slot
 
 // ------------------------------------------------------------------------------------
@@ -84,6 +93,7 @@ struct Plan {
     int nparts;       // partial lists per column left for the LDS exchange
     int lds_xch_off, lds_cand_off;
     // contiguous assignment (floor(b*i/n)) only
+    int tail_tpc;     // lanes per column in the last workgroup's merge of the row splits
     int assignment;   // ATK_INTERLEAVED / ATK_CONTIGUOUS
     int Gs;           // lanes side by side on one bucket (a power of two)
     int bblocks;      // workgroups side by side across the b buckets

@@ -37,7 +37,8 @@ struct S1Params {
     int lds_xch_off, lds_cand_off;  // byte offsets of the exchange and candidate areas in LDS
     int cb_shift, s_shift, gw_shift;  // log2 of colblocks, S, Gw when those are powers of two, else -1
     int fence_sync;      // debugging aid: add full agent-scope fences around the ticket
-    int wgs_per_row;     // workgroups that share one row's ticket
+    int tail_tpc_shift;  // log2 of the lanes that share a column in the last workgroup's merge
+    int wgs_per_ticket;  // workgroups that share a ticket: a row's (Stage 2), else a column block's row splits
     // contiguous assignment only
     int Gs, gs_shift;    // lanes per bucket (a power of two) and its log2
     int bblocks;         // workgroups side by side across the b buckets
@@ -158,10 +159,13 @@ __device__ __forceinline__ void emit_list(const S1Params &p, int r, int sp, int 
     }
 }
 
-// What follows the last emit_list() of a workgroup: the hand-over between the workgroups of a
-// row (ticket; the last one merges the row splits) and Stage 2.  Every thread calls it.
+// What follows the last emit_list() of a workgroup: the hand-over between the workgroups that
+// share a ticket, and Stage 2.  Every thread calls it.
+// With Stage 2 the whole row shares one ticket (one workgroup must see all b*k_b candidates);
+// without it every block of columns [c_lo, c_hi) has its own (ticket number `tk`), and whoever
+// draws the last one merges the row splits of just those columns.
 template <int ELT, int KB>
-__device__ __forceinline__ void row_tail(const S1Params &p, int r, unsigned char *smem) {
+__device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, int c_lo, int c_hi, unsigned char *smem) {
     const int tid = threadIdx.x, T = blockDim.x;
     u64 *cand = (u64 *)(smem + p.lds_cand_off);
     if (!p.use_scratch) {
@@ -172,31 +176,29 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, unsigned char
         // Cross-workgroup hand-over without cache-wide fences: the lists were written, and are
         // read below, with agent-scope atomic accesses (they go through to memory instead of
         // staying in one XCD's L2); the barrier waits until this workgroup's stores have been
-        // acknowledged, and only then one lane takes the row's ticket.  Whoever draws the
-        // last ticket knows that every other workgroup's lists are complete.
+        // acknowledged, and only then one lane takes the ticket.  Whoever draws the last one
+        // knows that every other workgroup's lists are complete.
         if (p.fence_sync) __threadfence();
         __syncthreads();
         uint32_t *flag = (uint32_t *)smem;
+        uint32_t *ticket_word = p.tickets + tk * kTicketStride;
         if (tid == 0) {
-            uint32_t ticket = __hip_atomic_fetch_add(&p.tickets[(int64_t)r * kTicketStride], 1u, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-            flag[0] = (ticket == (uint32_t)(p.wgs_per_row - 1)) ? 1u : 0u;
+            uint32_t ticket = __hip_atomic_fetch_add(ticket_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            flag[0] = (ticket == (uint32_t)(p.wgs_per_ticket - 1)) ? 1u : 0u;
         }
         __syncthreads();
         if (flag[0] == 0) return;
         if (p.fence_sync) __threadfence();
         if (tid == 0)  // ready for the next call
-            __hip_atomic_store(&p.tickets[(int64_t)r * kTicketStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(ticket_word, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-        // the last workgroup of the row merges the splits of every column; the loads of SU
-        // splits are in flight together
-        constexpr int SU = (KB <= 2) ? 8 : (KB <= 4 ? 4 : 2);
+        // The last workgroup merges the splits of its columns, SU splits per batch of loads.
+        constexpr int SU = tail_split_batch(KB);
+        const int ncols = c_hi - c_lo;
         const u64 *src = p.lists + (int64_t)r * p.S * p.b * p.k_b;
-        for (int col = tid; col < p.b; col += T) {
-            u64 acc[KB];
-#pragma unroll
-            for (int j = 0; j < KB; ++j) acc[j] = 0ull;
-            for (int s0 = 0; s0 < p.S; s0 += SU) {
+        // lists of splits s_first, s_first + s_step, ... of column `col`, merged into acc
+        auto gather = [&](int col, int s_first, int s_step, u64(&acc)[KB]) {
+            for (int s0 = s_first; s0 < p.S; s0 += s_step) {
                 u64 th[SU][KB];
 #pragma unroll
                 for (int u = 0; u < SU; ++u)
@@ -209,6 +211,8 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, unsigned char
 #pragma unroll
                 for (int u = 0; u < SU; ++u) merge_topk<KB>(acc, th[u]);
             }
+        };
+        auto put = [&](int col, const u64(&acc)[KB]) {
             if (p.stage2) {
 #pragma unroll
                 for (int j = 0; j < KB; ++j)
@@ -219,6 +223,34 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, unsigned char
                 for (int j = 0; j < KB; ++j)
                     if (j < p.k_b) write_composite<ELT>(acc[j], p.out_vals, p.out_idx, o + j);
             }
+        };
+        if (p.tail_tpc_shift == 0) {
+            // one lane per column (a plain loop: the compiler may overlap its iterations)
+            for (int ci = tid; ci < ncols; ci += T) {
+                u64 acc[KB];
+#pragma unroll
+                for (int j = 0; j < KB; ++j) acc[j] = 0ull;
+                gather(c_lo + ci, 0, SU, acc);
+                put(c_lo + ci, acc);
+            }
+        } else {
+            // Fewer columns than lanes and many splits: tpc lanes side by side share a column,
+            // each merges every tpc-th batch, then a butterfly of shuffles joins them.
+            const int tpc_shift = p.tail_tpc_shift, tpc = 1 << tpc_shift;  // chosen on the host: tpc * ncols <= T
+            const int part = tid & (tpc - 1);
+            const int ci = tid >> tpc_shift;
+            const bool ok = ci < ncols;
+            u64 acc[KB];
+#pragma unroll
+            for (int j = 0; j < KB; ++j) acc[j] = 0ull;
+            if (ok) gather(c_lo + ci, part * SU, tpc * SU, acc);
+            for (int off = 1; off < tpc; off <<= 1) {
+                u64 theirs[KB];
+#pragma unroll
+                for (int j = 0; j < KB; ++j) theirs[j] = shfl_xor_u64(acc[j], off);
+                merge_topk<KB>(acc, theirs);
+            }
+            if (ok && part == 0) put(c_lo + ci, acc);
         }
         if (!p.stage2) return;
         __syncthreads();
@@ -403,7 +435,9 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
         for (int e = 0; e < V; ++e) emit(col0 + e, comp[e]);
     }
 
-    row_tail<ELT, KB>(p, r, smem);
+    const bool whole = p.stage2 != 0;
+    row_tail<ELT, KB>(p, r, whole ? (int64_t)r : (int64_t)r * p.colblocks + cb, whole ? 0 : cb * p.Gw * V,
+                      whole ? p.b : min(p.b, (cb + 1) * p.Gw * V), smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -508,7 +542,9 @@ __global__ void __launch_bounds__(MAXT) contig_kernel(S1Params p) {
     }
     u64 *cand = (u64 *)(smem + p.lds_cand_off);
     if (active && q == 0) emit_list<ELT, KB>(p, r, sp, j, comp, cand);
-    row_tail<ELT, KB>(p, r, smem);
+    const bool whole = p.stage2 != 0;
+    row_tail<ELT, KB>(p, r, whole ? (int64_t)r : (int64_t)r * p.bblocks + bb, whole ? 0 : bb * bpw,
+                      whole ? p.b : min(p.b, (bb + 1) * bpw), smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -559,7 +595,8 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.nparts = pl.nparts;
     prm.lds_xch_off = pl.lds_xch_off;
     prm.lds_cand_off = pl.lds_cand_off;
-    prm.wgs_per_row = pl.S * pl.colblocks;
+    prm.wgs_per_ticket = pl.stage2 ? pl.S * pl.colblocks : pl.S;
+    prm.tail_tpc_shift = log2_exact(pl.tail_tpc);
     prm.cb_shift = log2_exact(pl.colblocks);
     prm.s_shift = log2_exact(pl.S);
     prm.gw_shift = log2_exact(pl.Gw);
@@ -607,7 +644,8 @@ hipError_t launch_approx_contig(const Plan &pl, const void *x, void *out_vals, i
     prm.use_scratch = pl.use_scratch;
     prm.lds_xch_off = pl.lds_xch_off;
     prm.lds_cand_off = pl.lds_cand_off;
-    prm.wgs_per_row = pl.S * pl.bblocks;
+    prm.wgs_per_ticket = pl.stage2 ? pl.S * pl.bblocks : pl.S;
+    prm.tail_tpc_shift = log2_exact(pl.tail_tpc);
     prm.Gs = pl.Gs;
     prm.gs_shift = log2_exact(pl.Gs);
     prm.bblocks = pl.bblocks;
