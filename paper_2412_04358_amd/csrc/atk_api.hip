@@ -84,8 +84,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // columns per lane: the default instance for (dtype, KB), or the widest one within V_forced
     int T_forced = 0, S_forced = 0, V_forced = 0;
     plan_override(&T_forced, &S_forced, &V_forced);
-    // (vector loads need a 16-byte aligned x and every matrix row starting on a multiple of V)
-    p.V = stage1_pick_v(dtype, p.KB, !ptr16 ? 1 : V_forced, b, n);
+    // (vector loads need a 16-byte aligned x and b a multiple of V)
+    p.V = stage1_pick_v(dtype, p.KB, !ptr16 ? 1 : V_forced, b);
     p.G = b / p.V;
     p.L = n / b;
     p.stage2 = b * k_b > k;

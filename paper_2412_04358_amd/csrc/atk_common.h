@@ -41,14 +41,16 @@ constexpr int max_threads_for_kb(int KB) { return KB <= 4 ? 1024 : 256; }
     X(ATK_BF16, 8, 1, 8) X(ATK_BF16, 8, 2, 4) X(ATK_BF16, 8, 4, 4) X(ATK_BF16, 8, 8, 2) X(ATK_BF16, 8, 16, 2) \
     X(ATK_BF16, 1, 1, 16) X(ATK_BF16, 1, 2, 8) X(ATK_BF16, 1, 4, 8) X(ATK_BF16, 1, 8, 4) X(ATK_BF16, 1, 16, 2)
 
-// Columns per lane for (dtype, KB): the first listed instance whose V divides both b and n, so
-// that every V-element load is naturally aligned (and equals `want`, when that is not 0).
-inline int stage1_pick_v(int dtype, int KB, int want, int64_t b, int64_t n) {
+// Columns per lane for (dtype, KB): the first listed instance whose V divides b, so that the
+// V-element loads of a lane stay aligned from one matrix row to the next (and equals `want`,
+// when that is not 0).  Rows that start off a V-element boundary (n not a multiple of V) are
+// read from the aligned address before them.
+inline int stage1_pick_v(int dtype, int KB, int want, int64_t b) {
 #define ATK_X(ELT, VV, KK, UU) \
-    if (dtype == ELT && KB == KK && (want == 0 || VV == want) && b % VV == 0 && n % VV == 0) return VV;
+    if (dtype == ELT && KB == KK && (want == 0 || VV == want) && b % VV == 0) return VV;
     ATK_STAGE1_INSTANCES(ATK_X)
 #undef ATK_X
-    return want ? stage1_pick_v(dtype, KB, 0, b, n) : 1;
+    return want ? stage1_pick_v(dtype, KB, 0, b) : 1;
 }
 constexpr int kStage2MaxCand = 4096;      // composites held in LDS by the fused Stage 2
 constexpr int kLdsBudget = 64 * 1024;     // static+dynamic LDS per workgroup we allow ourselves

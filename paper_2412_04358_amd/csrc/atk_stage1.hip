@@ -163,9 +163,11 @@ __device__ __forceinline__ void emit_list(const S1Params &p, int r, int sp, int 
 // share a ticket, and Stage 2.  Every thread calls it.
 // With Stage 2 the whole row shares one ticket (one workgroup must see all b*k_b candidates);
 // without it every block of columns [c_lo, c_hi) has its own (ticket number `tk`), and whoever
-// draws the last one merges the row splits of just those columns.
+// draws the last one merges the row splits of just those columns.  Column c of the block is
+// bucket c - rot (mod b).
 template <int ELT, int KB>
-__device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, int c_lo, int c_hi, unsigned char *smem) {
+__device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, int c_lo, int c_hi, int rot,
+                                         unsigned char *smem) {
     const int tid = threadIdx.x, T = blockDim.x;
     u64 *cand = (u64 *)(smem + p.lds_cand_off);
     if (!p.use_scratch) {
@@ -230,8 +232,9 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
                 u64 acc[KB];
 #pragma unroll
                 for (int j = 0; j < KB; ++j) acc[j] = 0ull;
-                gather(c_lo + ci, 0, SU, acc);
-                put(c_lo + ci, acc);
+                const int col = c_lo + ci - rot + (c_lo + ci < rot ? p.b : 0);
+                gather(col, 0, SU, acc);
+                put(col, acc);
             }
         } else {
             // Fewer columns than lanes and many splits: tpc lanes side by side share a column,
@@ -243,14 +246,15 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
             u64 acc[KB];
 #pragma unroll
             for (int j = 0; j < KB; ++j) acc[j] = 0ull;
-            if (ok) gather(c_lo + ci, part * SU, tpc * SU, acc);
+            const int col = c_lo + ci - rot + (c_lo + ci < rot ? p.b : 0);
+            if (ok) gather(col, part * SU, tpc * SU, acc);
             for (int off = 1; off < tpc; off <<= 1) {
                 u64 theirs[KB];
 #pragma unroll
                 for (int j = 0; j < KB; ++j) theirs[j] = shfl_xor_u64(acc[j], off);
                 merge_topk<KB>(acc, theirs);
             }
-            if (ok && part == 0) put(c_lo + ci, acc);
+            if (ok && part == 0) put(col, acc);
         }
         if (!p.stage2) return;
         __syncthreads();
@@ -271,9 +275,21 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     divmod(tid, p.Gw, p.gw_shift, ph, cgl);
     const int cg = cb * p.Gw + cgl;
     const bool active = (ph < p.P) && (cg < p.G);
-    const int t0 = sp * p.rows_per_split;
-    const int t1 = min(p.L, t0 + p.rows_per_split);
     const int col0 = cg * V;
+    // Rows whose first element is not aligned to a V-element load (n not a multiple of V) are
+    // read from the aligned address just before: the row is taken as a virtual row that starts
+    // `rot` elements early, so virtual column c holds bucket c - rot (mod b) and element
+    // (t, c) of the virtual matrix is column t*b + c - rot of the row.  The first `rot` virtual
+    // elements belong to the previous row and are skipped.
+    const int rot = (V > 1) ? (int)(((int64_t)r * p.n) & (V - 1)) : 0;
+    const bool carry = p.rem + rot >= p.b;       // the virtual row has one more full matrix row
+    const int Lr = p.L + (carry ? 1 : 0);       // full matrix rows of the virtual row
+    const int remr = p.rem + rot - (carry ? p.b : 0);  // columns of its ragged last matrix row
+    int eph = p.extra_ph + (carry ? 1 : 0);     // the row phase that takes the ragged row
+    if (eph >= p.P) eph -= p.P;
+    const int t0 = sp * p.rows_per_split;
+    const int t1 = (sp == p.S - 1) ? Lr : min(Lr, t0 + p.rows_per_split);
+    auto bucket_of = [&](int c) { return c - rot + (c < rot ? p.b : 0); };
 
     float val[V][KB];
     int tt[V][KB];
@@ -287,10 +303,18 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 
     // ---------------------------------------------------------------- streaming scan
     if (active) {
-        const unsigned char *base = (const unsigned char *)p.x + ((int64_t)r * p.n + (int64_t)col0) * ES;
+        const unsigned char *base = (const unsigned char *)p.x + ((int64_t)r * p.n - rot + (int64_t)col0) * ES;
         const int64_t row_bytes = (int64_t)p.b * ES;
         const int step = p.P;
         int t = t0 + ph;
+        if (V > 1 && rot > 0 && cg == 0 && t == 0 && t < t1) {
+            // the head of the virtual row: its first `rot` elements are not this row's
+            RowVec<ELT, V> v = load_vec<ELT, V>(base);
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                if (e >= rot) insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, V>(v, e)), 0);
+            t += step;
+        }
         for (; t + (U - 1) * step < t1; t += U * step) {
             RowVec<ELT, V> v[U];
 #pragma unroll
@@ -302,19 +326,20 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
             RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)t * row_bytes);
             scan_vec<ELT, V, KB>(val, tt, v, t);
         }
-        // n not a multiple of b: the last matrix row holds only the first `rem` columns (the
-        // short buckets of Figure 2).  It has the highest indices, so it is fed last.
-        if (p.rem > 0 && sp == p.S - 1 && ph == p.extra_ph && col0 < p.rem) {
-            const unsigned char *last = base + (int64_t)p.L * row_bytes;
-            if (col0 + V <= p.rem) {
+        // The (virtual) row does not end on a matrix row: the last matrix row holds only its
+        // first `remr` columns (the short buckets of Figure 2).  It has the highest indices, so
+        // it is fed last.
+        if (remr > 0 && sp == p.S - 1 && ph == eph && col0 < remr) {
+            const unsigned char *last = base + (int64_t)Lr * row_bytes;
+            if (col0 + V <= remr) {
                 RowVec<ELT, V> v = load_vec<ELT, V>(last);
-                scan_vec<ELT, V, KB>(val, tt, v, p.L);
+                scan_vec<ELT, V, KB>(val, tt, v, Lr);
             } else {
 #pragma unroll
                 for (int e = 0; e < V; ++e)
-                    if (col0 + e < p.rem) {
+                    if (col0 + e < remr) {
                         RowVec<ELT, 1> one = load_vec<ELT, 1>(last + e * ES);
-                        insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, 1>(one, 0)), p.L);
+                        insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, 1>(one, 0)), Lr);
                     }
             }
         }
@@ -324,7 +349,7 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     if (p.direct) {
         if (!active) return;
         const int64_t o = (int64_t)r * p.k + (int64_t)col0 * p.k_b;
-        if (p.vec_store && p.k_b == KB && (V * KB) % ((ELT == ATK_F32) ? 4 : 8) == 0) {
+        if (p.vec_store && rot == 0 && p.k_b == KB && (V * KB) % ((ELT == ATK_F32) ? 4 : 8) == 0) {
             constexpr int N = V * KB;  // contiguous outputs of this lane
             uint32_t ob[N];
             int32_t oi[N];
@@ -367,9 +392,9 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 #pragma unroll
                 for (int j = 0; j < KB; ++j)
                     if (j < p.k_b) {
-                        const int64_t pos = o + (int64_t)e * p.k_b + j;
+                        const int64_t pos = (int64_t)r * p.k + (int64_t)bucket_of(col0 + e) * p.k_b + j;
                         store_val<ELT>(p.out_vals, pos, __float_as_uint(val[e][j]));
-                        p.out_idx[pos] = tt[e][j] * p.b + col0 + e;
+                        p.out_idx[pos] = tt[e][j] * p.b + col0 + e - rot;
                     }
         }
         return;
@@ -382,7 +407,7 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 #pragma unroll
         for (int j = 0; j < KB; ++j)
             comp[e][j] = (tt[e][j] != kEmptyT)
-                             ? make_composite(__float_as_uint(val[e][j]), tt[e][j] * p.b + col0 + e)
+                             ? make_composite(__float_as_uint(val[e][j]), tt[e][j] * p.b + col0 + e - rot)
                              : 0ull;
 
     // ---------------------------------------------------------------- merge inside the wavefront
@@ -428,16 +453,16 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
                 for (int j = 0; j < KB; ++j) theirs[j] = xch[((int64_t)q * p.b + c) * KB + j];
                 merge_topk<KB>(acc, theirs);
             }
-            emit(c, acc);
+            emit(bucket_of(c), acc);
         }
     } else if (active && (!p.wave_merge || (tid & (kWave - 1)) < p.Gw)) {
 #pragma unroll
-        for (int e = 0; e < V; ++e) emit(col0 + e, comp[e]);
+        for (int e = 0; e < V; ++e) emit(bucket_of(col0 + e), comp[e]);
     }
 
     const bool whole = p.stage2 != 0;
     row_tail<ELT, KB>(p, r, whole ? (int64_t)r : (int64_t)r * p.colblocks + cb, whole ? 0 : cb * p.Gw * V,
-                      whole ? p.b : min(p.b, (cb + 1) * p.Gw * V), smem);
+                      whole ? p.b : min(p.b, (cb + 1) * p.Gw * V), whole ? 0 : rot, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -544,7 +569,7 @@ __global__ void __launch_bounds__(MAXT) contig_kernel(S1Params p) {
     if (active && q == 0) emit_list<ELT, KB>(p, r, sp, j, comp, cand);
     const bool whole = p.stage2 != 0;
     row_tail<ELT, KB>(p, r, whole ? (int64_t)r : (int64_t)r * p.bblocks + bb, whole ? 0 : bb * bpw,
-                      whole ? p.b : min(p.b, (bb + 1) * bpw), smem);
+                      whole ? p.b : min(p.b, (bb + 1) * bpw), 0, smem);
 }
 
 // ------------------------------------------------------------------------------------------------

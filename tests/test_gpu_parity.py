@@ -156,6 +156,19 @@ SHAPES = [
     (2, 66000, 512, 128, 4),      # remainder 80 of 128 columns: partial vectors
     (1, 128256, 256, 512, 1),     # vocabulary-sized row, b*k_b/k = 2
     (1, 128256, 256, 1000, 2),    # b does not divide n
+    # rows that start off a vector boundary (n % V != 0, b % V == 0): read from the aligned address before
+    (5, 4099, 1024, 1024, 1),     # every lane owns whole buckets, outputs rotated
+    (5, 8197, 2048, 1024, 2),
+    (7, 4101, 64, 64, 1),         # lanes share columns
+    (7, 4103, 48, 64, 1),         # ... with Stage 2
+    (6, 12289, 512, 512, 1),
+    (9, 5003, 96, 32, 3),
+    (4, 66001, 512, 128, 4),
+    (3, 65535, 16380, 16380, 1),  # the ragged last matrix row wraps into one more full row
+    (3, 40003, 16000, 8000, 2),
+    (7, 4159, 64, 64, 1),         # n % b = b - 1: with the rotation the last matrix row fills up
+    (5, 4159, 128, 64, 2),
+    (5, 5119, 1024, 1024, 1),
 ]
 
 
@@ -172,7 +185,8 @@ def test_forced_plans(plan, monkeypatch):
     monkeypatch.setenv("ATK_PLAN", plan)
     for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (3, 32768, 2048, 2048, 1),
                                            (3, 32768, 128, 64, 2), (3, 32768, 100, 32, 4), (2, 32768, 64, 8, 8),
-                                           (2, 32768, 200, 16, 16)]):
+                                           (2, 32768, 200, 16, 16), (3, 32771, 2048, 2048, 1), (3, 32770, 128, 64, 2),
+                                           (3, 32773, 4096, 1024, 4)]):
         for dtype in ["f32", "bf16"]:
             x = workloads.normal_rows(m, n, seed=200 + i, dtype=dtype)
             run_case(x, k, b, k_b, tag=plan)
