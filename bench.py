@@ -255,8 +255,8 @@ def _approx_entry(atk, torch, dev, ring, m, n, k, b, k_b, dt, es, reps, assignme
 
     us = _time_us(torch, launch, reps)
     nbytes = m * n * es + m * k * (es + 4)
-    return {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
-            "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+    return {"us": round(us, 2), "est_us": round(atk.estimate_us(m, n, k, b, k_b, dt), 2) if assignment is None else None,
+            "GBps": round(nbytes / us / 1e3, 1), "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
             "plan": atk.plan_describe(m, n, k, b, k_b, dt, assignment if assignment is not None else atk.ATK_INTERLEAVED)}
 
 

@@ -130,6 +130,28 @@ int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
                              char *buf, int64_t buflen);
 
 /*
+ * Choosing (b, k_b) (Section 3 and Appendices C-E).  Host only, no HIP call.
+ *
+ * atk_expected_recall: Eq. 1 of Appendix C, the expected fraction of the true top-k that the
+ *   method returns when top-k positions fall into buckets uniformly (a lower bound on the
+ *   recall once k_b is not small against n/b, as the remark after Eq. 1 says).  -1 for
+ *   arguments outside 1 <= k_b <= k <= b*k_b.
+ * atk_estimate_us: microseconds one approx_topk call with these arguments is expected to take on
+ *   an MI355X, in the shape of Appendix D's cost composition (Stage 1 + Stage 2 if b*k_b > k) with
+ *   terms fitted to this library's measured timings.  -1 if the arguments are not accepted.
+ * atk_advise: among k_b in {1,2,4,8,16} and b*k_b/k in {1,2,4,...,64} that approx_topk accepts,
+ *   the pair with the lowest estimate whose Eq. 1 recall is at least min_recall (0 < min_recall <= 1).
+ *   Writes *b, *k_b and, when not NULL, *recall and *us.  Returns ATK_OK, or
+ *   ATK_ADVISE_BELOW_TARGET (1) when no accepted pair reaches min_recall (then the pair with the
+ *   highest recall is written), or an error code.
+ */
+#define ATK_ADVISE_BELOW_TARGET 1
+double atk_expected_recall(int64_t k, int64_t b, int64_t k_b);
+double atk_estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
+int atk_advise(int64_t m, int64_t n, int64_t k, int dtype, double min_recall, int64_t *b, int64_t *k_b,
+               double *recall, double *us);
+
+/*
  * Measurement utilities (Appendix B.1 protocol, and the roofline's empirical ceiling).
  *
  * atk_read_ceiling: a read-only streaming kernel over `bytes` bytes (multiple of 16, 16-byte

@@ -9,11 +9,14 @@ from .binding import (  # noqa: F401
     ATK_F32,
     ATK_INTERLEAVED,
     ApproxTopkError,
+    advise,
     approx_topk,
     approx_topk_assign_raw,
     approx_topk_raw,
+    estimate_us,
     exact_topk,
     exact_topk_raw,
+    expected_recall,
     lib_path,
     load_library,
     plan_describe,

@@ -66,6 +66,14 @@ def load_library():
     lib.atk_exact_workspace_bytes.restype = i64
     lib.atk_plan_describe.argtypes = [i64, i64, i64, i64, i64, ci, ctypes.c_char_p, i64]
     lib.atk_plan_describe.restype = ci
+    dbl = ctypes.c_double
+    lib.atk_expected_recall.argtypes = [i64, i64, i64]
+    lib.atk_expected_recall.restype = dbl
+    lib.atk_estimate_us.argtypes = [i64, i64, i64, i64, i64, ci]
+    lib.atk_estimate_us.restype = dbl
+    lib.atk_advise.argtypes = [i64, i64, i64, ci, dbl, ctypes.POINTER(i64), ctypes.POINTER(i64),
+                               ctypes.POINTER(dbl), ctypes.POINTER(dbl)]
+    lib.atk_advise.restype = ci
     lib.atk_read_ceiling.argtypes = [vp, i64, vp, vp]
     lib.atk_read_ceiling.restype = ci
     lib.atk_copy.argtypes = [vp, vp, i64, vp]
@@ -164,3 +172,23 @@ def plan_describe(m, n, k, b, k_b, dtype=ATK_F32, assignment=ATK_INTERLEAVED) ->
     buf = ctypes.create_string_buffer(512)
     _check(load_library().atk_plan_describe_assign(m, n, k, b, k_b, dtype, assignment, buf, 512))
     return buf.value.decode()
+
+
+def expected_recall(k, b, k_b) -> float:
+    """Eq. 1 of Appendix C as the library computes it (host only)."""
+    return load_library().atk_expected_recall(k, b, k_b)
+
+
+def estimate_us(m, n, k, b, k_b, dtype=ATK_F32) -> float:
+    return load_library().atk_estimate_us(m, n, k, b, k_b, dtype)
+
+
+def advise(m, n, k, dtype=ATK_F32, min_recall=0.9):
+    """(b, k_b, expected recall, estimated microseconds, reached) for a recall target."""
+    b, kb = ctypes.c_int64(0), ctypes.c_int64(0)
+    rec, us = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = load_library().atk_advise(m, n, k, dtype, float(min_recall), ctypes.byref(b), ctypes.byref(kb),
+                                   ctypes.byref(rec), ctypes.byref(us))
+    if rc < 0:
+        _check(rc)
+    return b.value, kb.value, rec.value, us.value, rc == 0

@@ -1,0 +1,114 @@
+// Host-only helpers for choosing (b, k_b): the recall model of Appendix C (Eq. 1) and a
+// runtime estimate in the shape of Appendix D's cost composition,
+//   cost(approx) = cost(Stage 1 over b buckets) + [b*k_b > k] * cost(Stage 2 over b*k_b candidates),
+// with the terms taken from timings of this library's kernels on an MI355X instead of the
+// paper's operation counts.  Section 3 / Appendix E describe the trade-off this makes
+// executable: for k << n raise b (more candidates, then Stage 2), for k ~ n raise k_b with
+// b*k_b = k.  No HIP call is made here.
+#include <cmath>
+#include <cstdint>
+
+#include "atk_common.h"
+
+namespace atk {
+
+// Eq. 1 rewritten per bucket: with X ~ Binomial(k, 1/b) top-k elements in a bucket, min(X, k_b)
+// of them are returned, and E[recall] = (b/k) E[min(X, k_b)].  Only the k_b lowest terms of
+// the distribution are needed: E[min(X, k_b)] = k_b - sum_{z < k_b} (k_b - z) Pr(X = z).
+static double eq1_recall(int64_t k, int64_t b, int64_t k_b) {
+    if (b <= 1) return 1.0;
+    const double lp = -std::log((double)b), lq = std::log1p(-1.0 / (double)b);
+    double deficit = 0.0;
+    for (int64_t z = 0; z < k_b && z <= k; ++z) {
+        const double lc = std::lgamma((double)k + 1.0) - std::lgamma((double)z + 1.0) - std::lgamma((double)(k - z) + 1.0);
+        deficit += (double)(k_b - z) * std::exp(lc + (double)z * lp + (double)(k - z) * lq);
+    }
+    double r = (double)b / (double)k * ((double)k_b - deficit);
+    return r > 1.0 ? 1.0 : (r < 0.0 ? 0.0 : r);
+}
+
+// Microseconds of one approx_topk call, from measurements of this library on one MI355X:
+// a fixed launch + ramp cost, the row bytes at the streaming rate a launch of that size
+// reaches, a factor for the register queues of k_b > 1, the hand-over between workgroups when
+// rows are split, and Stage 2.
+static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    const double es = (dtype == ATK_F32) ? 4.0 : 2.0;
+    const double bytes = (double)m * (double)n * es + (double)m * (double)k * (es + 4.0);
+    // streaming rate grows with the size of the launch: about 5.5 TB/s at 32 MB, 6.4 TB/s from 0.5 GB
+    double rate = 6.5e6 * bytes / (bytes + 6.0e6);  // bytes per microsecond
+    if (rate < 0.5e6) rate = 0.5e6;
+    int KB = 1;
+    while (KB < k_b) KB <<= 1;
+    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.05 : KB == 4 ? 1.25 : KB == 8 ? 2.1 : 4.5;
+    double us = 1.5 + bytes / rate * queue;
+    const bool stage2 = b * k_b > k;
+    // rows are split over workgroups when one lane per column group cannot fill the chip
+    const double lanes = (double)m * (double)b / ((dtype == ATK_F32) ? 4.0 : 8.0);
+    if (lanes < 65536.0 || stage2) us += 2.0;
+    if (stage2) us += 2.5 + 0.0015 * (double)(b * k_b);
+    return us;
+}
+
+}  // namespace atk
+
+using namespace atk;
+
+extern "C" {
+
+double atk_expected_recall(int64_t k, int64_t b, int64_t k_b) {
+    if (k < 1 || b < 1 || k_b < 1 || k_b > k || b * k_b < k) return -1.0;
+    return eq1_recall(k, b, k_b);
+}
+
+double atk_estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    if (atk_check_approx(m, n, k, b, k_b, dtype) != ATK_OK) return -1.0;
+    return estimate_us(m, n, k, b, k_b, dtype);
+}
+
+int atk_advise(int64_t m, int64_t n, int64_t k, int dtype, double min_recall, int64_t *b_out, int64_t *k_b_out,
+               double *recall_out, double *us_out) {
+    if (!b_out || !k_b_out) return ATK_ERR_NULL_PTR;
+    int rc = atk_check_exact(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    if (!(min_recall > 0.0) || min_recall > 1.0) return ATK_ERR_BAD_PARAMS;
+    const int64_t lane = (dtype == ATK_F32) ? 4 : 8;
+    bool have = false, have_ok = false;
+    int64_t best_b = 0, best_kb = 0;
+    double best_recall = 0.0, best_us = 0.0;
+    for (int64_t k_b = 1; k_b <= ATK_MAX_KB && k_b <= k; k_b <<= 1) {
+        for (int64_t ratio = 1; ratio <= 64; ratio <<= 1) {
+            int64_t b = (ratio * k + k_b - 1) / k_b;
+            if (ratio > 1 && b % lane) b += lane - b % lane;  // whole vector loads per lane
+            if (b * k_b > k && b * k_b > atk_stage2_max_candidates()) break;
+            if (atk_check_approx(m, n, k, b, k_b, dtype) != ATK_OK) break;  // b grows with ratio: k_b > n/b from here on
+            const double rec = eq1_recall(k, b, k_b), us = estimate_us(m, n, k, b, k_b, dtype);
+            const bool ok = rec >= min_recall;
+            bool take;
+            if (!have)
+                take = true;
+            else if (ok != have_ok)
+                take = ok;
+            else if (ok)
+                take = us < best_us || (us == best_us && rec > best_recall);
+            else
+                take = rec > best_recall;
+            if (take) {
+                have = true;
+                have_ok = ok;
+                best_b = b;
+                best_kb = k_b;
+                best_recall = rec;
+                best_us = us;
+            }
+            if (rec >= 1.0) break;
+        }
+    }
+    if (!have) return ATK_ERR_UNSUPPORTED;
+    *b_out = best_b;
+    *k_b_out = best_kb;
+    if (recall_out) *recall_out = best_recall;
+    if (us_out) *us_out = best_us;
+    return have_ok ? ATK_OK : ATK_ADVISE_BELOW_TARGET;
+}
+
+}  // extern "C"

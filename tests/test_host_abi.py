@@ -205,3 +205,42 @@ def test_workspace_bytes(lib):
     assert lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0) == p["scratch_bytes"] > 0
     assert lib.atk_workspace_bytes(128, 65536, 64, 32, 1, 0) == PARAMS
     assert lib.atk_stage2_max_candidates() >= 1024
+
+
+# ----------------------------------------------------------------------------- choosing (b, k_b)
+def test_expected_recall_is_eq1(lib):
+    """The library's Eq. 1 (per-bucket form, k_b terms) against the oracle's (sum of binomial CDFs):
+    two independent writings of the same formula."""
+    from oracle import recall
+
+    for (k, b, k_b) in [(64, 64, 1), (64, 1024, 1), (16384, 4096, 4), (16384, 1024, 16), (256, 256, 1), (100, 128, 2),
+                        (64, 8, 8), (512, 512, 1), (7, 3, 3), (1, 1, 1), (100, 1, 100), (300, 77, 5)]:
+        assert abs(atk.expected_recall(k, b, k_b) - recall.expected_recall_eq1(k, b, k_b)) < 1e-9
+    assert abs(atk.expected_recall(64, 64, 1) - recall.expected_recall_kb1(64, 64)) < 1e-12
+    assert atk.expected_recall(64, 32, 1) == -1.0 and atk.expected_recall(4, 64, 8) == -1.0
+
+
+def test_advise(lib):
+    for (m, n, k, dt) in [(128, 65536, 64, atk.ATK_F32), (128, 65536, 16384, atk.ATK_F32), (64, 128256, 256, atk.ATK_BF16),
+                          (128, 2653751, 100, atk.ATK_BF16), (1, 40000, 5000, atk.ATK_BF16), (4, 4096, 64, atk.ATK_F32)]:
+        last_us = 0.0
+        for target in (0.3, 0.6, 0.8, 0.9, 0.95, 0.99):
+            b, k_b, rec, us, reached = atk.advise(m, n, k, dt, target)
+            assert lib.atk_check_approx(m, n, k, b, k_b, dt) == 0
+            assert abs(rec - atk.expected_recall(k, b, k_b)) < 1e-12
+            assert abs(us - atk.estimate_us(m, n, k, b, k_b, dt)) < 1e-9 and us > 0
+            if reached:
+                assert rec >= target
+                assert us >= last_us - 1e-9  # a higher target never gets cheaper
+                last_us = us
+    # the cheapest setting: one bucket per output, no Stage 2
+    b, k_b, rec, us, reached = atk.advise(128, 65536, 64, atk.ATK_F32, 0.5)
+    assert (b, k_b, reached) == (64, 1, True)
+    # k = n/4 leaves no room for more candidates: only larger k_b raises recall, and 0.99 is out of reach
+    b, k_b, rec, us, reached = atk.advise(128, 65536, 16384, atk.ATK_F32, 0.99)
+    assert not reached and b * k_b == 16384 and k_b == 16
+    i64 = ctypes.c_int64
+    bb, kk = i64(0), i64(0)
+    assert lib.atk_advise(128, 65536, 64, 0, 1.5, ctypes.byref(bb), ctypes.byref(kk), None, None) == PARAMS
+    assert lib.atk_advise(128, 65536, 64, 0, 0.9, None, ctypes.byref(kk), None, None) == NULLP
+    assert lib.atk_advise(128, 65536, 0, 0, 0.9, ctypes.byref(bb), ctypes.byref(kk), None, None) == SHAPE
