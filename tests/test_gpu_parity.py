@@ -205,6 +205,43 @@ def test_forced_lane_widths(lanes, monkeypatch):
             run_case(x, k, b, k_b, tag=lanes)
 
 
+def random_cases(seed, count):
+    """Seeded random legal (m, n, k, b, k_b) with b*k_b within what Stage 2 accepts."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        m = int(rng.integers(1, 9))
+        n = int(rng.choice([rng.integers(1, 200), rng.integers(200, 5000), rng.integers(5000, 70000)]))
+        k_b = int(rng.choice([1, 1, 1, 2, 3, 4, 5, 8, 11, 16]))
+        if k_b > n:
+            continue
+        b_max = n // k_b
+        b = int(rng.choice([rng.integers(1, min(b_max, 64) + 1), rng.integers(1, b_max + 1)]))
+        lo = max(k_b, 1)
+        hi = b * k_b
+        k = int(rng.choice([hi, rng.integers(lo, hi + 1)]))
+        if hi > k and hi > 4096:
+            k = hi  # no Stage 2 over more candidates than the library takes
+        out.append((m, n, k, b, k_b))
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_shapes(dtype):
+    for i, (m, n, k, b, k_b) in enumerate(random_cases(20241127, 60)):
+        x = workloads.normal_rows(m, n, seed=600 + i, dtype=dtype)
+        run_case(x, k, b, k_b, tag="random%d" % i)
+        run_case(x, k, b, k_b, tag="random%d contiguous" % i, assignment=atk.ATK_CONTIGUOUS)
+
+
+def test_many_short_rows():
+    """More rows than a grid dimension holds, each a few matrix rows long."""
+    x = workloads.normal_rows(70000, 64, seed=9)
+    run_case(x, 8, 8, 1, tag="many rows")
+    run_case(x, 6, 16, 1, tag="many rows, Stage 2")
+    run_case(x, 16, 8, 2, tag="many rows", assignment=atk.ATK_CONTIGUOUS)
+
+
 # ------------------------------------------------------------------------------- contiguous assignment
 CONTIG_SHAPES = [
     # (m, n, k, b, k_b)
