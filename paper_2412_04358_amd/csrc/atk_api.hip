@@ -68,6 +68,15 @@ static void plan_override(int *T, int *S, int *V) {
     }
 }
 
+// ATK_PLAN="..,PK=0": switches an optional code path off (for tests and sweeps)
+static bool plan_flag_off(const char *name) {
+    const char *e = getenv("ATK_PLAN");
+    if (!e) return false;
+    char key[16];
+    snprintf(key, sizeof key, "%s=0", name);
+    return strstr(e, key) != nullptr;
+}
+
 // ------------------------------------------------------------------------------------ approx plan
 static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, bool ptr16,
                              Plan *pl) {
@@ -167,6 +176,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.S = (int)S;
     p.rows_per_split = (int)rps;
 
+    p.packed = dtype == ATK_BF16 && p.KB >= 4 && p.rows_per_split + 2 < 32768 && !plan_flag_off("PK");
     p.tail_tpc = tail_lanes_per_column(p.stage2 ? b : std::min<int64_t>(b, (int64_t)p.Gw * p.V), p.T, p.KB, p.S);
     p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
     p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
@@ -414,10 +424,10 @@ int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, i
     if (rc != ATK_OK) return rc;
     snprintf(buf, (size_t)buflen,
              "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
-             "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld",
+             "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d",
              pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid,
              (int)pl.stage2, (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
-             (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes));
+             (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes), (int)pl.packed);
     return ATK_OK;
 }
 

@@ -91,6 +91,7 @@ struct Plan {
     bool stage2;      // b*k_b > k
     bool direct;      // every lane owns whole buckets: write results straight from registers
     bool use_scratch; // partial lists go through global scratch + a per-row ticket
+    bool packed;      // bf16, k_b >= 3: 32-bit (key, row) queue words; needs rows_per_split + 2 < 32768
     bool wave_merge;  // Gw < 64 and a power of two: lanes of a wavefront share columns, merged by shuffles
     int nparts;       // partial lists per column left for the LDS exchange
     int lds_xch_off, lds_cand_off;

@@ -136,6 +136,54 @@ __device__ __forceinline__ void scan_vec(float (&val)[V][KB], int (&tt)[V][KB], 
     for (int e = 0; e < V; ++e) insert<KB>(val[e], tt[e], x[e], t);
 }
 
+// ---- packed queues for bf16 with k_b >= 3 -------------------------------------------------------
+// A bf16 element and its matrix row fit one 32-bit word: [31:16] order-preserving key of the
+// value (-0 folded onto +0), [15:1] 0x7fff - (row - first row of this lane's split), [0] "was -0".
+// Larger word <=> larger value, or equal value and earlier row, so inserting into a descending
+// list is one median-of-three per slot instead of compares and selects on two arrays (measured
+// faster from four slots on; with two the conversion costs what it saves).  0 = empty.
+__device__ __forceinline__ uint32_t pack_bf16(uint32_t xb, uint32_t tl) {  // xb: the bf16 in the high half
+    const uint32_t sgn = (uint32_t)((int32_t)xb >> 31);
+    const uint32_t key = xb ^ ((sgn & 0x7fff0000u) | 0x80000000u);
+    return (xb == 0x80000000u) ? (0x80000001u | tl) : (key | tl);
+}
+__device__ __forceinline__ void unpack_bf16(uint32_t c, int t_first, float &v, int &t) {
+    if (c == 0u) {
+        v = __uint_as_float(0x7fc00000u);
+        t = kEmptyT;
+        return;
+    }
+    const uint32_t key = c >> 16;
+    uint32_t bits = (key & 0x8000u) ? (key ^ 0x8000u) : (~key & 0xffffu);
+    if (c & 1u) bits = 0x8000u;
+    v = __uint_as_float(bits << 16);
+    t = t_first + 0x7fff - (int)((c >> 1) & 0x7fffu);
+}
+__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+    return max(min(a, b), min(max(a, b), c));
+}
+template <int KB>
+__device__ __forceinline__ void insert_pk(uint32_t (&q)[KB], uint32_t c) {
+#pragma unroll
+    for (int j = KB - 1; j >= 1; --j) q[j] = umed3(q[j - 1], q[j], c);  // q[j-1] >= q[j]: c clamped between them
+    q[0] = max(q[0], c);
+}
+template <int ELT, int V, int KB>
+__device__ __forceinline__ void scan_vec_pk(uint32_t (&q)[V][KB], const RowVec<ELT, V> &v, int t_local) {
+    const uint32_t tl = (uint32_t)(0x7fff - t_local) << 1;
+    uint32_t c[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) c[e] = pack_bf16(elem_bits<ELT, V>(v, e), tl);
+    if (KB >= 8) {  // the insertion is cheap: only long queues are worth a wavefront-uniform skip
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < V; ++e) any = any || c[e] > q[e][KB - 1];
+        if (__ballot(any) == 0ull) return;
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) insert_pk<KB>(q[e], c[e]);
+}
+
 // Stage-1 result of bucket `col`, as seen by row split `sp` of row r: to the scratch lists (when
 // several workgroups share the row), to the candidate area in LDS (Stage 2 inside this
 // workgroup), or straight to the output.
@@ -264,10 +312,11 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
     select_write<ELT>(cand, p.b * p.k_b, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r);
 }
 
-template <int ELT, int V, int KB, int U, int MAXT>
+template <int ELT, int V, int KB, int U, int MAXT, bool PKF>
 __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int ES = (ELT == ATK_F32) ? 4 : 2;
+    constexpr bool PK = PKF && ELT == ATK_BF16 && KB >= 4;  // packed 32-bit queues (host: rows per split < 32766)
     const int tid = threadIdx.x, T = blockDim.x;
     int wg = blockIdx.x, cb, sp, r, cgl, ph;
     divmod(wg, p.colblocks, p.cb_shift, wg, cb);
@@ -293,13 +342,29 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 
     float val[V][KB];
     int tt[V][KB];
+    uint32_t pk[PK ? V : 1][PK ? KB : 1];
 #pragma unroll
     for (int e = 0; e < V; ++e)
 #pragma unroll
         for (int j = 0; j < KB; ++j) {
             val[e][j] = __uint_as_float(0x7fc00000u);
             tt[e][j] = kEmptyT;
+            if constexpr (PK) pk[e][j] = 0u;
         }
+#define ATK_FEED_VEC(vec, row)                                  \
+    do {                                                        \
+        if constexpr (PK)                                       \
+            scan_vec_pk<ELT, V, KB>(pk, vec, (row) - t0);       \
+        else                                                    \
+            scan_vec<ELT, V, KB>(val, tt, vec, (row));          \
+    } while (0)
+#define ATK_FEED_ELEM(e, xb, row)                                                                    \
+    do {                                                                                             \
+        if constexpr (PK)                                                                            \
+            insert_pk<KB>(pk[e], pack_bf16(xb, (uint32_t)(0x7fff - ((row) - t0)) << 1));             \
+        else                                                                                         \
+            insert<KB>(val[e], tt[e], __uint_as_float(xb), (row));                                   \
+    } while (0)
 
     // ---------------------------------------------------------------- streaming scan
     if (active) {
@@ -312,7 +377,7 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
             RowVec<ELT, V> v = load_vec<ELT, V>(base);
 #pragma unroll
             for (int e = 0; e < V; ++e)
-                if (e >= rot) insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, V>(v, e)), 0);
+                if (e >= rot) ATK_FEED_ELEM(e, (elem_bits<ELT, V>(v, e)), 0);
             t += step;
         }
         for (; t + (U - 1) * step < t1; t += U * step) {
@@ -320,11 +385,11 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 #pragma unroll
             for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes);
 #pragma unroll
-            for (int u = 0; u < U; ++u) scan_vec<ELT, V, KB>(val, tt, v[u], t + u * step);
+            for (int u = 0; u < U; ++u) ATK_FEED_VEC(v[u], t + u * step);
         }
         for (; t < t1; t += step) {
             RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)t * row_bytes);
-            scan_vec<ELT, V, KB>(val, tt, v, t);
+            ATK_FEED_VEC(v, t);
         }
         // The (virtual) row does not end on a matrix row: the last matrix row holds only its
         // first `remr` columns (the short buckets of Figure 2).  It has the highest indices, so
@@ -333,16 +398,25 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
             const unsigned char *last = base + (int64_t)Lr * row_bytes;
             if (col0 + V <= remr) {
                 RowVec<ELT, V> v = load_vec<ELT, V>(last);
-                scan_vec<ELT, V, KB>(val, tt, v, Lr);
+                ATK_FEED_VEC(v, Lr);
             } else {
 #pragma unroll
                 for (int e = 0; e < V; ++e)
                     if (col0 + e < remr) {
                         RowVec<ELT, 1> one = load_vec<ELT, 1>(last + e * ES);
-                        insert<KB>(val[e], tt[e], __uint_as_float(elem_bits<ELT, 1>(one, 0)), Lr);
+                        ATK_FEED_ELEM(e, (elem_bits<ELT, 1>(one, 0)), Lr);
                     }
             }
         }
+    }
+
+#undef ATK_FEED_VEC
+#undef ATK_FEED_ELEM
+    if constexpr (PK) {
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+#pragma unroll
+            for (int j = 0; j < KB; ++j) unpack_bf16(pk[e][j], t0, val[e][j], tt[e][j]);
     }
 
     // ---------------------------------------------------------------- every lane owns whole buckets
@@ -577,7 +651,14 @@ template <int ELT, int V, int KB, int U>
 static hipError_t launch_one(const Plan &pl, const S1Params &prm, hipStream_t stream) {
     constexpr int MAXT = max_threads_for_kb(KB);
     if (pl.T > MAXT) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U, MAXT>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T),
+    if constexpr (ELT == ATK_BF16 && KB >= 4) {
+        if (pl.packed) {
+            hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U, MAXT, true>), dim3((unsigned)pl.grid),
+                               dim3((unsigned)pl.T), (size_t)pl.lds_bytes, stream, prm);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U, MAXT, false>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T),
                        (size_t)pl.lds_bytes, stream, prm);
     return hipGetLastError();
 }

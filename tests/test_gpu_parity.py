@@ -323,6 +323,25 @@ def test_interleaved_flag_is_approx_topk():
     assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
 
 
+@pytest.mark.parametrize("plan", ["", "PK=0", "T=64,S=1"])
+def test_bf16_packed_queues(plan, monkeypatch):
+    """bf16 with k_b >= 3 keeps (key, row) in one 32-bit word per slot when a lane's share of the row
+    is short enough; the results are the same with that path switched off, and on rows whose
+    single split is too long for it."""
+    if plan:
+        monkeypatch.setenv("ATK_PLAN", plan)
+    cases = [(3, 16384, 2048, 1024, 2), (3, 16384, 96, 32, 4), (2, 16384, 64, 8, 8), (2, 16392, 64, 64, 3),
+             (4, 65536, 16384, 1024, 16), (2, 300000, 16, 4, 4), (2, 300001, 10, 2, 5), (1, 1 << 20, 64, 16, 4)]
+    for i, (m, n, k, b, k_b) in enumerate(cases):
+        run_case(workloads.normal_rows(m, n, seed=700 + i, dtype="bf16"), k, b, k_b, tag="packed " + plan)
+    for k, b, k_b in [(96, 32, 4), (40, 64, 2), (128, 8, 16)]:
+        run_case(workloads.few_levels(3, 8192, levels=3, seed=1, dtype="bf16"), k, b, k_b, tag="packed 3 levels " + plan)
+        run_case(workloads.special_values(3, 8192, seed=3, dtype="bf16"), k, b, k_b, tag="packed specials " + plan)
+    z = torch.zeros((2, 4096))
+    z[:, ::3] = -0.0
+    run_case(z.to(torch.bfloat16), 50, 64, 2, tag="packed zeros " + plan)
+
+
 # ------------------------------------------------------------------------------- ties and special values
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ties_and_specials(dtype):
