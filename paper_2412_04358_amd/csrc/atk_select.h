@@ -338,14 +338,33 @@ __device__ void select_radix_write(u64 *cand, int count, int k, void *out_vals, 
 //
 // idx_bits: the candidates' column indices are below 2^idx_bits (1..31); it tells which index
 // bits vary, so that equal values can be spread over bins by index.
+template <int ELT, int NS>
+__device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, int idx_bits, void *out_vals,
+                                                   int32_t *out_idx, int64_t row_out);
+
 template <int ELT>
 __device__ void select_write(u64 *cand, int count, int k, int idx_bits, void *out_vals, int32_t *out_idx,
                              int64_t row_out) {
-    const int tid = threadIdx.x, T = blockDim.x;
+    const int T = blockDim.x;
     if (count > kBkSlots * T || T > kBkBins) {
         select_radix_write<ELT>(cand, count, k, out_vals, out_idx, row_out);
         return;
     }
+    // the tail is a chain of dependent instructions in one workgroup: code for as many register
+    // slots as the candidates need, not for the maximum
+    if (count <= T)
+        select_bucket_rank<ELT, 1>(cand, count, k, idx_bits, out_vals, out_idx, row_out);
+    else if (count <= 2 * T)
+        select_bucket_rank<ELT, 2>(cand, count, k, idx_bits, out_vals, out_idx, row_out);
+    else
+        select_bucket_rank<ELT, kBkSlots>(cand, count, k, idx_bits, out_vals, out_idx, row_out);
+}
+
+// The fast path of select_write with NS candidates per lane in registers (count <= NS * blockDim.x).
+template <int ELT, int NS>
+__device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, int idx_bits, void *out_vals,
+                                                   int32_t *out_idx, int64_t row_out) {
+    const int tid = threadIdx.x, T = blockDim.x;
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     const int lane = tid & (kWave - 1), n_waves = T >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -355,10 +374,10 @@ __device__ void select_write(u64 *cand, int count, int k, int idx_bits, void *ou
     uint32_t *misc = abv + kBkBins + 8;  // [0] overflow flag, [1] min key, [2] max key, [3] OR of keys, [8..24) wavefront totals
 
     // ---- candidates into registers (0 = none); clear the counts
-    u64 c[kBkSlots];
+    u64 c[NS];
     uint32_t k_min = 0xffffffffu, k_max = 0u, k_or = 0u;
 #pragma unroll
-    for (int e = 0; e < kBkSlots; ++e) {
+    for (int e = 0; e < NS; ++e) {
         const int i = tid + e * T;
         c[e] = (i < count) ? cand[i] : 0ull;
     }
@@ -373,7 +392,7 @@ __device__ void select_write(u64 *cand, int count, int k, int idx_bits, void *ou
         }
     }
 #pragma unroll
-    for (int e = 0; e < kBkSlots; ++e)
+    for (int e = 0; e < NS; ++e)
         if (c[e]) {
             const uint32_t key = (uint32_t)(c[e] >> 32);
             k_min = key < k_min ? key : k_min;
@@ -403,9 +422,9 @@ __device__ void select_write(u64 *cand, int count, int k, int idx_bits, void *ou
     const u64 span = ((u64)((k_max - k_min) >> tz) + 1ull) << idx_bits;  // bin keys are below span
     const int rbits = 64 - __clzll((long long)span);
     const int bshift = rbits > 11 ? rbits - 11 : 0;
-    uint32_t bin[kBkSlots];
+    uint32_t bin[NS];
 #pragma unroll
-    for (int e = 0; e < kBkSlots; ++e) {
+    for (int e = 0; e < NS; ++e) {
         const u64 bk = ((u64)(((uint32_t)(c[e] >> 32) - k_min) >> tz) << idx_bits) | (((uint32_t)c[e] >> 1) & imask);
         bin[e] = (uint32_t)(bk >> bshift);
         if (c[e]) atomicAdd(&cnt[bin[e]], 1u);
@@ -461,15 +480,15 @@ __device__ void select_write(u64 *cand, int count, int k, int idx_bits, void *ou
     }
 
     // ---- file the possible winners by bin, in place of cand (every lane has its own in registers)
-    uint32_t start[kBkSlots];
+    uint32_t start[NS];
 #pragma unroll
-    for (int e = 0; e < kBkSlots; ++e) {
+    for (int e = 0; e < NS; ++e) {
         start[e] = c[e] ? abv[bin[e] + 4] : 0xffffffffu;
         if (start[e] < (uint32_t)k) cand[start[e] + atomicSub(&cnt[bin[e]], 1u) - 1u] = c[e];
     }
     __syncthreads();
 #pragma unroll
-    for (int e = 0; e < kBkSlots; ++e)
+    for (int e = 0; e < NS; ++e)
         if (start[e] < (uint32_t)k) {
             const uint32_t end = abv[bin[e] + 3];  // start of the next lower bin
             uint32_t r = start[e];
