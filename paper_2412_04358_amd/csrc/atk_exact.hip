@@ -127,16 +127,18 @@ __device__ __forceinline__ void for_chunk(const void *x, int64_t n, int r, int c
         if (ELT == ATK_F32) return __builtin_nontemporal_load((const uint32_t *)x + (int64_t)r * n + i);
         return ((uint32_t)__builtin_nontemporal_load((const uint16_t *)x + (int64_t)r * n + i)) << 16;
     };
+    // both loops keep whole wavefronts together (f may use wavefront-wide operations and carry
+    // wavefront-uniform state): their conditions only look at the wavefront's first element
+    const int lane = threadIdx.x & (kWave - 1);
     int64_t i = e0 + threadIdx.x;
-    for (; i + 3 * T < e1; i += 4 * T) {
+    for (; i - lane + 3 * T + (kWave - 1) < e1; i += 4 * T) {
         const uint32_t b0 = load_bits(i), b1 = load_bits(i + T), b2 = load_bits(i + 2 * T), b3 = load_bits(i + 3 * T);
         f(make_composite(b0, (int32_t)i), true);
         f(make_composite(b1, (int32_t)(i + T)), true);
         f(make_composite(b2, (int32_t)(i + 2 * T)), true);
         f(make_composite(b3, (int32_t)(i + 3 * T)), true);
     }
-    // the tail keeps whole wavefronts together (f may use wavefront-wide operations)
-    for (; i - threadIdx.x < e1; i += T) {
+    for (; i - lane < e1; i += T) {
         const bool ok = i < e1;
         f(ok ? make_composite(load_bits(i), (int32_t)i) : 0ull, ok);
     }
@@ -200,26 +202,64 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
 }
 
 // Every element at or above the row's threshold goes to sel[row][..] (exactly k of them, any order).
+// A workgroup sweeps its chunk once, counting its survivors and parking the first kStash of
+// them in LDS, then reserves their places with one atomic on the row's cursor (one per 16384
+// elements: at large k, one per wavefront and load had every wavefront of a row queueing on
+// the same counter).  Few survivors (small k) are written from LDS; if they did not all fit,
+// the chunk is swept a second time and written straight from registers.
+constexpr int kStash = 2048;
 template <int ELT>
 __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, int64_t n, ExRowState *st, u64 *sel,
                                                                  int64_t k) {
+    __shared__ u64 stash[kStash];
+    __shared__ uint32_t wave_cnt[kMaxThreads / kWave];
+    __shared__ uint32_t wave_base[kMaxThreads / kWave];
+    __shared__ uint32_t stash_n, first_pos;
     const int r = blockIdx.y;
     const u64 thr = st[r].prefix;
     u64 *dst = sel + (int64_t)r * k;
-    const int lane = threadIdx.x & (kWave - 1);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    if (threadIdx.x == 0) stash_n = 0;
+    __syncthreads();
+    uint32_t mine = 0;  // survivors of this wavefront's share (the same number in each of its lanes)
     for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
         const bool keep = ok && c >= thr;
         const u64 mask = __ballot(keep);
         if (mask) {  // uniform over the wavefront
-            const int n_keep = __popcll(mask);
-            const int leader = __ffsll((long long)mask) - 1;
-            uint32_t basepos = 0;
-            if (lane == leader) basepos = atomicAdd(&st[r].cursor, (uint32_t)n_keep);
-            basepos = (uint32_t)__builtin_amdgcn_readlane((int)basepos, leader);
-            const uint32_t pos = basepos + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-            if (keep && pos < (uint32_t)k) dst[pos] = c;
+            const uint32_t cnt = (uint32_t)__popcll(mask);
+            uint32_t at = 0;
+            if (lane == 0) at = atomicAdd(&stash_n, cnt);
+            at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at) +
+                 __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (keep && at < (uint32_t)kStash) stash[at] = c;
+            mine += cnt;
         }
+    });
+    if (lane == 0) wave_cnt[wave] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+        for (int w = 0; w < n_waves; ++w) {
+            wave_base[w] = total;
+            total += wave_cnt[w];
+        }
+        first_pos = total ? atomicAdd(&st[r].cursor, total) : 0u;
+    }
+    __syncthreads();
+    const uint32_t total = stash_n, first = first_pos;
+    if (total <= (uint32_t)kStash) {
+        for (uint32_t i = threadIdx.x; i < total; i += blockDim.x)
+            if (first + i < (uint32_t)k) dst[first + i] = stash[i];
+        return;
+    }
+    uint32_t cursor = first + wave_base[wave];
+    for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
+        const bool keep = ok && c >= thr;
+        const u64 mask = __ballot(keep);
+        const uint32_t pos = cursor + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (keep && pos < (uint32_t)k) dst[pos] = c;
+        cursor += (uint32_t)__popcll(mask);
     });
 }
 
