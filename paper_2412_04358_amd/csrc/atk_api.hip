@@ -223,6 +223,40 @@ int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, in
     const int t_max = max_threads_for_kb(p.KB);
     const int64_t chunks = ceil_div(n, b) / p.V;  // of the longest bucket (V > 1: of every bucket)
     const int64_t want_lanes = 512 * (int64_t)kNumCU;
+    if (chunks <= kWave) {
+        // Short buckets: as many lanes per bucket as it has loads (rounded up to a power of two),
+        // so that a wavefront reads one contiguous stretch, and NB buckets per lane group in turn.
+        int64_t Gs = pow2_ceil(chunks);
+        int T = T_forced ? T_forced : 256;
+        if (T > t_max) T = t_max;
+        const int64_t need = ceil_div(b * Gs, kWave) * kWave;  // lanes that cover one row's buckets
+        if (need < T) T = (int)need;
+        const int bpw = T / (int)Gs;
+        int64_t NB = (m * b * Gs) / (2 * want_lanes);
+        if (NB > 8) NB = 8;
+        if (NB > ceil_div(b, bpw)) NB = ceil_div(b, bpw);
+        if (NB < 1) NB = 1;
+        p.Gs = (int)Gs;
+        p.T = T;
+        p.NB = (int)NB;
+        p.bblocks = (int)ceil_div(b, bpw * NB);
+        p.S = 1;
+        p.chunks_per_split = (int)chunks;
+        p.use_scratch = p.stage2 && p.bblocks > 1;
+        p.tail_tpc = 1;
+        if (p.stage2 && b * k_b > kStage2MaxCand) return ATK_ERR_UNSUPPORTED;
+        const int64_t lds_s2 = p.stage2 ? select_lds_bytes(b * k_b, (int)pow2_ceil(k)) : 0;
+        p.lds_xch_off = 16;
+        p.lds_cand_off = 16;
+        p.lds_bytes = (int)(16 + lds_s2);
+        if (p.lds_bytes > kLdsBudget) return ATK_ERR_UNSUPPORTED;
+        p.scratch_ticket_bytes = p.use_scratch ? m * kTicketStride * 4 : 0;
+        p.scratch_lists_bytes = p.use_scratch ? m * b * k_b * 8 : 0;
+        p.grid = m * p.bblocks;
+        if (p.grid >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
+        *pl = p;
+        return ATK_OK;
+    }
     int64_t Gs = 1;
     while (Gs * 2 <= t_max && Gs * 16 <= chunks) Gs <<= 1;                          // about 8..16 loads per lane
     while (Gs * 2 <= t_max && Gs * 2 <= chunks && m * b * Gs < want_lanes) Gs <<= 1;  // more lanes, down to one load each
@@ -442,9 +476,9 @@ int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     rc = make_contig_plan(m, n, k, b, k_b, dtype, true, &pl);
     if (rc != ATK_OK) return rc;
     snprintf(buf, (size_t)buflen,
-             "contiguous V=%d KB=%d T=%d Gs=%d bblocks=%d S=%d chunks_per_split=%d grid=%lld stage2=%d scratch=%d "
+             "contiguous V=%d KB=%d T=%d Gs=%d NB=%d bblocks=%d S=%d chunks_per_split=%d grid=%lld stage2=%d scratch=%d "
              "lds=%d scratch_bytes=%lld",
-             pl.V, pl.KB, pl.T, pl.Gs, pl.bblocks, pl.S, pl.chunks_per_split, (long long)pl.grid, (int)pl.stage2,
+             pl.V, pl.KB, pl.T, pl.Gs, pl.NB, pl.bblocks, pl.S, pl.chunks_per_split, (long long)pl.grid, (int)pl.stage2,
              (int)pl.use_scratch, pl.lds_bytes, (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes));
     return ATK_OK;
 }

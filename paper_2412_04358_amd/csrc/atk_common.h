@@ -101,6 +101,7 @@ struct Plan {
     int Gs;           // lanes side by side on one bucket (a power of two)
     int bblocks;      // workgroups side by side across the b buckets
     int chunks_per_split;  // V-element chunks of a bucket per row split
+    int NB;           // short buckets (one load per lane): buckets a lane group takes in turn, else 0
     int64_t scratch_lists_bytes;   // composites
     int64_t scratch_ticket_bytes;  // one counter per row
     int lds_bytes;    // dynamic LDS of the launch

@@ -43,6 +43,7 @@ struct S1Params {
     int Gs, gs_shift;    // lanes per bucket (a power of two) and its log2
     int bblocks;         // workgroups side by side across the b buckets
     int chunks_per_split;
+    int NB;              // short buckets: buckets a lane group takes in turn (0: one bucket per group)
 };
 
 template <int ELT, int V>
@@ -558,7 +559,66 @@ __global__ void __launch_bounds__(MAXT) contig_kernel(S1Params p) {
     divmod(wg, p.bblocks, -1, wg, bb);
     divmod(wg, p.S, p.s_shift, r, sp);
     const int g = tid >> p.gs_shift, q = tid & (p.Gs - 1);
-    const int bpw = T >> p.gs_shift;  // buckets per workgroup
+    const int bpw = T >> p.gs_shift;  // buckets the workgroup works on at a time
+
+    // ---- short buckets: a bucket is one load per lane of its group; the group takes NB buckets in turn
+    if (p.NB > 0) {
+        const int first = bb * bpw * p.NB;  // first bucket of this workgroup
+        u64 *cand = (u64 *)(smem + p.lds_cand_off);
+        for (int i0 = 0; i0 < p.NB; i0 += U) {
+            RowVec<ELT, V> v[U];
+            int bj[U];
+            int64_t r0[U];
+            bool has[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int jj = first + (i0 + u) * bpw + g;
+                const bool ok = (i0 + u < p.NB) && jj < p.b;
+                int64_t a0 = 0, a1 = 0;
+                if (ok) {
+                    if (p.rem == 0) {
+                        a0 = (int64_t)jj * p.L;
+                        a1 = a0 + p.L;
+                    } else {
+                        a0 = ((int64_t)jj * p.n + p.b - 1) / p.b;
+                        a1 = ((int64_t)(jj + 1) * p.n + p.b - 1) / p.b;
+                    }
+                }
+                bj[u] = ok ? jj : -1;
+                r0[u] = a0;
+                has[u] = ok && (int64_t)q * V < a1 - a0;
+                if (has[u]) v[u] = load_vec<ELT, V>((const unsigned char *)p.x + ((int64_t)r * p.n + a0 + (int64_t)q * V) * ES);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float val[KB];
+                int tt[KB];
+#pragma unroll
+                for (int i = 0; i < KB; ++i) {
+                    val[i] = __uint_as_float(0x7fc00000u);
+                    tt[i] = kEmptyT;
+                }
+                if (has[u]) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) insert<KB>(val, tt, __uint_as_float(elem_bits<ELT, V>(v[u], e)), q * V + e);
+                }
+                u64 comp[KB];
+#pragma unroll
+                for (int i = 0; i < KB; ++i)
+                    comp[i] = (tt[i] != kEmptyT) ? make_composite(__float_as_uint(val[i]), (int32_t)(r0[u] + tt[i])) : 0ull;
+                for (int off = 1; off < p.Gs; off <<= 1) {
+                    u64 theirs[KB];
+#pragma unroll
+                    for (int i = 0; i < KB; ++i) theirs[i] = shfl_xor_u64(comp[i], off);
+                    merge_topk<KB>(comp, theirs);
+                }
+                if (q == 0 && bj[u] >= 0) emit_list<ELT, KB>(p, r, 0, bj[u], comp, cand);
+            }
+        }
+        row_tail<ELT, KB>(p, r, (int64_t)r, 0, p.b, 0, smem);  // no row splits here: a ticket only with Stage 2
+        return;
+    }
+
     const int j = bb * bpw + g;       // this lane's bucket
     const bool active = j < p.b;
 
@@ -756,6 +816,8 @@ hipError_t launch_approx_contig(const Plan &pl, const void *x, void *out_vals, i
     prm.gs_shift = log2_exact(pl.Gs);
     prm.bblocks = pl.bblocks;
     prm.chunks_per_split = pl.chunks_per_split;
+    prm.NB = pl.NB;
+    prm.rem = (int)(pl.n % pl.b);
     {
         const char *e = getenv("ATK_SYNC");
         prm.fence_sync = (e && strcmp(e, "fence") == 0) ? 1 : 0;

@@ -434,3 +434,40 @@ def test_alternating_sizes_share_the_scratch_pool():
         run_case(big, 64, 256, 1, tag="big")
         run_case(small, 128, 64, 2, tag="small")
         run_case(big, 64, 64, 1, tag="big")
+
+
+def test_hip_graph_replay_matches_eager():
+    """The calls can be captured in a HIP graph once the scratch pool has its size: replays, with
+    eager work and synchronisations between them, give the eager results every time."""
+    x1 = workloads.normal_rows(16, 32768, seed=31).cuda()
+    x2 = workloads.normal_rows(16, 32768, seed=32).cuda()
+    cases = [(64, 64, 1), (64, 512, 1), (128, 32, 4), (4096, 4096, 1)]
+    eager = {}
+    for xi, x in enumerate((x1, x2)):
+        for c in cases:
+            v, i = atk.approx_topk(x, *c)
+            eager[(xi, c)] = (v.clone(), i.clone())
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    xin = x1.clone()
+    outs = {c: (torch.empty((16, c[0]), dtype=torch.float32, device="cuda"),
+                torch.empty((16, c[0]), dtype=torch.int32, device="cuda")) for c in cases}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        for c in cases:  # warm-up on the capture stream
+            atk.approx_topk(xin, *c, out=outs[c])
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for c in cases:
+                atk.approx_topk(xin, *c, out=outs[c])
+    for rep in range(4):
+        xi = rep % 2
+        xin.copy_((x1, x2)[xi])
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for c in cases:
+            assert torch.equal(outs[c][0], eager[(xi, c)][0]) and torch.equal(outs[c][1], eager[(xi, c)][1]), (rep, c)
+        # eager work between the replays, on the same pool
+        v, i = atk.approx_topk(x2, 64, 256, 1)
+        assert torch.equal(i, atk.approx_topk(x2, 64, 256, 1)[1])

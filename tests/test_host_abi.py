@@ -156,7 +156,9 @@ def test_contiguous_plan_shapes(lib):
             if p["V"] > 1:
                 assert n % b == 0 and (n // b) % p["V"] == 0
             chunks = -(-n // b) // p["V"]
-            assert p["bblocks"] * (T // Gs) >= b
+            assert p["bblocks"] * (T // Gs) * max(1, p["NB"]) >= b
+            if p["NB"] > 0:
+                assert chunks <= Gs <= 64 and p["S"] == 1
             assert p["S"] * p["chunks_per_split"] >= chunks and (p["S"] - 1) * p["chunks_per_split"] < chunks
             assert p["S"] == 1 or Gs == T
             assert p["grid"] == m * p["S"] * p["bblocks"]
@@ -164,7 +166,7 @@ def test_contiguous_plan_shapes(lib):
             assert p["scratch"] == int(p["S"] > 1 or (p["stage2"] == 1 and p["bblocks"] > 1))
     # a short run per bucket: one lane each, written straight out
     p = parse_contig_plan(atk.plan_describe(128, 65536, 16384, 16384, 1, atk.ATK_F32, C))
-    assert p["Gs"] == 1 and p["V"] == 4 and p["scratch"] == 0
+    assert p["Gs"] == 1 and p["V"] == 4 and p["scratch"] == 0 and p["NB"] >= 1
     # one long row, few buckets: whole workgroups per bucket and row splits
     p = parse_contig_plan(atk.plan_describe(1, 1 << 20, 64, 8, 8, atk.ATK_F32, C))
     assert p["Gs"] == p["T"] and p["S"] > 1 and p["scratch"] == 1
@@ -244,3 +246,15 @@ def test_advise(lib):
     assert lib.atk_advise(128, 65536, 64, 0, 1.5, ctypes.byref(bb), ctypes.byref(kk), None, None) == PARAMS
     assert lib.atk_advise(128, 65536, 64, 0, 0.9, None, ctypes.byref(kk), None, None) == NULLP
     assert lib.atk_advise(128, 65536, 0, 0, 0.9, ctypes.byref(bb), ctypes.byref(kk), None, None) == SHAPE
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    """No CPU fallback: without the built library the binding raises on first use."""
+    from paper_2412_04358_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", os.path.join(ROOT, "paper_2412_04358_amd", "lib", "no_such_library.so"))
+    with pytest.raises(RuntimeError, match="not built"):
+        binding.load_library()
+    with pytest.raises(RuntimeError, match="not built"):
+        binding.plan_describe(4, 4096, 64, 64, 1)
