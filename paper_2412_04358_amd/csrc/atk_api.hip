@@ -125,9 +125,24 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (T_forced) T = T_forced;
     if (T > t_max) T = t_max;
 
+    // Long queues (k_b >= 5) on short buckets are bound by the chain of dependent selects of each
+    // insertion: with one lane per column group and few column groups there are too few
+    // independent chains per SIMD.  Then lanes share column groups inside the workgroup (P row
+    // phases, merged once through LDS) until about one wavefront per SIMD is there (measured:
+    // 14.3 -> 11.5 us at m = 32 on the 65536-long rows with k_b = 8; at m = 128 the merge costs more
+    // than the extra lanes bring).
+    int p_want = 1;
+    if (p.KB >= 8 && p.G >= T && !T_forced)
+        while (p_want < 4 && m * p.G * p_want < 64 * 4 * (int64_t)kNumCU && p.L >= 4 * p_want * 2) p_want <<= 1;
+    {
+        const char *e = getenv("ATK_PLAN");
+        const char *q = e ? strstr(e, "P=") : nullptr;
+        if (q && (q == e || q[-1] == ',') && (atoi(q + 2) == 1 || atoi(q + 2) == 2 || atoi(q + 2) == 4)) p_want = atoi(q + 2);
+    }
+
     int64_t lds = 0;
     for (;;) {
-        p.Gw = (int)((p.G < T) ? p.G : T);
+        p.Gw = (int)((p.G < T / p_want) ? p.G : T / p_want);
         p.P = T / p.Gw;
         if (p.P > p.L) p.P = (int)p.L;
         if (p.P < 1) p.P = 1;
@@ -136,7 +151,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         p.T = t_used;
         p.wave_merge = p.P > 1 && p.Gw < kWave && (p.Gw & (p.Gw - 1)) == 0;
         p.nparts = p.wave_merge ? p.T / kWave : p.P;
-        const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * b * p.KB * 8 : 0;
+        const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * std::min<int64_t>(b, (int64_t)p.Gw * p.V) * p.KB * 8 : 0;
         const int64_t lds_s2 = p.stage2 ? select_lds_bytes(b * k_b, (int)pow2_ceil(k)) : 0;
         p.lds_xch_off = 16;
         p.lds_cand_off = (int)(16 + lds_xch);
@@ -183,7 +198,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (p.use_scratch && p.stage2) {
         // the candidates are gathered by the last workgroup of the row, after its exchange area
         // is dead, so the two share LDS (without splits emit() fills one while the other is read)
-        const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * b * p.KB * 8 : 0;
+        const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * std::min<int64_t>(b, (int64_t)p.Gw * p.V) * p.KB * 8 : 0;
         const int64_t lds_s2 = select_lds_bytes(b * k_b, (int)pow2_ceil(k));
         p.lds_cand_off = 16;
         p.lds_bytes = (int)(16 + (lds_xch > lds_s2 ? lds_xch : lds_s2));

@@ -381,12 +381,37 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
                 if (e >= rot) ATK_FEED_ELEM(e, (elem_bits<ELT, V>(v, e)), 0);
             t += step;
         }
-        for (; t + (U - 1) * step < t1; t += U * step) {
-            RowVec<ELT, V> v[U];
+        if (KB == 8) {
+            // The next batch's loads are issued before the current one is worked on (measured:
+            // 4-7 % at eight slots, nothing or a loss at other queue lengths).
+            RowVec<ELT, V> v[U], w[U];
+            bool have = t + (U - 1) * step < t1;
+            if (have) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes);
+                for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes);
+            }
+            while (have) {
+                const int tn = t + U * step;
+                const bool more = tn + (U - 1) * step < t1;
+                if (more) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) ATK_FEED_VEC(v[u], t + u * step);
+                    for (int u = 0; u < U; ++u) w[u] = load_vec<ELT, V>(base + (int64_t)(tn + u * step) * row_bytes);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) ATK_FEED_VEC(v[u], t + u * step);
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = w[u];
+                t = tn;
+                have = more;
+            }
+        } else {
+            for (; t + (U - 1) * step < t1; t += U * step) {
+                RowVec<ELT, V> v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes);
+#pragma unroll
+                for (int u = 0; u < U; ++u) ATK_FEED_VEC(v[u], t + u * step);
+            }
         }
         for (; t < t1; t += step) {
             RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)t * row_bytes);
@@ -506,29 +531,32 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 
     // ---------------------------------------------------------------- merge across wavefronts (LDS, one barrier)
     if (p.nparts > 1) {
-        // only reached with one column block (G < T), so the workgroup's columns are 0..b-1
+        // columns are numbered from the first one of this workgroup's column block
         u64 *xch = (u64 *)(smem + p.lds_xch_off);  // [part][column][slot]
         const int lane = tid & (kWave - 1);
         const int part = p.wave_merge ? (tid >> 6) : ph;
         const bool holder = active && (!p.wave_merge || lane < p.Gw);
+        const int colbase = cb * p.Gw * V;
+        const int wcols = min(p.Gw * V, p.b - colbase);
+        const int64_t pstride = (int64_t)p.Gw * V;  // columns per part
         if (holder) {
 #pragma unroll
             for (int e = 0; e < V; ++e)
 #pragma unroll
-                for (int j = 0; j < KB; ++j) xch[((int64_t)part * p.b + col0 + e) * KB + j] = comp[e][j];
+                for (int j = 0; j < KB; ++j) xch[((int64_t)part * pstride + cgl * V + e) * KB + j] = comp[e][j];
         }
         __syncthreads();
-        for (int c = tid; c < p.b; c += T) {
+        for (int c = tid; c < wcols; c += T) {
             u64 acc[KB];
 #pragma unroll
             for (int j = 0; j < KB; ++j) acc[j] = xch[(int64_t)c * KB + j];
             for (int q = 1; q < p.nparts; ++q) {
                 u64 theirs[KB];
 #pragma unroll
-                for (int j = 0; j < KB; ++j) theirs[j] = xch[((int64_t)q * p.b + c) * KB + j];
+                for (int j = 0; j < KB; ++j) theirs[j] = xch[((int64_t)q * pstride + c) * KB + j];
                 merge_topk<KB>(acc, theirs);
             }
-            emit(bucket_of(c), acc);
+            emit(bucket_of(colbase + c), acc);
         }
     } else if (active && (!p.wave_merge || (tid & (kWave - 1)) < p.Gw)) {
 #pragma unroll

@@ -179,14 +179,16 @@ def test_shapes(dtype):
         run_case(x, k, b, k_b, tag="shape%d" % i)
 
 
-@pytest.mark.parametrize("plan", ["T=64,S=1", "T=64,S=7", "T=128,S=3", "T=256,S=2", "T=256,S=64", "T=512,S=1", "T=1024,S=2", "T=1024,S=5"])
+@pytest.mark.parametrize("plan", ["T=64,S=1", "T=64,S=7", "T=128,S=3", "T=256,S=2", "T=256,S=64", "T=512,S=1", "T=1024,S=2", "T=1024,S=5",
+                                  "P=2", "P=4", "T=128,P=2,S=3"])
 def test_forced_plans(plan, monkeypatch):
     """The same results whatever the launch geometry (threads per workgroup, row splits)."""
     monkeypatch.setenv("ATK_PLAN", plan)
     for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (3, 32768, 2048, 2048, 1),
                                            (3, 32768, 128, 64, 2), (3, 32768, 100, 32, 4), (2, 32768, 64, 8, 8),
                                            (2, 32768, 200, 16, 16), (3, 32771, 2048, 2048, 1), (3, 32770, 128, 64, 2),
-                                           (3, 32773, 4096, 1024, 4)]):
+                                           (3, 32773, 4096, 1024, 4), (2, 32768, 4096, 512, 8), (2, 32772, 8192, 512, 16),
+                                           (2, 32768, 100, 512, 8)]):
         for dtype in ["f32", "bf16"]:
             x = workloads.normal_rows(m, n, seed=200 + i, dtype=dtype)
             run_case(x, k, b, k_b, tag=plan)
