@@ -108,6 +108,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int64_t want_threads = n_vec / 16;
     if (want_threads < 512 * (int64_t)kNumCU) want_threads = 512 * (int64_t)kNumCU;
     if (want_threads > 2048 * (int64_t)kNumCU) want_threads = 2048 * (int64_t)kNumCU;
+    // with queues, a lane that sees more rows inserts less often: half as many lanes measured faster
+    if (p.KB >= 4 && want_threads > 1024 * (int64_t)kNumCU) want_threads = 1024 * (int64_t)kNumCU;
     int T = 256;
     if (p.G <= 256) {
         const int t_cols = (int)(ceil_div(p.G, kWave) * kWave);  // lanes that give every column group one lane
