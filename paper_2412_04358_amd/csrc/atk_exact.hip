@@ -25,13 +25,17 @@ constexpr int kExWidth[kExPasses] = {11, 11, 10, 11, 11, 10};
 constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps
 constexpr int kSortTile = 2048;          // elements per workgroup of the global sort
 constexpr int kSortLdsMaxK = 4096;       // survivors ordered in LDS by one workgroup
+constexpr int kFilterMaxK = 1024;        // largest k that takes the copy-out path (its selection must fit 64 KB of LDS)
+constexpr int kFilterCap = 4096;         // elements at or above the first digit's bucket that one workgroup selects from in LDS
 
 struct ExRowState {  // one per row, 32 bytes
     u64 prefix;      // decided high bits of the threshold
     uint32_t need;   // elements still needed inside the current bucket
     uint32_t done;   // threshold known
     uint32_t cursor; // survivors written so far
-    uint32_t pad[3];
+    uint32_t mode;   // 0: digit by digit; 1: few enough elements share the first digit's bucket or lie above it -
+                     // they are copied out and selected in LDS; 2: finished that way
+    uint32_t pad[2];
 };
 
 int64_t pow2_ceil64(int64_t v) {
@@ -70,6 +74,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     int64_t bytes = m * (int64_t)sizeof(ExRowState);
     bytes = ceil_div64(bytes, 256) * 256;
     bytes += m * k * 8;
+    if (k <= kFilterMaxK) bytes += m * (int64_t)kFilterCap * 8;  // copy-out buffer of the small-k path
     if (k > kSortLdsMaxK) {
         bytes += m * k * 8;
         bytes += m * ceil_div64(k, kSortTile) * 256 * 4;
@@ -114,6 +119,7 @@ __global__ void ex_init_kernel(ExRowState *st, int m, uint32_t k) {
         st[r].need = k;
         st[r].done = 0u;
         st[r].cursor = 0u;
+        st[r].mode = 0u;
     }
 }
 
@@ -168,7 +174,10 @@ __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, int
 
 // One workgroup (256 lanes) per row: pick the digit bucket that holds the need-th largest
 // element, update the row state, and leave the global histogram zeroed.
-__global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t *ghist, int shift, int last_pass) {
+// filter_cap > 0 (first pass only): a row with at most that many elements in or above the chosen
+// bucket, and not finished by this pass alone, is handed to the copy-out path (mode 1).
+__global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t *ghist, int shift, int last_pass,
+                                                        uint32_t filter_cap) {
     __shared__ uint32_t wave_tot[4];
     const int r = blockIdx.x, tid = threadIdx.x;
     if (st[r].done) return;
@@ -195,7 +204,9 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
             const uint32_t left = need - above;
             st[r].prefix |= (u64)(uint32_t)(base + q) << shift;
             st[r].need = left;
-            st[r].done = (hb[q] == left || last_pass) ? 1u : 0u;
+            const bool done = hb[q] == left || last_pass;
+            st[r].done = done ? 1u : 0u;
+            if (filter_cap && !done && with <= filter_cap) st[r].mode = 1u;
         }
         above = with;
     }
@@ -208,7 +219,9 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
 // the same counter).  Few survivors (small k) are written from LDS; if they did not all fit,
 // the chunk is swept a second time and written straight from registers.
 constexpr int kStash = 2048;
-template <int ELT>
+// FILTER: the same sweep for the rows in mode 1, whose threshold so far is just the first digit:
+// at most kFilterCap elements per row reach it, and they go to a buffer of that stride.
+template <int ELT, bool FILTER>
 __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, int64_t n, ExRowState *st, u64 *sel,
                                                                  int64_t k) {
     __shared__ u64 stash[kStash];
@@ -216,8 +229,9 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
     __shared__ uint32_t wave_base[kMaxThreads / kWave];
     __shared__ uint32_t stash_n, first_pos;
     const int r = blockIdx.y;
+    if (FILTER ? st[r].mode != 1u : st[r].mode == 2u) return;  // uniform over the workgroup
     const u64 thr = st[r].prefix;
-    u64 *dst = sel + (int64_t)r * k;
+    u64 *dst = sel + (int64_t)r * k;  // k: the row stride of sel (kFilterCap for FILTER)
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
     if (threadIdx.x == 0) stash_n = 0;
     __syncthreads();
@@ -265,17 +279,37 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
 
 // k <= kSortLdsMaxK: one workgroup per row orders the survivors in LDS and writes the outputs.
 template <int ELT>
-__global__ void __launch_bounds__(kMaxThreads) ex_order_lds_kernel(const u64 *sel, int k, void *out_vals,
-                                                                   int32_t *out_idx) {
+__global__ void __launch_bounds__(kMaxThreads) ex_order_lds_kernel(const u64 *sel, const ExRowState *st, int k,
+                                                                   void *out_vals, int32_t *out_idx) {
     extern __shared__ __align__(16) unsigned char smem[];
     u64 *s = (u64 *)smem;
     const int kp = pow2_ceil_dev(k);
     uint32_t *rk = (uint32_t *)(s + kp);
     const int r = blockIdx.x;
+    if (st[r].mode == 2u) return;  // already written by the copy-out path
     for (int i = threadIdx.x; i < k; i += blockDim.x) s[i] = sel[(int64_t)r * k + i];
     for (int i = threadIdx.x; i < kRankMax; i += blockDim.x) rk[i] = 0;
     __syncthreads();
     order_write<ELT>(s, k, rk, out_vals, out_idx, (int64_t)r);
+}
+
+// Rows in mode 1: the copied-out elements (at most kFilterCap) contain the k largest; one workgroup
+// selects and orders them in LDS, writes the outputs and marks the row finished.
+template <int ELT>
+__global__ void __launch_bounds__(kMaxThreads) ex_filter_select_kernel(const u64 *buf, ExRowState *st, int k, int idx_bits,
+                                                                       void *out_vals, int32_t *out_idx) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    u64 *cand = (u64 *)smem;
+    const int r = blockIdx.x;
+    if (st[r].mode != 1u) return;  // uniform; read by every lane before lane 0 changes it below
+    const int count = (int)st[r].cursor;
+    for (int i = threadIdx.x; i < count; i += blockDim.x) cand[i] = buf[(int64_t)r * kFilterCap + i];
+    __syncthreads();
+    select_write<ELT>(cand, count, k, idx_bits, out_vals, out_idx, (int64_t)r);
+    if (threadIdx.x == 0) {
+        st[r].mode = 2u;
+        st[r].done = 1u;
+    }
 }
 
 // ---- global least-significant-digit radix sort of the survivors, descending, 8-bit digits ----
@@ -384,19 +418,32 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
     const dim3 sweep((unsigned)pl.chunks, (unsigned)m);
 
     hipLaunchKernelGGL(ex_init_kernel, dim3((unsigned)ceil_div64(m, 256)), dim3(256), 0, stream, st, (int)m, (uint32_t)k);
+    // Small k: after the first digit most rows have only a handful of elements left in play; those
+    // are copied out in one more sweep and finished in LDS instead of being swept digit by digit.
+    const bool filter = k <= kFilterMaxK;
+    int idx_bits = 1;  // column indices are below 2^idx_bits
+    while (((int64_t)1 << idx_bits) < n) ++idx_bits;
     for (int p = 0; p < kExPasses; ++p) {
         hipLaunchKernelGGL(ex_hist_kernel<ELT>, sweep, dim3(kMaxThreads), 0, stream, x, n, st, ghist, kExShift[p],
                            kExWidth[p]);
         hipLaunchKernelGGL(ex_decide_kernel, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p],
-                           p == kExPasses - 1 ? 1 : 0);
+                           p == kExPasses - 1 ? 1 : 0, (uint32_t)((p == 0 && filter) ? kFilterCap : 0));
+        if (p == 0 && filter) {
+            u64 *fbuf = sel + m * k;
+            hipLaunchKernelGGL((ex_collect_kernel<ELT, true>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, fbuf,
+                               (int64_t)kFilterCap);
+            const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
+            hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st,
+                               (int)k, idx_bits, out_vals, out_idx);
+        }
     }
-    hipLaunchKernelGGL(ex_collect_kernel<ELT>, sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
+    hipLaunchKernelGGL((ex_collect_kernel<ELT, false>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
     if (k <= kSortLdsMaxK) {
         const size_t lds = (size_t)pow2_ceil64(k) * 8 + kRankMax * 4;
-        hipLaunchKernelGGL(ex_order_lds_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), lds, stream, sel, (int)k,
+        hipLaunchKernelGGL(ex_order_lds_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), lds, stream, sel, st, (int)k,
                            out_vals, out_idx);
         return hipGetLastError();
     }
@@ -404,8 +451,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
     u64 *bufs[2] = {sel, sel + m * k};
     uint32_t *tile_hist = (uint32_t *)(bufs[1] + m * k);
     const int tiles = (int)ceil_div64(k, kSortTile);
-    int idx_bits = 1;  // the index field holds 0x7fffffff - idx in bits [31:1]; bit 0 is the zero-sign flag
-    while (((int64_t)1 << idx_bits) < n) ++idx_bits;
+    // (the index field holds 0x7fffffff - idx in bits [31:1]; bit 0 is the zero-sign flag)
     int cur = 0;
     for (int shift = 0; shift < 64; shift += 8) {
         if (shift < 32 && shift >= idx_bits + 1) continue;

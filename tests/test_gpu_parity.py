@@ -393,6 +393,15 @@ def test_exact_long_rows(dtype):
     run_exact(workloads.few_levels(3, 30000, levels=2, seed=5, dtype=dtype), 777)
     run_exact(workloads.few_levels(2, 30000, levels=1, seed=6, dtype=dtype), 9000)
     run_exact(workloads.special_values(2, 40000, seed=7, dtype=dtype), 6000)
+    # small k on long rows: after the first digit the elements still in play are copied out and finished
+    # in LDS; rows with too many of them (ties, few levels) stay on the digit-by-digit path, both in one call
+    for m, n, k in [(5, 200000, 64), (3, 200000, 1000), (4, 65536, 1), (2, 1 << 20, 256)]:
+        run_exact(workloads.normal_rows(m, n, seed=500 + k, dtype=dtype), k)
+    mixed = torch.cat([workloads.normal_rows(2, 60000, seed=11, dtype=dtype),
+                       workloads.few_levels(2, 60000, levels=2, seed=12, dtype=dtype),
+                       workloads.special_values(1, 60000, seed=13, dtype=dtype)])
+    run_exact(mixed, 100)
+    run_exact(mixed, 1024)
 
 
 def test_exact_cfg4():
