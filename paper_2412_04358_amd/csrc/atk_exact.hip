@@ -25,6 +25,9 @@ constexpr int kExWidth[kExPasses] = {11, 11, 10, 11, 11, 10};
 constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps
 constexpr int kSortTile = 2048;          // elements per workgroup of the global sort
 constexpr int kSortLdsMaxK = 4096;       // survivors ordered in LDS by one workgroup
+constexpr int kPartTile = 4096;          // survivors per workgroup of the partition sort's sweeps
+constexpr int kPartMaxBins = 2048;
+constexpr int kPartWaveMax = 512;        // largest bin that one wavefront orders on its own
 constexpr int kFilterMaxK = 1024;        // largest k that takes the copy-out path (its selection must fit 64 KB of LDS)
 constexpr int kFilterCap = 4096;         // elements at or above the first digit's bucket that one workgroup selects from in LDS
 
@@ -34,8 +37,9 @@ struct ExRowState {  // one per row, 32 bytes
     uint32_t done;   // threshold known
     uint32_t cursor; // survivors written so far
     uint32_t mode;   // 0: digit by digit; 1: few enough elements share the first digit's bucket or lie above it -
-                     // they are copied out and selected in LDS; 2: finished that way
-    uint32_t pad[2];
+                     // they are copied out and selected in LDS; 2: finished that way; 3 (large k): the
+                     // survivors are ordered by the digit-by-digit global sort, not by the partition sort
+    u64 cmax;        // largest survivor (large k)
 };
 
 int64_t pow2_ceil64(int64_t v) {
@@ -78,6 +82,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     if (k > kSortLdsMaxK) {
         bytes += m * k * 8;
         bytes += m * ceil_div64(k, kSortTile) * 256 * 4;
+        bytes += 256 + m * (int64_t)kPartMaxBins * 4 * 4;  // partition sort: list of big bins, counts, starts, cursors
     }
     p.scratch_bytes = bytes;
     *pl = p;
@@ -120,6 +125,7 @@ __global__ void ex_init_kernel(ExRowState *st, int m, uint32_t k) {
         st[r].done = 0u;
         st[r].cursor = 0u;
         st[r].mode = 0u;
+        st[r].cmax = 0ull;
     }
 }
 
@@ -236,8 +242,10 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
     if (threadIdx.x == 0) stash_n = 0;
     __syncthreads();
     uint32_t mine = 0;  // survivors of this wavefront's share (the same number in each of its lanes)
+    u64 cmax_local = 0ull;
     for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
         const bool keep = ok && c >= thr;
+        if (!FILTER && keep && c > cmax_local) cmax_local = c;
         const u64 mask = __ballot(keep);
         if (mask) {  // uniform over the wavefront
             const uint32_t cnt = (uint32_t)__popcll(mask);
@@ -250,6 +258,11 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
         }
     });
     if (lane == 0) wave_cnt[wave] = mine;
+    if (!FILTER) {  // the row's largest survivor, for the partition sort's bins
+        u64 lo = ~0ull, hi = cmax_local;
+        wave_min_max_u64(lo, hi);
+        if (lane == 0 && hi) atomicMax((unsigned long long *)&st[r].cmax, (unsigned long long)hi);
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t total = 0;
@@ -312,12 +325,258 @@ __global__ void __launch_bounds__(kMaxThreads) ex_filter_select_kernel(const u64
     }
 }
 
+// ---- partition sort of many survivors (k > kSortLdsMaxK) -------------------------------------------
+// The k survivors of a row lie between its threshold and its largest element.  They are cut
+// into nb bins that are linear in (composite - threshold), a counting pass and a scatter pass
+// bring every bin together (highest bin first), and one workgroup per bin orders it in LDS.
+// Composites are distinct, so the order is total.  A row in which some bin is too big for LDS
+// (values piled on a few levels) is marked mode 3 and left to the digit-by-digit sort below.
+struct PartRow {  // per row
+    uint32_t shift;
+    uint32_t pad;
+};
+__device__ __forceinline__ uint32_t part_shift(u64 span, int nb) {  // smallest s with (span >> s) < nb
+    const int bits = span ? 64 - __clzll((long long)span) : 0;
+    int lg = 0;
+    while ((1 << lg) < nb) ++lg;
+    return bits > lg ? (uint32_t)(bits - lg) : 0u;
+}
+
+__global__ void __launch_bounds__(256) part_zero_kernel(uint32_t *words, int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) words[i] = 0u;
+}
+
+// counts[row][bin] += elements of this tile in bin
+__global__ void __launch_bounds__(256) part_hist_kernel(const u64 *sel, const ExRowState *st, int64_t k, int nb,
+                                                        uint32_t *counts) {
+    __shared__ uint32_t lh[kPartMaxBins];
+    const int r = blockIdx.y, tid = threadIdx.x;
+    const u64 thr = st[r].prefix;
+    const uint32_t shift = part_shift(st[r].cmax - thr, nb);
+    for (int i = tid; i < nb; i += 256) lh[i] = 0;
+    __syncthreads();
+    const int64_t e0 = (int64_t)blockIdx.x * kPartTile;
+    const u64 *row = sel + (int64_t)r * k;
+    for (int j = 0; j < kPartTile / 256; ++j) {
+        const int64_t i = e0 + j * 256 + tid;
+        if (i < k) atomicAdd(&lh[(uint32_t)((row[i] - thr) >> shift)], 1u);
+    }
+    __syncthreads();
+    uint32_t *gc = counts + (int64_t)r * nb;
+    for (int i = tid; i < nb; i += 256) {
+        const uint32_t v = lh[i];
+        if (v) atomicAdd(&gc[i], v);
+    }
+}
+
+// one workgroup per row: starts[row][bin] = survivors in higher bins; cursors cleared; rows with a
+// bin beyond what one workgroup orders in LDS go to the other sort
+// (and the bins too big for one wavefront to rank are listed in big[1..], their number in big[0])
+__global__ void __launch_bounds__(256) part_scan_kernel(ExRowState *st, int nb, const uint32_t *counts, uint32_t *starts,
+                                                        uint32_t *cursors, uint32_t *big) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t too_big;
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *gc = counts + (int64_t)r * nb;
+    if (tid == 0) too_big = 0;
+    __syncthreads();
+    // lane t owns the q bins below nb - t*q: lane order is descending bin order
+    const int q = nb / 256 > 0 ? nb / 256 : 1;
+    const int hi = nb - 1 - tid * q;
+    uint32_t s = 0, mx = 0;
+    for (int j = 0; j < q; ++j) {
+        const uint32_t v = (hi - j >= 0) ? gc[hi - j] : 0u;
+        s += v;
+        mx = v > mx ? v : mx;
+    }
+    if (mx > (uint32_t)kSortLdsMaxK) too_big = 1;
+    const uint32_t incl = wave_incl_scan_u32(s);
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+    __syncthreads();
+    uint32_t run = incl - s;
+    for (int w = 0; w < (tid >> 6); ++w) run += wave_tot[w];
+    for (int j = 0; j < q; ++j)
+        if (hi - j >= 0) {
+            starts[(int64_t)r * nb + hi - j] = run;
+            cursors[(int64_t)r * nb + hi - j] = 0u;
+            run += gc[hi - j];
+        }
+    if (too_big) {
+        if (tid == 0) st[r].mode = 3u;
+        return;
+    }
+    for (int j = 0; j < q; ++j)
+        if (hi - j >= 0 && gc[hi - j] > (uint32_t)kPartWaveMax) big[1 + atomicAdd(&big[0], 1u)] = (uint32_t)r * kPartMaxBins + (uint32_t)(hi - j);
+}
+
+// every element of the tile goes to its bin's segment of dst (any order inside the bin)
+__global__ void __launch_bounds__(256) part_scatter_kernel(const u64 *sel, u64 *dst, const ExRowState *st, int64_t k, int nb,
+                                                           const uint32_t *starts, uint32_t *cursors) {
+    __shared__ uint32_t lh[kPartMaxBins];    // count of the tile per bin, then position of the next element
+    const int r = blockIdx.y, tid = threadIdx.x;
+    if (st[r].mode == 3u) return;
+    const u64 thr = st[r].prefix;
+    const uint32_t shift = part_shift(st[r].cmax - thr, nb);
+    for (int i = tid; i < nb; i += 256) lh[i] = 0;
+    __syncthreads();
+    const int64_t e0 = (int64_t)blockIdx.x * kPartTile;
+    const u64 *row = sel + (int64_t)r * k;
+    u64 c[kPartTile / 256];
+    uint32_t bin[kPartTile / 256];
+#pragma unroll
+    for (int j = 0; j < kPartTile / 256; ++j) {
+        const int64_t i = e0 + j * 256 + tid;
+        c[j] = (i < k) ? row[i] : 0ull;
+        bin[j] = c[j] ? (uint32_t)((c[j] - thr) >> shift) : 0u;
+        if (c[j]) atomicAdd(&lh[bin[j]], 1u);
+    }
+    __syncthreads();
+    // reserve the tile's share of every bin it touches
+    for (int i = tid; i < nb; i += 256) {
+        const uint32_t v = lh[i];
+        lh[i] = starts[(int64_t)r * nb + i] + (v ? atomicAdd(&cursors[(int64_t)r * nb + i], v) : 0u);
+    }
+    __syncthreads();
+    u64 *orow = dst + (int64_t)r * k;
+#pragma unroll
+    for (int j = 0; j < kPartTile / 256; ++j)
+        if (c[j]) orow[atomicAdd(&lh[bin[j]], 1u)] = c[j];
+}
+
+// One wavefront per (row, bin), four to a workgroup, for bins of at most kPartWaveMax elements.  The
+// wavefront works alone (no workgroup barrier), its elements in registers and its tables in its own
+// pieces of LDS: it cuts the bin once more into kPartSub sub-bins that are linear between the bin's
+// smallest and largest element (inside one bin the values are spread almost evenly, so a sub-bin
+// holds a couple of elements at most), takes a descending prefix sum over the sub-bin counts,
+// files every element into its sub-bin's segment, and an element's rank is its segment's start
+// plus the larger elements of that segment.
+constexpr int kPartSub = 512;
+constexpr int kPartSlots = kPartWaveMax / kWave;  // elements a lane holds
+__device__ __forceinline__ void wave_sync_lds() {  // orders this wavefront's LDS writes before its later reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+template <int ELT>
+__global__ void __launch_bounds__(256) part_sort_small_kernel(const u64 *src, const ExRowState *st, int64_t k, int nb,
+                                                              int64_t total_bins, const uint32_t *counts,
+                                                              const uint32_t *starts, void *out_vals, int32_t *out_idx) {
+    __shared__ u64 filed[4][kPartWaveMax];
+    __shared__ uint32_t sub_cnt[4][kPartSub];
+    __shared__ uint32_t sub_off[4][kPartSub + 8];  // [sb + 1] = start of sub-bin sb's segment, [0] = end of sub-bin 0's
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & (kWave - 1);
+    const int64_t g = (int64_t)blockIdx.x * 4 + wave;
+    if (g >= total_bins) return;
+    const int r = (int)(g / nb), bin = (int)(g % nb);
+    if (st[r].mode == 3u) return;
+    const int cnt = (int)counts[(int64_t)r * nb + bin];
+    if (cnt == 0 || cnt > kPartWaveMax) return;
+    const int64_t start = starts[(int64_t)r * nb + bin];
+    const u64 *seg = src + (int64_t)r * k + start;
+    u64 *fl = filed[wave];
+    uint32_t *sc = sub_cnt[wave], *so = sub_off[wave];
+
+    u64 c[kPartSlots];  // 0 = none
+    u64 lo = ~0ull, hi = 0ull;
+#pragma unroll
+    for (int e = 0; e < kPartSlots; ++e) {
+        const int i = lane + e * kWave;
+        c[e] = (i < cnt) ? seg[i] : 0ull;
+    }
+#pragma unroll
+    for (int e = 0; e < kPartSlots; ++e)
+        if (c[e]) {
+            lo = c[e] < lo ? c[e] : lo;
+            hi = c[e] > hi ? c[e] : hi;
+        }
+    for (int i = lane; i < kPartSub; i += kWave) sc[i] = 0u;
+    wave_min_max_u64(lo, hi);
+    const uint32_t sh = part_shift(hi - lo, kPartSub);
+    uint32_t sb[kPartSlots];
+    wave_sync_lds();
+#pragma unroll
+    for (int e = 0; e < kPartSlots; ++e) {
+        sb[e] = c[e] ? (uint32_t)((c[e] - lo) >> sh) : 0u;
+        if (c[e]) atomicAdd(&sc[sb[e]], 1u);
+    }
+    wave_sync_lds();
+    {
+        // lane l owns the Q sub-bins below kPartSub - Q*l: lane order is descending sub-bin order
+        constexpr int Q = kPartSub / kWave;
+        const int top = kPartSub - 1 - lane * Q;
+        uint32_t sum = 0;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) sum += sc[top - q];
+        uint32_t run = wave_incl_scan_u32(sum) - sum;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            so[top - q + 1] = run;
+            run += sc[top - q];
+        }
+        if (lane == kWave - 1) so[0] = (uint32_t)cnt;
+    }
+    wave_sync_lds();
+#pragma unroll
+    for (int e = 0; e < kPartSlots; ++e)
+        if (c[e]) fl[so[sb[e] + 1] + atomicSub(&sc[sb[e]], 1u) - 1u] = c[e];
+    wave_sync_lds();
+#pragma unroll
+    for (int e = 0; e < kPartSlots; ++e)
+        if (c[e]) {
+            const uint32_t s0 = so[sb[e] + 1], s1 = so[sb[e]];
+            uint32_t rank = s0;
+            for (uint32_t q = s0; q < s1; ++q) rank += (fl[q] > c[e]) ? 1u : 0u;
+            write_composite<ELT>(c[e], out_vals, out_idx, (int64_t)r * k + start + rank);
+        }
+}
+
+// The bins listed by the scan (more than kPartWaveMax elements): workgroups take them in turn and
+// order each in LDS with a bitonic network, largest first.
+template <int ELT>
+__global__ void __launch_bounds__(256) part_sort_big_kernel(const u64 *src, const ExRowState *st, int64_t k, int nb,
+                                                            const uint32_t *counts, const uint32_t *starts,
+                                                            const uint32_t *big, void *out_vals, int32_t *out_idx) {
+    __shared__ u64 s[kSortLdsMaxK];
+    const int tid = threadIdx.x;
+    const uint32_t n_big = big[0];
+    for (uint32_t w = blockIdx.x; w < n_big; w += gridDim.x) {  // the same trips for every lane of the workgroup
+        const int r = (int)(big[1 + w] / kPartMaxBins), bin = (int)(big[1 + w] % kPartMaxBins);
+        const int cnt = (int)counts[(int64_t)r * nb + bin];
+        const int64_t start = starts[(int64_t)r * nb + bin];
+        const u64 *seg = src + (int64_t)r * k + start;
+        const int kp = pow2_ceil_dev(cnt);
+        __syncthreads();  // the previous bin's reads of s are over
+        for (int i = tid; i < kp; i += 256) s[i] = (i < cnt) ? seg[i] : 0ull;  // empties sort to the end
+        __syncthreads();
+        for (int size = 2; size <= kp; size <<= 1) {
+            for (int stride = size >> 1; stride >= 1; stride >>= 1) {
+                for (int i = tid; i < (kp >> 1); i += 256) {
+                    const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));
+                    const int hi = lo + stride;
+                    const bool desc = (lo & size) == 0;
+                    const u64 a = s[lo], b = s[hi];
+                    const bool sw = desc ? (b > a) : (b < a);
+                    if (sw) {
+                        s[lo] = b;
+                        s[hi] = a;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        for (int i = tid; i < cnt; i += 256) write_composite<ELT>(s[i], out_vals, out_idx, (int64_t)r * k + start + i);
+    }
+}
+
 // ---- global least-significant-digit radix sort of the survivors, descending, 8-bit digits ----
 // bin = 255 - digit, so that ascending bins are descending digits.
-__global__ void __launch_bounds__(256) sort_hist_kernel(const u64 *src, int64_t k, int tiles, uint32_t *tile_hist,
-                                                        int shift) {
+// (all three kernels skip rows that the partition sort has taken, i.e. whose mode is not 3)
+__global__ void __launch_bounds__(256) sort_hist_kernel(const u64 *src, const ExRowState *st, int64_t k, int tiles,
+                                                        uint32_t *tile_hist, int shift) {
     __shared__ uint32_t lh[256];
     const int r = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+    if (st[r].mode != 3u) return;
     lh[tid] = 0;
     __syncthreads();
     const int64_t e0 = (int64_t)tile * kSortTile;
@@ -332,9 +591,10 @@ __global__ void __launch_bounds__(256) sort_hist_kernel(const u64 *src, int64_t 
 
 // one workgroup per row: tile_hist[tile][bin] <- number of elements of the row that sort before
 // the first element of (tile, bin): all smaller bins, and the same bin in earlier tiles
-__global__ void __launch_bounds__(256) sort_scan_kernel(uint32_t *tile_hist, int tiles) {
+__global__ void __launch_bounds__(256) sort_scan_kernel(uint32_t *tile_hist, const ExRowState *st, int tiles) {
     __shared__ uint32_t wave_tot[4];
     const int r = blockIdx.x, tid = threadIdx.x;  // tid = bin
+    if (st[r].mode != 3u) return;
     uint32_t *th = tile_hist + (int64_t)r * tiles * 256;
     uint32_t total = 0;
     for (int t = 0; t < tiles; ++t) total += th[t * 256 + tid];
@@ -353,11 +613,12 @@ __global__ void __launch_bounds__(256) sort_scan_kernel(uint32_t *tile_hist, int
 // stable scatter of one tile: the tile is walked in rounds of 256 consecutive elements; inside a
 // round an element's rank among equal bins is its rank among the lanes of its wavefront with
 // that bin (eight ballots) plus the counts of the lower wavefronts
-__global__ void __launch_bounds__(256) sort_scatter_kernel(const u64 *src, u64 *dst, int64_t k, int tiles,
-                                                           const uint32_t *tile_hist, int shift) {
+__global__ void __launch_bounds__(256) sort_scatter_kernel(const u64 *src, u64 *dst, const ExRowState *st, int64_t k,
+                                                           int tiles, const uint32_t *tile_hist, int shift) {
     __shared__ uint32_t running[256];
     __shared__ uint32_t wcnt[4][256];
     const int r = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+    if (st[r].mode != 3u) return;
     const int lane = tid & 63, wave = tid >> 6;
     running[tid] = tile_hist[((int64_t)r * tiles + tile) * 256 + tid];
 #pragma unroll
@@ -396,10 +657,13 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const u64 *src, u64 *
 }
 
 template <int ELT>
-__global__ void __launch_bounds__(256) ex_decode_kernel(const u64 *sorted, int64_t total, void *out_vals,
-                                                        int32_t *out_idx) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < total) write_composite<ELT>(sorted[i], out_vals, out_idx, i);
+__global__ void __launch_bounds__(256) ex_decode_kernel(const u64 *sorted, const ExRowState *st, int64_t k, int64_t total,
+                                                        void *out_vals, int32_t *out_idx) {
+    const int r = blockIdx.y;
+    if (st[r].mode != 3u) return;
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = (int64_t)r * k + j;
+    if (j < k && i < total) write_composite<ELT>(sorted[i], out_vals, out_idx, i);
 }
 
 template <int ELT>
@@ -447,24 +711,49 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
                            out_vals, out_idx);
         return hipGetLastError();
     }
-    // global sort: digits that are the same for every element (high bits of the index field) are skipped
     u64 *bufs[2] = {sel, sel + m * k};
     uint32_t *tile_hist = (uint32_t *)(bufs[1] + m * k);
     const int tiles = (int)ceil_div64(k, kSortTile);
+    // partition sort: about 128 survivors per bin
+    {
+        int nb = 16;
+        while (nb < kPartMaxBins && (int64_t)nb * 128 < k) nb <<= 1;
+        uint32_t *big = tile_hist + m * (int64_t)tiles * 256;  // [0] count, [1..] listed bins
+        uint32_t *counts = big + 64 + m * (int64_t)nb;
+        uint32_t *starts = counts + m * (int64_t)nb;
+        uint32_t *cursors = starts + m * (int64_t)nb;
+        const int ptiles = (int)ceil_div64(k, kPartTile);
+        const int64_t total_bins = m * (int64_t)nb;
+        // the list's counter and the counts start from zero (a fill kernel, so that the call can be captured in a graph)
+        hipLaunchKernelGGL(part_zero_kernel, dim3((unsigned)ceil_div64(64 + 2 * total_bins, 256)), dim3(256), 0, stream, big,
+                           64 + 2 * total_bins);
+        hipLaunchKernelGGL(part_hist_kernel, dim3((unsigned)ptiles, (unsigned)m), dim3(256), 0, stream, sel, st, k, nb, counts);
+        hipLaunchKernelGGL(part_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, st, nb, counts, starts, cursors, big);
+        hipLaunchKernelGGL(part_scatter_kernel, dim3((unsigned)ptiles, (unsigned)m), dim3(256), 0, stream, sel, bufs[1], st, k,
+                           nb, starts, cursors);
+        hipLaunchKernelGGL(part_sort_small_kernel<ELT>, dim3((unsigned)ceil_div64(total_bins, 4)), dim3(256), 0, stream,
+                           bufs[1], st, k, nb, total_bins, counts, starts, out_vals, out_idx);
+        hipLaunchKernelGGL(part_sort_big_kernel<ELT>, dim3(1024), dim3(256), 0, stream, bufs[1], st, k, nb, counts, starts,
+                           big, out_vals, out_idx);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    // rows the partition sort could not take (mode 3): stable least-significant-digit sort; digits that are
+    // the same for every element (high bits of the index field) are skipped
     // (the index field holds 0x7fffffff - idx in bits [31:1]; bit 0 is the zero-sign flag)
     int cur = 0;
     for (int shift = 0; shift < 64; shift += 8) {
         if (shift < 32 && shift >= idx_bits + 1) continue;
         const dim3 grid((unsigned)tiles, (unsigned)m);
-        hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(256), 0, stream, bufs[cur], k, tiles, tile_hist, shift);
-        hipLaunchKernelGGL(sort_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, tile_hist, tiles);
-        hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], k, tiles, tile_hist,
-                           shift);
+        hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(256), 0, stream, bufs[cur], st, k, tiles, tile_hist, shift);
+        hipLaunchKernelGGL(sort_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, tile_hist, st, tiles);
+        hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], st, k, tiles,
+                           tile_hist, shift);
         cur ^= 1;
     }
     const int64_t total = m * k;
-    hipLaunchKernelGGL(ex_decode_kernel<ELT>, dim3((unsigned)ceil_div64(total, 256)), dim3(256), 0, stream, bufs[cur], total,
-                       out_vals, out_idx);
+    hipLaunchKernelGGL(ex_decode_kernel<ELT>, dim3((unsigned)ceil_div64(k, 256), (unsigned)m), dim3(256), 0, stream, bufs[cur],
+                       st, k, total, out_vals, out_idx);
     return hipGetLastError();
 }
 

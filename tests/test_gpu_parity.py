@@ -402,6 +402,16 @@ def test_exact_long_rows(dtype):
                        workloads.special_values(1, 60000, seed=13, dtype=dtype)])
     run_exact(mixed, 100)
     run_exact(mixed, 1024)
+    # many survivors: partition sort (one wavefront per bin), its bitonic path for crowded bins (k of a
+    # million: more than 512 per bin), and rows whose values pile up on a few levels, which fall back to
+    # the digit-by-digit sort - all three kinds of row in one call as well
+    run_exact(workloads.normal_rows(1, 1 << 21, seed=21, dtype=dtype), 1 << 20)
+    run_exact(workloads.few_levels(2, 200000, levels=3, seed=22, dtype=dtype), 50000)
+    run_exact(workloads.few_levels(2, 200000, levels=3, seed=23, dtype=dtype), 150000)
+    big_mixed = torch.cat([workloads.normal_rows(2, 150000, seed=24, dtype=dtype),
+                           workloads.few_levels(1, 150000, levels=2, seed=25, dtype=dtype),
+                           workloads.special_values(1, 150000, seed=26, dtype=dtype)])
+    run_exact(big_mixed, 30000)
 
 
 def test_exact_cfg4():
