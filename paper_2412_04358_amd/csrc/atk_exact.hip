@@ -224,10 +224,11 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
 // elements: at large k, one per wavefront and load had every wavefront of a row queueing on
 // the same counter).  Few survivors (small k) are written from LDS; if they did not all fit,
 // the chunk is swept a second time and written straight from registers.
-constexpr int kStash = 2048;
 // FILTER: the same sweep for the rows in mode 1, whose threshold so far is just the first digit:
 // at most kFilterCap elements per row reach it, and they go to a buffer of that stride.
-template <int ELT, bool FILTER>
+// kStash: 2048 keeps the sweep's occupancy up when few survive; 6144 saves the second sweep when about a
+// quarter of a chunk does.
+template <int ELT, bool FILTER, int kStash>
 __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, int64_t n, ExRowState *st, u64 *sel,
                                                                  int64_t k) {
     __shared__ u64 stash[kStash];
@@ -694,14 +695,17 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
                            p == kExPasses - 1 ? 1 : 0, (uint32_t)((p == 0 && filter) ? kFilterCap : 0));
         if (p == 0 && filter) {
             u64 *fbuf = sel + m * k;
-            hipLaunchKernelGGL((ex_collect_kernel<ELT, true>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, fbuf,
+            hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, fbuf,
                                (int64_t)kFilterCap);
             const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
             hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st,
                                (int)k, idx_bits, out_vals, out_idx);
         }
     }
-    hipLaunchKernelGGL((ex_collect_kernel<ELT, false>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
+    if (k * kExChunk / n <= 1536)  // expected survivors per chunk
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
+    else
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 6144>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
