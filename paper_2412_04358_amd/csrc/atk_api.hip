@@ -121,6 +121,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
             while (T > 256 && m * T * 2 > want_threads) T >>= 1;  // keep at least two splits' worth of lanes
         }
     }
+    // Stage 2 runs in this workgroup: it wants a lane for every two candidates (four at most, or it
+    // falls back to the digit-by-digit selection), whatever the streaming part would be happy with
+    if (p.stage2) {
+        int t_s2 = (int)(ceil_div(ceil_div(b * k_b, 2), kWave) * kWave);
+        if (t_s2 > 512) t_s2 = 512;
+        if (T < t_s2) T = t_s2;
+    }
     // many column groups but few rows: smaller workgroups rather than row splits
     if (p.G > 256)
         while (T > kWave && m * ceil_div(p.G, T) < (int64_t)kNumCU) T >>= 1;
@@ -155,9 +162,18 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         p.nparts = p.wave_merge ? p.T / kWave : p.P;
         const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * std::min<int64_t>(b, (int64_t)p.Gw * p.V) * p.KB * 8 : 0;
         const int64_t lds_s2 = p.stage2 ? select_lds_bytes(b * k_b, (int)pow2_ceil(k)) : 0;
-        p.lds_xch_off = 16;
-        p.lds_cand_off = (int)(16 + lds_xch);
-        lds = 16 + lds_xch + lds_s2;
+        if (p.stage2) {
+            // candidates first; behind them the exchange area and, once that is dead, Stage 2's tables
+            const int64_t cand_bytes = ceil_div(b * k_b * 8, 16) * 16;
+            const int64_t tables = lds_s2 - b * k_b * 8;
+            p.lds_cand_off = 16;
+            p.lds_xch_off = (int)(16 + cand_bytes);
+            lds = 16 + cand_bytes + (lds_xch > tables ? lds_xch : tables);
+        } else {
+            p.lds_xch_off = 16;
+            p.lds_cand_off = (int)(16 + lds_xch);
+            lds = 16 + lds_xch;
+        }
         if (lds <= kLdsBudget || T <= kWave) break;
         T >>= 1;
     }
@@ -174,6 +190,10 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int64_t s_fill = ceil_div(kNumCU, base);         // splits that give every CU a workgroup
     if (S > s_traffic) S = s_traffic > s_fill ? s_traffic : (S < s_fill ? S : s_fill);  // filling the chip comes first
     if (S > s_rows) S = s_rows;
+    // Two splits buy nothing once half the CUs have a big workgroup each (the memory system, not the
+    // CU count, bounds a launch of this size), and cost the trip through scratch and the ticket
+    // before Stage 2 can start: measured equal at b <= 512 and 1 us slower at b = 1024 on 128 x 65536.
+    if (S == 2 && p.stage2 && p.colblocks == 1 && base * T >= 256 * (int64_t)kNumCU) S = 1;
     {
         // The workgroup that draws the last ticket merges S lists per column, SU splits per batch
         // of loads, tpc lanes per column: keep that serial tail to about four batches.
@@ -203,6 +223,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         const int64_t lds_xch = (p.nparts > 1) ? (int64_t)p.nparts * std::min<int64_t>(b, (int64_t)p.Gw * p.V) * p.KB * 8 : 0;
         const int64_t lds_s2 = select_lds_bytes(b * k_b, (int)pow2_ceil(k));
         p.lds_cand_off = 16;
+        p.lds_xch_off = 16;
         p.lds_bytes = (int)(16 + (lds_xch > lds_s2 ? lds_xch : lds_s2));
     }
 

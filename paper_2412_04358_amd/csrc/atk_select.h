@@ -366,6 +366,13 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
                                                    int32_t *out_idx, int64_t row_out) {
     const int tid = threadIdx.x, T = blockDim.x;
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    // as many bins as it takes for about one candidate in four bins, 256 at least: clearing and
+    // scanning them is serial work per lane, which a small workgroup with few candidates cannot afford
+    int lg_bins = 8;
+    while ((1 << lg_bins) < kBkBins && (1 << lg_bins) < 4 * count) ++lg_bins;
+    if ((1 << lg_bins) < T) lg_bins = 31 - __builtin_clz(T) + (((T & (T - 1)) != 0) ? 1 : 0);  // a bin per lane at least
+    if (lg_bins > 11) lg_bins = 11;
+    const int n_bins = 1 << lg_bins;
     const int lane = tid & (kWave - 1), n_waves = T >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // LDS behind the candidates (16-byte aligned pieces): counts, "above" table, small words
@@ -383,7 +390,7 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
     }
     {
         const v4u zero = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < kBkBins / 4; i += T) ((v4u *)cnt)[i] = zero;
+        for (int i = tid; i < n_bins / 4; i += T) ((v4u *)cnt)[i] = zero;
         if (tid == 0) {
             misc[0] = 0u;
             misc[1] = 0xffffffffu;
@@ -415,13 +422,13 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
     k_or = misc[3];
     // Bin key: the value key relative to the minimum, with the low bits that are zero in every
     // key squeezed out (bf16 values widened to f32 have 16 of them), followed by the varying
-    // index bits; 2048 bins, linear over that range.  Equal values thus spread over bins by
+    // index bits; n_bins bins, linear over that range.  Equal values thus spread over bins by
     // index when the values alone do not fill the bins.
     const int tz = k_or ? __builtin_ctz(k_or) : 0;
     const uint32_t imask = (idx_bits >= 31) ? 0x7fffffffu : ((1u << idx_bits) - 1u);
     const u64 span = ((u64)((k_max - k_min) >> tz) + 1ull) << idx_bits;  // bin keys are below span
     const int rbits = 64 - __clzll((long long)span);
-    const int bshift = rbits > 11 ? rbits - 11 : 0;
+    const int bshift = rbits > lg_bins ? rbits - lg_bins : 0;
     uint32_t bin[NS];
 #pragma unroll
     for (int e = 0; e < NS; ++e) {
@@ -432,10 +439,10 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
     __syncthreads();
 
     // ---- descending exclusive prefix over the bins: thread t owns the q bins below 2048 - t*q
-    const int q = kBkBins / T;  // T is a multiple of 64 and at most 2048; q*T may fall short of 2048
+    const int q = n_bins / T;  // T is a multiple of 64 and at most n_bins; q*T may fall short of n_bins
     {
         // general q: walk the own bins from the top; q is 2, 4, 8 ... for the usual workgroup sizes
-        const int hi = kBkBins - 1 - tid * q;
+        const int hi = n_bins - 1 - tid * q;
         uint32_t s = 0, mx = 0;
         for (int j = 0; j < q; ++j) {
             const uint32_t v = cnt[hi - j];
