@@ -112,16 +112,21 @@ int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype);
 /* Largest b*k_b for which Stage 2 runs on-chip in the same launch. */
 int64_t atk_stage2_max_candidates(void);
 
-/* Bytes of library scratch an approx_topk / exact_topk call with these arguments uses (0 if none, <0 = error code). */
+/* Bytes of library scratch an approx_topk / approx_topk_assign / exact_topk call with these arguments uses
+ * (0 if none, <0 = error code). */
 int64_t atk_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
+int64_t atk_workspace_bytes_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment);
 int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype);
 
 /*
  * Writes a one-line, human-readable description of the launch plan the library would use
  * (threads per workgroup, lanes per bucket column, row splits, fused Stage 2, ...) into
  * buf (NUL-terminated, truncated to buflen).  Host only; used by tests and the benchmark log.
- * The plan can be overridden for tuning with the environment variable ATK_PLAN, e.g.
- * "T=256,S=16" (threads per workgroup, splits per row).
+ * The plan can be overridden for tuning and tests with the environment variable ATK_PLAN, a comma
+ * separated list of: T=<threads per workgroup: 64..1024>, S=<workgroups a row is split over>,
+ * V=<columns per lane: 1, 2, 4, 8>, P=<lanes of a workgroup sharing a column group: 1, 2, 4>,
+ * PK=0 (bf16: no packed queue words).  Values the kernels cannot take are ignored or clamped;
+ * results never depend on the plan.
  */
 int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
                       int64_t buflen);

@@ -62,6 +62,8 @@ def load_library():
     lib.atk_stage2_max_candidates.restype = i64
     lib.atk_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, ci]
     lib.atk_workspace_bytes.restype = i64
+    lib.atk_workspace_bytes_assign.argtypes = [i64, i64, i64, i64, i64, ci, ci]
+    lib.atk_workspace_bytes_assign.restype = i64
     lib.atk_exact_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.atk_exact_workspace_bytes.restype = i64
     lib.atk_plan_describe.argtypes = [i64, i64, i64, i64, i64, ci, ctypes.c_char_p, i64]

@@ -477,6 +477,17 @@ int64_t atk_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t 
     return pl.scratch_ticket_bytes + pl.scratch_lists_bytes;
 }
 
+int64_t atk_workspace_bytes_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment) {
+    if (assignment == ATK_INTERLEAVED) return atk_workspace_bytes(m, n, k, b, k_b, dtype);
+    if (assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    Plan pl;
+    rc = make_contig_plan(m, n, k, b, k_b, dtype, true, &pl);
+    if (rc != ATK_OK) return rc;
+    return pl.scratch_ticket_bytes + pl.scratch_lists_bytes;
+}
+
 int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype) {
     int rc = check_common(m, n, k, dtype);
     if (rc != ATK_OK) return rc;

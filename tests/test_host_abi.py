@@ -207,6 +207,11 @@ def test_workspace_bytes(lib):
     assert lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0) == p["scratch_bytes"] > 0
     assert lib.atk_workspace_bytes(128, 65536, 64, 32, 1, 0) == PARAMS
     assert lib.atk_stage2_max_candidates() >= 1024
+    assert lib.atk_workspace_bytes_assign(128, 65536, 64, 64, 1, 0, 0) == lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0)
+    pc = parse_contig_plan(atk.plan_describe(1, 1 << 20, 64, 8, 8, atk.ATK_F32, atk.ATK_CONTIGUOUS))
+    assert lib.atk_workspace_bytes_assign(1, 1 << 20, 64, 8, 8, 0, 1) == pc["scratch_bytes"] > 0
+    assert lib.atk_workspace_bytes_assign(128, 65536, 16384, 16384, 1, 0, 1) == 0
+    assert lib.atk_workspace_bytes_assign(128, 65536, 64, 64, 1, 0, 5) == PARAMS
 
 
 # ----------------------------------------------------------------------------- choosing (b, k_b)
