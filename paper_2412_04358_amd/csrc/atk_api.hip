@@ -265,7 +265,7 @@ int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, in
         // Short buckets: as many lanes per bucket as it has loads (rounded up to a power of two),
         // so that a wavefront reads one contiguous stretch, and NB buckets per lane group in turn.
         int64_t Gs = pow2_ceil(chunks);
-        int T = T_forced ? T_forced : 256;
+        int T = T_forced ? T_forced : (p.stage2 ? 512 : 256);  // (measured: Stage 2 likes the bigger workgroup)
         if (T > t_max) T = t_max;
         const int64_t need = ceil_div(b * Gs, kWave) * kWave;  // lanes that cover one row's buckets
         if (need < T) T = (int)need;

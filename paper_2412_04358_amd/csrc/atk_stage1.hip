@@ -634,11 +634,25 @@ __global__ void __launch_bounds__(MAXT) contig_kernel(S1Params p) {
 #pragma unroll
                 for (int i = 0; i < KB; ++i)
                     comp[i] = (tt[i] != kEmptyT) ? make_composite(__float_as_uint(val[i]), (int32_t)(r0[u] + tt[i])) : 0ull;
-                for (int off = 1; off < p.Gs; off <<= 1) {
-                    u64 theirs[KB];
+                if (KB == 1) {
+                    // one slot: the merge is a maximum over the group's lanes; inside a row of 16 lanes
+                    // it goes through DPP (register to register), only groups of 32 and 64 lanes need
+                    // a cross-row exchange on top
+                    u64 v = comp[0], t;
+                    if (p.Gs >= 2) { t = dpp_u64<0xB1>(v); v = t > v ? t : v; }
+                    if (p.Gs >= 4) { t = dpp_u64<0x4E>(v); v = t > v ? t : v; }
+                    if (p.Gs >= 8) { t = dpp_u64<0x141>(v); v = t > v ? t : v; }
+                    if (p.Gs >= 16) { t = dpp_u64<0x140>(v); v = t > v ? t : v; }
+                    if (p.Gs >= 32) { t = shfl_xor_u64(v, 16); v = t > v ? t : v; }
+                    if (p.Gs >= 64) { t = shfl_xor_u64(v, 32); v = t > v ? t : v; }
+                    comp[0] = v;
+                } else {
+                    for (int off = 1; off < p.Gs; off <<= 1) {
+                        u64 theirs[KB];
 #pragma unroll
-                    for (int i = 0; i < KB; ++i) theirs[i] = shfl_xor_u64(comp[i], off);
-                    merge_topk<KB>(comp, theirs);
+                        for (int i = 0; i < KB; ++i) theirs[i] = shfl_xor_u64(comp[i], off);
+                        merge_topk<KB>(comp, theirs);
+                    }
                 }
                 if (q == 0 && bj[u] >= 0) emit_list<ELT, KB>(p, r, 0, bj[u], comp, cand);
             }
