@@ -463,7 +463,7 @@ int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype) {
     int rc = check_common(m, n, k, dtype);
     if (rc != ATK_OK) return rc;
     ExactPlan pl;
-    return make_exact_plan(m, n, k, dtype, &pl);
+    return make_exact_plan(m > 65535 ? 65535 : m, n, k, dtype, &pl);  // long rows go through in blocks of rows
 }
 
 int64_t atk_stage2_max_candidates(void) { return kStage2MaxCand; }
@@ -492,7 +492,8 @@ int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype) {
     int rc = check_common(m, n, k, dtype);
     if (rc != ATK_OK) return rc;
     ExactPlan pl;
-    rc = make_exact_plan(m, n, k, dtype, &pl);
+    rc = make_exact_plan(m > 65535 ? 65535 : m, n, k, dtype, &pl);  // long rows go through in blocks of 65535
+    if (rc == ATK_OK && pl.single_wg) rc = make_exact_plan(m, n, k, dtype, &pl);
     if (rc != ATK_OK) return rc;
     return pl.scratch_bytes + pl.state_bytes;
 }
@@ -590,16 +591,28 @@ int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *
     const int es = (dtype == ATK_F32) ? 4 : 2;
     if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
     if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
-    ExactPlan pl;
-    rc = make_exact_plan(m, n, k, dtype, &pl);
-    if (rc != ATK_OK) return rc;
-    void *state = nullptr, *data = nullptr;
-    hipError_t e = get_pool(kPoolState, (size_t)pl.state_bytes, &state);
-    if (e != hipSuccess) return hip_fail(e);
-    e = get_pool(kPoolData, (size_t)pl.scratch_bytes, &data);
-    if (e != hipSuccess) return hip_fail(e);
-    e = launch_exact(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
-    if (e != hipSuccess) return hip_fail(e);
+    // long rows are the y dimension of their grids: more rows than that go through in blocks, one
+    // after the other on the stream, sharing the scratch
+    const int64_t rows_per_pass = 65535;
+    for (int64_t r0 = 0; r0 < m; r0 += rows_per_pass) {
+        const int64_t rows = (m - r0 < rows_per_pass) ? m - r0 : rows_per_pass;
+        ExactPlan pl;
+        rc = make_exact_plan(rows, n, k, dtype, &pl);
+        if (rc != ATK_OK) return rc;
+        if (pl.single_wg && r0 == 0) {  // one workgroup per row, rows along x: no limit
+            rc = make_exact_plan(m, n, k, dtype, &pl);
+            if (rc != ATK_OK) return rc;
+        }
+        void *state = nullptr, *data = nullptr;
+        hipError_t e = get_pool(kPoolState, (size_t)pl.state_bytes, &state);
+        if (e != hipSuccess) return hip_fail(e);
+        e = get_pool(kPoolData, (size_t)pl.scratch_bytes, &data);
+        if (e != hipSuccess) return hip_fail(e);
+        e = launch_exact(pl, (const unsigned char *)x + r0 * n * es, (unsigned char *)out_vals + r0 * k * es,
+                         out_idx + r0 * k, state, data, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e);
+        if (pl.single_wg) break;
+    }
     return ATK_OK;
 }
 

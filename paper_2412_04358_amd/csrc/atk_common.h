@@ -128,6 +128,7 @@ struct ExactPlan {
     int T;
     int lds_bytes;
     int chunks;             // workgroups per row of the global path
+    bool filter;            // small k: rows may finish through the copy-out buffer
     int64_t scratch_bytes;  // data pool
     int64_t state_bytes;    // zeroed-state pool
 };

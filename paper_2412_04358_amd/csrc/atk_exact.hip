@@ -62,6 +62,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.scratch_bytes = 0;
     p.state_bytes = 0;
     p.lds_bytes = 0;
+    p.filter = false;
     if (m >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
     const int64_t lds = select_lds_bytes(n, (int)pow2_ceil64(k < (1 << 20) ? k : (1 << 20)));
     p.single_wg = lds <= kLdsBudget;
@@ -71,14 +72,16 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
         return ATK_OK;
     }
     p.chunks = (int)ceil_div64(n, kExChunk);
-    if (m > 65535) return ATK_ERR_UNSUPPORTED;  // rows are the grid's y dimension
+    if (m > 65535) return ATK_ERR_UNSUPPORTED;  // rows are the grid's y dimension: exact_topk() passes blocks of rows
     // state pool: global histograms (left zero by every call)
     p.state_bytes = m * kExBins * 4;
     // data pool: row states, survivors, and for the global sort a second buffer + tile histograms
     int64_t bytes = m * (int64_t)sizeof(ExRowState);
     bytes = ceil_div64(bytes, 256) * 256;
     bytes += m * k * 8;
-    if (k <= kFilterMaxK) bytes += m * (int64_t)kFilterCap * 8;  // copy-out buffer of the small-k path
+    // copy-out buffer of the small-k path, as long as it stays modest (256 MB)
+    p.filter = k <= kFilterMaxK && m * (int64_t)kFilterCap * 8 <= (256ll << 20);
+    if (p.filter) bytes += m * (int64_t)kFilterCap * 8;
     if (k > kSortLdsMaxK) {
         bytes += m * k * 8;
         bytes += m * ceil_div64(k, kSortTile) * 256 * 4;
@@ -685,7 +688,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
     hipLaunchKernelGGL(ex_init_kernel, dim3((unsigned)ceil_div64(m, 256)), dim3(256), 0, stream, st, (int)m, (uint32_t)k);
     // Small k: after the first digit most rows have only a handful of elements left in play; those
     // are copied out in one more sweep and finished in LDS instead of being swept digit by digit.
-    const bool filter = k <= kFilterMaxK;
+    const bool filter = pl.filter;
     int idx_bits = 1;  // column indices are below 2^idx_bits
     while (((int64_t)1 << idx_bits) < n) ++idx_bits;
     for (int p = 0; p < kExPasses; ++p) {

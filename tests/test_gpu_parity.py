@@ -414,6 +414,12 @@ def test_exact_long_rows(dtype):
     run_exact(big_mixed, 30000)
 
 
+def test_exact_many_long_rows():
+    """More long rows than a grid dimension holds: they go through in blocks of rows."""
+    x = workloads.normal_rows(66000, 9000, seed=41)  # 9000 f32 per row do not fit one workgroup's LDS
+    run_exact(x, 10, rows=[0, 1, 65534, 65535, 65536, 65999])
+
+
 def test_exact_cfg4():
     x = workloads.config_input("cfg4")
     rows = [0, 1, 64, 127]
