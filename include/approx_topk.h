@@ -74,8 +74,11 @@ enum {
  * n need not be a multiple of b: bucket j holds the indices j, j+b, ... below n (the short
  * buckets of Figure 2); k_b <= floor(n/b) keeps every bucket long enough.
  *
- * ATK_ERR_UNSUPPORTED: k_b > ATK_MAX_KB; a Stage 2 whose b*k_b candidates exceed the
- * on-chip limit reported by atk_stage2_max_candidates().
+ * Stage 2 runs inside the same kernel launch as long as its b*k_b candidates fit one workgroup
+ * (atk_stage2_max_candidates()); with more, Stage 1 leaves the candidates in library scratch and
+ * the long-row exact selection picks the k largest of them in further launches.
+ *
+ * ATK_ERR_UNSUPPORTED: k_b > ATK_MAX_KB.
  */
 int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
                 void *out_vals, int32_t *out_idx, void *stream);
@@ -109,7 +112,7 @@ int atk_last_hip_error(void);
 int atk_check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
 int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype);
 
-/* Largest b*k_b for which Stage 2 runs on-chip in the same launch. */
+/* Largest b*k_b for which Stage 2 runs on-chip in the same launch (more candidates take further launches). */
 int64_t atk_stage2_max_candidates(void);
 
 /* Bytes of library scratch an approx_topk / approx_topk_assign / exact_topk call with these arguments uses

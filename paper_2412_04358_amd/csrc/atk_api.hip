@@ -452,89 +452,71 @@ const char *atk_strerror(int code) {
 
 int atk_last_hip_error(void) { return g_last_hip_error; }
 
-int atk_check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
-    int rc = check_approx(m, n, k, b, k_b, dtype);
-    if (rc != ATK_OK) return rc;
-    Plan pl;
-    return make_plan(m, n, k, b, k_b, dtype, &pl);
-}
+// ---- the whole call: Stage 1 (+ fused Stage 2), or Stage 1 into scratch followed by the long-row
+// exact selection over the candidates when there are more of them than one workgroup holds
+struct FullPlan {
+    Plan s1;
+    bool two_step;
+    ExactPlan ex;            // two_step: selection over the b*k_b candidates of (a block of) the rows
+    int64_t cand_vals_off;   // byte offsets into the data pool
+    int64_t cand_idx_off;
+    int64_t ex_data_off;
+    int64_t ex_state_off;    // byte offset into the state pool
+    int64_t state_bytes, data_bytes;
+};
+static const int64_t kExactRowsPerPass = 65535;  // long rows are the y dimension of their grids
+static int64_t align256(int64_t v) { return (v + 255) / 256 * 256; }
 
-int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype) {
-    int rc = check_common(m, n, k, dtype);
+static int make_full_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
+                          bool ptr16, FullPlan *fp) {
+    if (assignment != ATK_INTERLEAVED && assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    const int64_t nc = b * k_b;
+    fp->two_step = nc > k && nc > kStage2MaxCand;
+    const int64_t k1 = fp->two_step ? nc : k;  // two steps: Stage 1 writes all its candidates, bucket by bucket
+    int rc = (assignment == ATK_CONTIGUOUS) ? make_contig_plan(m, n, k1, b, k_b, dtype, ptr16, &fp->s1)
+                                            : make_plan_aligned(m, n, k1, b, k_b, dtype, ptr16, &fp->s1);
     if (rc != ATK_OK) return rc;
-    ExactPlan pl;
-    return make_exact_plan(m > 65535 ? 65535 : m, n, k, dtype, &pl);  // long rows go through in blocks of rows
-}
-
-int64_t atk_stage2_max_candidates(void) { return kStage2MaxCand; }
-
-int64_t atk_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
-    int rc = check_approx(m, n, k, b, k_b, dtype);
+    fp->state_bytes = fp->s1.scratch_ticket_bytes;
+    fp->data_bytes = fp->s1.scratch_lists_bytes;
+    if (!fp->two_step) return ATK_OK;
+    rc = make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, nc, k, dtype, &fp->ex);
+    if (rc == ATK_OK && fp->ex.single_wg) rc = make_exact_plan(m, nc, k, dtype, &fp->ex);
     if (rc != ATK_OK) return rc;
-    Plan pl;
-    rc = make_plan(m, n, k, b, k_b, dtype, &pl);
-    if (rc != ATK_OK) return rc;
-    return pl.scratch_ticket_bytes + pl.scratch_lists_bytes;
-}
-
-int64_t atk_workspace_bytes_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment) {
-    if (assignment == ATK_INTERLEAVED) return atk_workspace_bytes(m, n, k, b, k_b, dtype);
-    if (assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
-    int rc = check_approx(m, n, k, b, k_b, dtype);
-    if (rc != ATK_OK) return rc;
-    Plan pl;
-    rc = make_contig_plan(m, n, k, b, k_b, dtype, true, &pl);
-    if (rc != ATK_OK) return rc;
-    return pl.scratch_ticket_bytes + pl.scratch_lists_bytes;
-}
-
-int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype) {
-    int rc = check_common(m, n, k, dtype);
-    if (rc != ATK_OK) return rc;
-    ExactPlan pl;
-    rc = make_exact_plan(m > 65535 ? 65535 : m, n, k, dtype, &pl);  // long rows go through in blocks of 65535
-    if (rc == ATK_OK && pl.single_wg) rc = make_exact_plan(m, n, k, dtype, &pl);
-    if (rc != ATK_OK) return rc;
-    return pl.scratch_bytes + pl.state_bytes;
-}
-
-int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
-                      int64_t buflen) {
-    if (!buf || buflen < 1) return ATK_ERR_NULL_PTR;
-    int rc = check_approx(m, n, k, b, k_b, dtype);
-    if (rc != ATK_OK) return rc;
-    Plan pl;
-    rc = make_plan(m, n, k, b, k_b, dtype, &pl);
-    if (rc != ATK_OK) return rc;
-    snprintf(buf, (size_t)buflen,
-             "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
-             "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d",
-             pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid,
-             (int)pl.stage2, (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
-             (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes), (int)pl.packed);
+    fp->ex.idx_n = n;
+    fp->cand_vals_off = align256(fp->s1.scratch_lists_bytes);
+    fp->cand_idx_off = fp->cand_vals_off + align256(m * nc * es);
+    fp->ex_data_off = fp->cand_idx_off + align256(m * nc * 4);
+    fp->ex_state_off = align256(fp->s1.scratch_ticket_bytes);
+    fp->data_bytes = fp->ex_data_off + fp->ex.scratch_bytes;
+    fp->state_bytes = fp->ex_state_off + fp->ex.state_bytes;
     return ATK_OK;
 }
 
-int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
-                             char *buf, int64_t buflen) {
-    if (assignment == ATK_INTERLEAVED) return atk_plan_describe(m, n, k, b, k_b, dtype, buf, buflen);
-    if (!buf || buflen < 1) return ATK_ERR_NULL_PTR;
-    if (assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
-    int rc = check_approx(m, n, k, b, k_b, dtype);
-    if (rc != ATK_OK) return rc;
-    Plan pl;
-    rc = make_contig_plan(m, n, k, b, k_b, dtype, true, &pl);
-    if (rc != ATK_OK) return rc;
-    snprintf(buf, (size_t)buflen,
-             "contiguous V=%d KB=%d T=%d Gs=%d NB=%d bblocks=%d S=%d chunks_per_split=%d grid=%lld stage2=%d scratch=%d "
-             "lds=%d scratch_bytes=%lld",
-             pl.V, pl.KB, pl.T, pl.Gs, pl.NB, pl.bblocks, pl.S, pl.chunks_per_split, (long long)pl.grid, (int)pl.stage2,
-             (int)pl.use_scratch, pl.lds_bytes, (long long)(pl.scratch_ticket_bytes + pl.scratch_lists_bytes));
+// exact selection over the rows of x (values) / xi (their indices, or NULL), in blocks of rows
+static int run_exact(const ExactPlan &first, const void *x, const int32_t *xi, int64_t m, int64_t n, int64_t k, int dtype,
+                     void *out_vals, int32_t *out_idx, void *state, void *data, hipStream_t stream) {
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    if (first.single_wg) {  // one workgroup per row, rows along x: no limit on m
+        hipError_t e = launch_exact(first, x, xi, out_vals, out_idx, state, data, stream);
+        return e == hipSuccess ? ATK_OK : hip_fail(e);
+    }
+    for (int64_t r0 = 0; r0 < m; r0 += kExactRowsPerPass) {
+        ExactPlan pl = first;
+        if (m - r0 < pl.m) {
+            int rc = make_exact_plan(m - r0, n, k, dtype, &pl);
+            if (rc != ATK_OK) return rc;
+            pl.idx_n = first.idx_n;
+        }
+        hipError_t e = launch_exact(pl, (const unsigned char *)x + r0 * n * es, xi ? xi + r0 * n : nullptr,
+                                    (unsigned char *)out_vals + r0 * k * es, out_idx + r0 * k, state, data, stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
     return ATK_OK;
 }
 
-int approx_topk_assign(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
-                       int assignment, void *out_vals, int32_t *out_idx, void *stream) {
+static int run_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
+                      void *out_vals, int32_t *out_idx, void *stream) {
     if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
     int rc = check_approx(m, n, k, b, k_b, dtype);
     if (rc != ATK_OK) return rc;
@@ -542,45 +524,109 @@ int approx_topk_assign(const void *x, int64_t m, int64_t n, int64_t k, int64_t b
     const int es = (dtype == ATK_F32) ? 4 : 2;
     if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
     if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
-    Plan pl;
-    const bool ptr16 = ((uintptr_t)x & 15u) == 0;
-    if (assignment == ATK_CONTIGUOUS)
-        rc = make_contig_plan(m, n, k, b, k_b, dtype, ptr16, &pl);
-    else
-        rc = make_plan_aligned(m, n, k, b, k_b, dtype, ptr16, &pl);
+    FullPlan fp;
+    rc = make_full_plan(m, n, k, b, k_b, dtype, assignment, ((uintptr_t)x & 15u) == 0, &fp);
     if (rc != ATK_OK) return rc;
     void *state = nullptr, *data = nullptr;
-    hipError_t e = get_pool(kPoolState, (size_t)pl.scratch_ticket_bytes, &state);
+    hipError_t e = get_pool(kPoolState, (size_t)fp.state_bytes, &state);
     if (e != hipSuccess) return hip_fail(e);
-    e = get_pool(kPoolData, (size_t)pl.scratch_lists_bytes, &data);
+    e = get_pool(kPoolData, (size_t)fp.data_bytes, &data);
     if (e != hipSuccess) return hip_fail(e);
+    void *s1_vals = out_vals;
+    int32_t *s1_idx = out_idx;
+    if (fp.two_step) {
+        s1_vals = (unsigned char *)data + fp.cand_vals_off;
+        s1_idx = (int32_t *)((unsigned char *)data + fp.cand_idx_off);
+    }
     if (assignment == ATK_CONTIGUOUS)
-        e = launch_approx_contig(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
+        e = launch_approx_contig(fp.s1, x, s1_vals, s1_idx, state, data, (hipStream_t)stream);
     else
-        e = launch_approx(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
+        e = launch_approx(fp.s1, x, s1_vals, s1_idx, state, data, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
+    if (!fp.two_step) return ATK_OK;
+    return run_exact(fp.ex, s1_vals, s1_idx, m, b * k_b, k, dtype, out_vals, out_idx,
+                     (unsigned char *)state + fp.ex_state_off, (unsigned char *)data + fp.ex_data_off, (hipStream_t)stream);
+}
+
+int atk_check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    FullPlan fp;
+    return make_full_plan(m, n, k, b, k_b, dtype, ATK_INTERLEAVED, true, &fp);
+}
+
+int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype) {
+    int rc = check_common(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    ExactPlan pl;
+    return make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, n, k, dtype, &pl);
+}
+
+int64_t atk_stage2_max_candidates(void) { return kStage2MaxCand; }
+
+int64_t atk_workspace_bytes_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment) {
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    FullPlan fp;
+    rc = make_full_plan(m, n, k, b, k_b, dtype, assignment, true, &fp);
+    if (rc != ATK_OK) return rc;
+    return fp.state_bytes + fp.data_bytes;
+}
+
+int64_t atk_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    return atk_workspace_bytes_assign(m, n, k, b, k_b, dtype, ATK_INTERLEAVED);
+}
+
+int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype) {
+    int rc = check_common(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    ExactPlan pl;
+    rc = make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, n, k, dtype, &pl);
+    if (rc == ATK_OK && pl.single_wg) rc = make_exact_plan(m, n, k, dtype, &pl);
+    if (rc != ATK_OK) return rc;
+    return pl.scratch_bytes + pl.state_bytes;
+}
+
+int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
+                             char *buf, int64_t buflen) {
+    if (!buf || buflen < 1) return ATK_ERR_NULL_PTR;
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    FullPlan fp;
+    rc = make_full_plan(m, n, k, b, k_b, dtype, assignment, true, &fp);
+    if (rc != ATK_OK) return rc;
+    const Plan &pl = fp.s1;
+    // two steps: Stage 2 is the long-row exact selection over the candidates Stage 1 left in scratch
+    const int stage2 = fp.two_step ? 2 : (int)pl.stage2;
+    if (assignment == ATK_CONTIGUOUS)
+        snprintf(buf, (size_t)buflen,
+                 "contiguous V=%d KB=%d T=%d Gs=%d NB=%d bblocks=%d S=%d chunks_per_split=%d grid=%lld stage2=%d "
+                 "scratch=%d lds=%d scratch_bytes=%lld",
+                 pl.V, pl.KB, pl.T, pl.Gs, pl.NB, pl.bblocks, pl.S, pl.chunks_per_split, (long long)pl.grid, stage2,
+                 (int)pl.use_scratch, pl.lds_bytes, (long long)(fp.state_bytes + fp.data_bytes));
+    else
+        snprintf(buf, (size_t)buflen,
+                 "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
+                 "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d",
+                 pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid, stage2,
+                 (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
+                 (long long)(fp.state_bytes + fp.data_bytes), (int)pl.packed);
     return ATK_OK;
+}
+
+int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
+                      int64_t buflen) {
+    return atk_plan_describe_assign(m, n, k, b, k_b, dtype, ATK_INTERLEAVED, buf, buflen);
+}
+
+int approx_topk_assign(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
+                       int assignment, void *out_vals, int32_t *out_idx, void *stream) {
+    return run_approx(x, m, n, k, b, k_b, dtype, assignment, out_vals, out_idx, stream);
 }
 
 int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
                 void *out_vals, int32_t *out_idx, void *stream) {
-    if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
-    int rc = check_approx(m, n, k, b, k_b, dtype);
-    if (rc != ATK_OK) return rc;
-    const int es = (dtype == ATK_F32) ? 4 : 2;
-    if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
-    if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
-    Plan pl;
-    rc = make_plan_aligned(m, n, k, b, k_b, dtype, ((uintptr_t)x & 15u) == 0, &pl);
-    if (rc != ATK_OK) return rc;
-    void *state = nullptr, *data = nullptr;
-    hipError_t e = get_pool(kPoolState, (size_t)pl.scratch_ticket_bytes, &state);
-    if (e != hipSuccess) return hip_fail(e);
-    e = get_pool(kPoolData, (size_t)pl.scratch_lists_bytes, &data);
-    if (e != hipSuccess) return hip_fail(e);
-    e = launch_approx(pl, x, out_vals, out_idx, state, data, (hipStream_t)stream);
-    if (e != hipSuccess) return hip_fail(e);
-    return ATK_OK;
+    return run_approx(x, m, n, k, b, k_b, dtype, ATK_INTERLEAVED, out_vals, out_idx, stream);
 }
 
 int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *out_vals, int32_t *out_idx,
@@ -591,29 +637,16 @@ int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *
     const int es = (dtype == ATK_F32) ? 4 : 2;
     if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
     if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
-    // long rows are the y dimension of their grids: more rows than that go through in blocks, one
-    // after the other on the stream, sharing the scratch
-    const int64_t rows_per_pass = 65535;
-    for (int64_t r0 = 0; r0 < m; r0 += rows_per_pass) {
-        const int64_t rows = (m - r0 < rows_per_pass) ? m - r0 : rows_per_pass;
-        ExactPlan pl;
-        rc = make_exact_plan(rows, n, k, dtype, &pl);
-        if (rc != ATK_OK) return rc;
-        if (pl.single_wg && r0 == 0) {  // one workgroup per row, rows along x: no limit
-            rc = make_exact_plan(m, n, k, dtype, &pl);
-            if (rc != ATK_OK) return rc;
-        }
-        void *state = nullptr, *data = nullptr;
-        hipError_t e = get_pool(kPoolState, (size_t)pl.state_bytes, &state);
-        if (e != hipSuccess) return hip_fail(e);
-        e = get_pool(kPoolData, (size_t)pl.scratch_bytes, &data);
-        if (e != hipSuccess) return hip_fail(e);
-        e = launch_exact(pl, (const unsigned char *)x + r0 * n * es, (unsigned char *)out_vals + r0 * k * es,
-                         out_idx + r0 * k, state, data, (hipStream_t)stream);
-        if (e != hipSuccess) return hip_fail(e);
-        if (pl.single_wg) break;
-    }
-    return ATK_OK;
+    ExactPlan pl;
+    rc = make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, n, k, dtype, &pl);
+    if (rc == ATK_OK && pl.single_wg) rc = make_exact_plan(m, n, k, dtype, &pl);
+    if (rc != ATK_OK) return rc;
+    void *state = nullptr, *data = nullptr;
+    hipError_t e = get_pool(kPoolState, (size_t)pl.state_bytes, &state);
+    if (e != hipSuccess) return hip_fail(e);
+    e = get_pool(kPoolData, (size_t)pl.scratch_bytes, &data);
+    if (e != hipSuccess) return hip_fail(e);
+    return run_exact(pl, x, nullptr, m, n, k, dtype, out_vals, out_idx, state, data, (hipStream_t)stream);
 }
 
 int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream) {

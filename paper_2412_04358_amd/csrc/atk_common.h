@@ -124,6 +124,7 @@ hipError_t launch_approx_contig(const Plan &plan, const void *x, void *out_vals,
 struct ExactPlan {
     int dtype;
     int64_t m, n, k;
+    int64_t idx_n;          // column indices are below this (n, unless the rows are lists of (value, index) pairs)
     bool single_wg;         // whole row fits one workgroup's LDS
     int T;
     int lds_bytes;
@@ -133,8 +134,11 @@ struct ExactPlan {
     int64_t state_bytes;    // zeroed-state pool
 };
 int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *plan);
-hipError_t launch_exact(const ExactPlan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state,
-                        void *data, hipStream_t stream);
+// xi: NULL, or (device, m x n int32) the column index each element of x stands for: the rows are then
+// lists of (value, index) pairs with distinct indices below plan.idx_n, and the order among equal
+// values and out_idx follow those indices (Stage 2 over more candidates than fit one workgroup).
+hipError_t launch_exact(const ExactPlan &plan, const void *x, const int32_t *xi, void *out_vals, int32_t *out_idx,
+                        void *state, void *data, hipStream_t stream);
 
 // ------------------------------------------------------------------------------------
 // Device helpers.

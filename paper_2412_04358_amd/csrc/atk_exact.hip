@@ -63,6 +63,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.state_bytes = 0;
     p.lds_bytes = 0;
     p.filter = false;
+    p.idx_n = n;
     if (m >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
     const int64_t lds = select_lds_bytes(n, (int)pow2_ceil64(k < (1 << 20) ? k : (1 << 20)));
     p.single_wg = lds <= kLdsBudget;
@@ -94,8 +95,8 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
 
 // ------------------------------------------------------------------------------------ small rows
 template <int ELT>
-__global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x, int n, int k, void *out_vals,
-                                                                  int32_t *out_idx) {
+__global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x, const int32_t *xi, int n, int k, int idx_bits,
+                                                                  void *out_vals, int32_t *out_idx) {
     extern __shared__ __align__(16) unsigned char smem[];
     u64 *cand = (u64 *)smem;
     const int r = blockIdx.x;
@@ -104,18 +105,18 @@ __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x,
         if (ELT == ATK_F32) return ((const uint32_t *)x)[(int64_t)r * n + i];
         return ((uint32_t)((const uint16_t *)x)[(int64_t)r * n + i]) << 16;
     };
+    auto index_of = [&](int i) -> int32_t { return xi ? xi[(int64_t)r * n + i] : i; };
     int i = threadIdx.x;
     for (; i + 3 * T < n; i += 4 * T) {  // four loads in flight
         uint32_t b0 = load_bits(i), b1 = load_bits(i + T), b2 = load_bits(i + 2 * T), b3 = load_bits(i + 3 * T);
-        cand[i] = make_composite(b0, i);
-        cand[i + T] = make_composite(b1, i + T);
-        cand[i + 2 * T] = make_composite(b2, i + 2 * T);
-        cand[i + 3 * T] = make_composite(b3, i + 3 * T);
+        const int32_t i0 = index_of(i), i1 = index_of(i + T), i2 = index_of(i + 2 * T), i3 = index_of(i + 3 * T);
+        cand[i] = make_composite(b0, i0);
+        cand[i + T] = make_composite(b1, i1);
+        cand[i + 2 * T] = make_composite(b2, i2);
+        cand[i + 3 * T] = make_composite(b3, i3);
     }
-    for (; i < n; i += T) cand[i] = make_composite(load_bits(i), i);
+    for (; i < n; i += T) cand[i] = make_composite(load_bits(i), index_of(i));
     __syncthreads();
-    int idx_bits = 1;
-    while ((1 << idx_bits) < n) ++idx_bits;
     select_write<ELT>(cand, n, k, idx_bits, out_vals, out_idx, (int64_t)r);
 }
 
@@ -133,8 +134,10 @@ __global__ void ex_init_kernel(ExRowState *st, int m, uint32_t k) {
 }
 
 // Calls f(composite) for every element of this workgroup's chunk of row r, 4 loads per lane in flight.
+// xi: when not NULL, the column index that element i of a row stands for (the rows are then lists of
+// (value, index) pairs, such as Stage-1 candidates), else i itself.
 template <int ELT, typename F>
-__device__ __forceinline__ void for_chunk(const void *x, int64_t n, int r, int chunk, F f) {
+__device__ __forceinline__ void for_chunk(const void *x, const int32_t *xi, int64_t n, int r, int chunk, F f) {
     const int64_t e0 = (int64_t)chunk * kExChunk;
     const int64_t e1 = (e0 + kExChunk < n) ? e0 + kExChunk : n;
     const int T = blockDim.x;
@@ -146,21 +149,23 @@ __device__ __forceinline__ void for_chunk(const void *x, int64_t n, int r, int c
     // wavefront-uniform state): their conditions only look at the wavefront's first element
     const int lane = threadIdx.x & (kWave - 1);
     int64_t i = e0 + threadIdx.x;
+    auto index_of = [&](int64_t i) -> int32_t { return xi ? xi[(int64_t)r * n + i] : (int32_t)i; };
     for (; i - lane + 3 * T + (kWave - 1) < e1; i += 4 * T) {
         const uint32_t b0 = load_bits(i), b1 = load_bits(i + T), b2 = load_bits(i + 2 * T), b3 = load_bits(i + 3 * T);
-        f(make_composite(b0, (int32_t)i), true);
-        f(make_composite(b1, (int32_t)(i + T)), true);
-        f(make_composite(b2, (int32_t)(i + 2 * T)), true);
-        f(make_composite(b3, (int32_t)(i + 3 * T)), true);
+        const int32_t i0 = index_of(i), i1 = index_of(i + T), i2 = index_of(i + 2 * T), i3 = index_of(i + 3 * T);
+        f(make_composite(b0, i0), true);
+        f(make_composite(b1, i1), true);
+        f(make_composite(b2, i2), true);
+        f(make_composite(b3, i3), true);
     }
     for (; i - lane < e1; i += T) {
         const bool ok = i < e1;
-        f(ok ? make_composite(load_bits(i), (int32_t)i) : 0ull, ok);
+        f(ok ? make_composite(load_bits(i), index_of(i)) : 0ull, ok);
     }
 }
 
 template <int ELT>
-__global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, int64_t n, const ExRowState *st,
+__global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, const int32_t *xi, int64_t n, const ExRowState *st,
                                                               uint32_t *ghist, int shift, int width) {
     __shared__ uint32_t lh[kExBins];
     const int r = blockIdx.y;
@@ -170,7 +175,7 @@ __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, int
     const uint32_t dmask = (1u << width) - 1u;
     for (int i = threadIdx.x; i < kExBins; i += blockDim.x) lh[i] = 0;
     __syncthreads();
-    for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
+    for_chunk<ELT>(x, xi, n, r, blockIdx.x, [&](u64 c, bool ok) {
         if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
     });
     __syncthreads();
@@ -232,7 +237,7 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
 // kStash: 2048 keeps the sweep's occupancy up when few survive; 6144 saves the second sweep when about a
 // quarter of a chunk does.
 template <int ELT, bool FILTER, int kStash>
-__global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, int64_t n, ExRowState *st, u64 *sel,
+__global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st, u64 *sel,
                                                                  int64_t k) {
     __shared__ u64 stash[kStash];
     __shared__ uint32_t wave_cnt[kMaxThreads / kWave];
@@ -247,7 +252,7 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
     __syncthreads();
     uint32_t mine = 0;  // survivors of this wavefront's share (the same number in each of its lanes)
     u64 cmax_local = 0ull;
-    for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
+    for_chunk<ELT>(x, xi, n, r, blockIdx.x, [&](u64 c, bool ok) {
         const bool keep = ok && c >= thr;
         if (!FILTER && keep && c > cmax_local) cmax_local = c;
         const u64 mask = __ballot(keep);
@@ -284,7 +289,7 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
         return;
     }
     uint32_t cursor = first + wave_base[wave];
-    for_chunk<ELT>(x, n, r, blockIdx.x, [&](u64 c, bool ok) {
+    for_chunk<ELT>(x, xi, n, r, blockIdx.x, [&](u64 c, bool ok) {
         const bool keep = ok && c >= thr;
         const u64 mask = __ballot(keep);
         const uint32_t pos = cursor + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
@@ -671,12 +676,14 @@ __global__ void __launch_bounds__(256) ex_decode_kernel(const u64 *sorted, const
 }
 
 template <int ELT>
-static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state,
-                                 void *data, hipStream_t stream) {
+static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32_t *xi, void *out_vals, int32_t *out_idx,
+                                 void *state, void *data, hipStream_t stream) {
     const int64_t m = pl.m, n = pl.n, k = pl.k;
     if (pl.single_wg) {
-        hipLaunchKernelGGL(exact_small_kernel<ELT>, dim3((unsigned)m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x, (int)n,
-                           (int)k, out_vals, out_idx);
+        int small_bits = 1;
+        while (((int64_t)1 << small_bits) < pl.idx_n) ++small_bits;
+        hipLaunchKernelGGL(exact_small_kernel<ELT>, dim3((unsigned)m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x, xi, (int)n,
+                           (int)k, small_bits, out_vals, out_idx);
         return hipGetLastError();
     }
     uint32_t *ghist = (uint32_t *)state;
@@ -690,15 +697,15 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
     // are copied out in one more sweep and finished in LDS instead of being swept digit by digit.
     const bool filter = pl.filter;
     int idx_bits = 1;  // column indices are below 2^idx_bits
-    while (((int64_t)1 << idx_bits) < n) ++idx_bits;
+    while (((int64_t)1 << idx_bits) < pl.idx_n) ++idx_bits;
     for (int p = 0; p < kExPasses; ++p) {
-        hipLaunchKernelGGL(ex_hist_kernel<ELT>, sweep, dim3(kMaxThreads), 0, stream, x, n, st, ghist, kExShift[p],
+        hipLaunchKernelGGL(ex_hist_kernel<ELT>, sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist, kExShift[p],
                            kExWidth[p]);
         hipLaunchKernelGGL(ex_decide_kernel, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p],
                            p == kExPasses - 1 ? 1 : 0, (uint32_t)((p == 0 && filter) ? kFilterCap : 0));
         if (p == 0 && filter) {
             u64 *fbuf = sel + m * k;
-            hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, fbuf,
+            hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, fbuf,
                                (int64_t)kFilterCap);
             const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
             hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st,
@@ -706,9 +713,9 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
         }
     }
     if (k * kExChunk / n <= 1536)  // expected survivors per chunk
-        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k);
     else
-        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 6144>), sweep, dim3(kMaxThreads), 0, stream, x, n, st, sel, k);
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 6144>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -764,10 +771,10 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, void *out_v
     return hipGetLastError();
 }
 
-hipError_t launch_exact(const ExactPlan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state,
-                        void *data, hipStream_t stream) {
-    if (pl.dtype == ATK_F32) return launch_exact_t<ATK_F32>(pl, x, out_vals, out_idx, state, data, stream);
-    return launch_exact_t<ATK_BF16>(pl, x, out_vals, out_idx, state, data, stream);
+hipError_t launch_exact(const ExactPlan &pl, const void *x, const int32_t *xi, void *out_vals, int32_t *out_idx,
+                        void *state, void *data, hipStream_t stream) {
+    if (pl.dtype == ATK_F32) return launch_exact_t<ATK_F32>(pl, x, xi, out_vals, out_idx, state, data, stream);
+    return launch_exact_t<ATK_BF16>(pl, x, xi, out_vals, out_idx, state, data, stream);
 }
 
 }  // namespace atk

@@ -222,8 +222,6 @@ def random_cases(seed, count):
         lo = max(k_b, 1)
         hi = b * k_b
         k = int(rng.choice([hi, rng.integers(lo, hi + 1)]))
-        if hi > k and hi > 4096:
-            k = hi  # no Stage 2 over more candidates than the library takes
         out.append((m, n, k, b, k_b))
     return out
 
@@ -242,6 +240,20 @@ def test_many_short_rows():
     run_case(x, 8, 8, 1, tag="many rows")
     run_case(x, 6, 16, 1, tag="many rows, Stage 2")
     run_case(x, 16, 8, 2, tag="many rows", assignment=atk.ATK_CONTIGUOUS)
+
+
+def test_stage2_over_many_candidates():
+    """b*k_b above what one workgroup holds: Stage 1 leaves the candidates in scratch and the long-row
+    selection finishes; ties are still decided by the original column index."""
+    cases = [(3, 65536, 4096, 8192, 1), (3, 65536, 1000, 4096, 2), (2, 100000, 5000, 10000, 3), (2, 40000, 4097, 4100, 1),
+             (2, 1 << 18, 20000, 1 << 15, 1), (130, 20000, 100, 5000, 1)]
+    for dtype in ["f32", "bf16"]:
+        for i, (m, n, k, b, k_b) in enumerate(cases):
+            run_case(workloads.normal_rows(m, n, seed=800 + i, dtype=dtype), k, b, k_b, tag="big stage 2")
+        run_case(workloads.few_levels(3, 65536, levels=3, seed=5, dtype=dtype), 3000, 8192, 1, tag="big stage 2, 3 levels")
+        run_case(workloads.special_values(2, 65536, seed=6, dtype=dtype), 5000, 4096, 2, tag="big stage 2, specials")
+        run_case(workloads.normal_rows(3, 65536, seed=810, dtype=dtype), 4096, 8192, 1, tag="big stage 2 contiguous",
+                 assignment=atk.ATK_CONTIGUOUS)
 
 
 # ------------------------------------------------------------------------------- contiguous assignment

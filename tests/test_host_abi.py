@@ -59,7 +59,7 @@ OK, NULLP, SHAPE, PARAMS, UNSUP, DTYPE = 0, -1, -2, -3, -4, -5
     ((4, 4095, 64, 64, 1, 0), OK),          # n not a multiple of b: short buckets
     ((4, 4095, 64, 64, 64, 0), PARAMS),     # k_b above floor(n/b)
     ((4, 4096, 64, 2, 32, 0), UNSUP),       # k_b above the register-queue cap
-    ((4, 1 << 16, 64, 1 << 13, 1, 0), UNSUP),  # Stage 2 over more candidates than fit on chip
+    ((4, 1 << 16, 64, 1 << 13, 1, 0), OK),     # Stage 2 over more candidates than fit on chip: further launches
 ])
 def test_check_approx(lib, args, code):
     assert lib.atk_check_approx(*args) == code
@@ -207,6 +207,10 @@ def test_workspace_bytes(lib):
     assert lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0) == p["scratch_bytes"] > 0
     assert lib.atk_workspace_bytes(128, 65536, 64, 32, 1, 0) == PARAMS
     assert lib.atk_stage2_max_candidates() >= 1024
+    # more candidates than one workgroup holds: Stage 1 writes them to scratch (values + indices) for the second step
+    p2 = parse_plan(atk.plan_describe(4, 1 << 16, 64, 1 << 13, 1))
+    assert p2["stage2"] == 2 and p2["scratch_bytes"] >= 4 * (1 << 13) * 8
+    assert lib.atk_workspace_bytes(4, 1 << 16, 64, 1 << 13, 1, 0) == p2["scratch_bytes"]
     assert lib.atk_workspace_bytes_assign(128, 65536, 64, 64, 1, 0, 0) == lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0)
     pc = parse_contig_plan(atk.plan_describe(1, 1 << 20, 64, 8, 8, atk.ATK_F32, atk.ATK_CONTIGUOUS))
     assert lib.atk_workspace_bytes_assign(1, 1 << 20, 64, 8, 8, 0, 1) == pc["scratch_bytes"] > 0
