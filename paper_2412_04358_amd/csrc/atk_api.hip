@@ -110,7 +110,15 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (want_threads > 2048 * (int64_t)kNumCU) want_threads = 2048 * (int64_t)kNumCU;
     // with queues, a lane that sees more rows inserts less often: half as many lanes measured faster
     if (p.KB >= 4 && want_threads > 1024 * (int64_t)kNumCU) want_threads = 1024 * (int64_t)kNumCU;
+    // A running maximum costs a lane next to nothing, so k_b = 1 is bound by the memory system alone,
+    // and that likes few, long streams: about one workgroup per CU measured fastest on long rows
+    // (128 x 2^20, b = 64: 85.6 us with 1024 workgroups of 512 lanes, 80.1 with 256, 75.5 with 256
+    // of 256 lanes), and every split less is a partial list less through memory.
+    if (p.KB == 1) want_threads = 512 * (int64_t)kNumCU;
+    // rows short enough that a Stage 2 plan is better off in one workgroup per row than in two (below)
+    const bool one_piece = n * (dtype == ATK_BF16 ? 4 : 1) <= 512 * 512;
     int T = 256;
+    int64_t lanes_per_wg = 0;  // what a workgroup counts as when the splits are chosen (0: its size)
     if (p.G <= 256) {
         const int t_cols = (int)(ceil_div(p.G, kWave) * kWave);  // lanes that give every column group one lane
         if (m * t_cols * 2 >= want_threads) {
@@ -119,6 +127,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         } else {
             T = t_max < 512 ? t_max : 512;
             while (T > 256 && m * T * 2 > want_threads) T >>= 1;  // keep at least two splits' worth of lanes
+            // k_b = 1 in f32 with at least 32 loads per lane left: four wavefronts per CU stream faster
+            // than eight (fewer open streams per memory channel); the number of workgroups stays.
+            // bf16 lanes do twice the work per load and want the eight (43 against 55 us on 128 x 2^20).
+            if (p.KB == 1 && T == 512 && dtype == ATK_F32 && !(p.stage2 && one_piece)) {
+                const int64_t s512 = std::max<int64_t>(1, want_threads / (m * 512));
+                if (p.L * p.G / (512 * s512) >= 32) { T = 256; lanes_per_wg = 512; }
+            }
         }
     }
     // Stage 2 runs in this workgroup: it wants a lane for every two candidates (four at most, or it
@@ -131,7 +146,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // many column groups but few rows: smaller workgroups rather than row splits
     if (p.G > 256)
         while (T > kWave && m * ceil_div(p.G, T) < (int64_t)kNumCU) T >>= 1;
-    if (T_forced) T = T_forced;
+    if (T_forced) { T = T_forced; lanes_per_wg = 0; }
     if (T > t_max) T = t_max;
 
     // Long queues (k_b >= 5) on short buckets are bound by the chain of dependent selects of each
@@ -184,7 +199,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.colblocks = (int)ceil_div(p.G, p.Gw);
 
     int64_t base = m * p.colblocks;
-    int64_t S = want_threads / (base * T);
+    int64_t S = want_threads / (base * (lanes_per_wg ? lanes_per_wg : T));
     int64_t s_rows = p.L / ((int64_t)p.P * 4);       // every lane keeps at least 4 loads
     int64_t s_traffic = (p.L * es) / (32 * k_b);     // partial lists (written + read back) below half the bytes streamed
     int64_t s_fill = ceil_div(kNumCU, base);         // splits that give every CU a workgroup
@@ -193,7 +208,10 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // Two splits buy nothing once half the CUs have a big workgroup each (the memory system, not the
     // CU count, bounds a launch of this size), and cost the trip through scratch and the ticket
     // before Stage 2 can start: measured equal at b <= 512 and 1 us slower at b = 1024 on 128 x 65536.
-    if (S == 2 && p.stage2 && p.colblocks == 1 && base * T >= 256 * (int64_t)kNumCU) S = 1;
+    // Long rows are the other way round: there the second workgroup per row shortens the streaming
+    // part by more than the trip costs (128 x 2^20 f32, b = 1024: 90.5 us in one piece, 84.2 in two;
+    // the two are level at 2^18 elements in f32 and at 2^16 in bf16).
+    if (S == 2 && p.stage2 && p.colblocks == 1 && base * T >= 256 * (int64_t)kNumCU && one_piece) S = 1;
     {
         // The workgroup that draws the last ticket merges S lists per column, SU splits per batch
         // of loads, tpc lanes per column: keep that serial tail to about four batches.
