@@ -5,6 +5,7 @@
 // paper's operation counts.  Section 3 / Appendix E describe the trade-off this makes
 // executable: for k << n raise b (more candidates, then Stage 2), for k ~ n raise k_b with
 // b*k_b = k.  No HIP call is made here.
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 
@@ -28,24 +29,39 @@ static double eq1_recall(int64_t k, int64_t b, int64_t k_b) {
 }
 
 // Microseconds of one approx_topk call, from measurements of this library on one MI355X:
-// a fixed launch + ramp cost, the row bytes at the streaming rate a launch of that size
-// reaches, a factor for the register queues of k_b > 1, the hand-over between workgroups when
-// rows are split, and Stage 2.
+// a fixed launch + ramp cost, the bytes at the streaming rate a launch of that size reaches
+// (the bytes read times a factor for the register queues of k_b > 1), the hand-over between
+// workgroups when rows are split, and Stage 2.  Small launches are bound by the chain of
+// hand-overs instead (workgroup merge, ticket, merge of the splits, Stage 2): a floor.
 static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
     const double es = (dtype == ATK_F32) ? 4.0 : 2.0;
-    const double bytes = (double)m * (double)n * es + (double)m * (double)k * (es + 4.0);
-    // streaming rate grows with the size of the launch: about 5.5 TB/s at 32 MB, 6.4 TB/s from 0.5 GB
-    double rate = 6.5e6 * bytes / (bytes + 6.0e6);  // bytes per microsecond
-    if (rate < 0.5e6) rate = 0.5e6;
+    const double rd = (double)m * (double)n * es, wr = (double)m * (double)k * (es + 4.0), bytes = rd + wr;
     int KB = 1;
     while (KB < k_b) KB <<= 1;
-    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.05 : KB == 4 ? 1.25 : KB == 8 ? 2.1 : 4.5;
-    double us = 1.5 + bytes / rate * queue;
+    // streaming rate grows with the size of the launch.  f32 running maxima: 5.8 TB/s at 32 MB,
+    // 7.1 TB/s at 0.5 GB; queues and bf16 (twice the elements per byte): 5.5 and 6.4 TB/s
+    const bool lean = KB == 1 && dtype == ATK_F32;
+    double rate = (lean ? 7.2e6 : 6.5e6) * bytes / (bytes + (lean ? 8.0e6 : 6.0e6));  // bytes per microsecond
+    if (rate < 0.5e6) rate = 0.5e6;
+    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.07 : KB == 4 ? 1.3 : KB == 8 ? 2.3 : 6.0;
+    double us = 1.5 + (rd * queue + wr) / rate;
     const bool stage2 = b * k_b > k;
-    // rows are split over workgroups when one lane per column group cannot fill the chip
-    const double lanes = (double)m * (double)b / ((dtype == ATK_F32) ? 4.0 : 8.0);
-    if (lanes < 65536.0 || stage2) us += 2.0;
-    if (stage2) us += 2.5 + 0.0015 * (double)(b * k_b);
+    const double cand = (double)(b * k_b);
+    // Rows are split over workgroups when whole rows, in workgroups of one lane per column group
+    // (64 lanes at least), leave CUs idle; a lane keeps four loads at least.
+    const double groups = (double)b / (double)stage1_pick_v(dtype, KB, 0, b);
+    double splits = 256.0 / ((double)m * std::max(1.0, groups / 64.0));
+    splits = std::min(splits, std::min((double)n / 8192.0, (double)(n / b) / 4.0));
+    if (stage2 && splits > 16.0) splits = 16.0;
+    if (splits > 128.0) splits = 128.0;
+    const bool split = splits >= 2.0;
+    if (split || stage2) us += 2.0;
+    if (stage2) us += 2.5 + 0.0015 * cand;
+    double floor_us = 4.0;
+    if (split && !(stage2 && m >= 128)) floor_us = 7.5 + bytes / 16.0e6 + (stage2 ? 4.0 + 0.0015 * cand : 0.0);
+    if (us < floor_us) us = floor_us;
+    // few rows: many splits per row, merged by the workgroup that finishes the row
+    if (split && splits > 2.0) us += 0.04 * splits * (stage2 ? std::max(1.0, cand / 256.0) : 1.0);
     return us;
 }
 
