@@ -23,6 +23,7 @@ constexpr int kExPasses = 6;             // 64 bits = 11+11+10 (value key) + 11+
 constexpr int kExShift[kExPasses] = {53, 42, 32, 21, 10, 0};
 constexpr int kExWidth[kExPasses] = {11, 11, 10, 11, 11, 10};
 constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps
+constexpr int kExRow = kExBins + kTicketStride;  // words per row of the global histograms: the bins, then the row's ticket
 constexpr int kSortTile = 2048;          // elements per workgroup of the global sort
 constexpr int kSortLdsMaxK = 4096;       // survivors ordered in LDS by one workgroup
 constexpr int kPartTile = 4096;          // survivors per workgroup of the partition sort's sweeps
@@ -75,7 +76,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.chunks = (int)ceil_div64(n, kExChunk);
     if (m > 65535) return ATK_ERR_UNSUPPORTED;  // rows are the grid's y dimension: exact_topk() passes blocks of rows
     // state pool: global histograms (left zero by every call)
-    p.state_bytes = m * kExBins * 4;
+    p.state_bytes = m * (int64_t)kExRow * 4;
     // data pool: row states, survivors, and for the global sort a second buffer + tile histograms
     int64_t bytes = m * (int64_t)sizeof(ExRowState);
     bytes = ceil_div64(bytes, 256) * 256;
@@ -121,18 +122,6 @@ __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x,
 }
 
 // ------------------------------------------------------------------------------------ long rows
-__global__ void ex_init_kernel(ExRowState *st, int m, uint32_t k) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r < m) {
-        st[r].prefix = 0ull;
-        st[r].need = k;
-        st[r].done = 0u;
-        st[r].cursor = 0u;
-        st[r].mode = 0u;
-        st[r].cmax = 0ull;
-    }
-}
-
 // Calls f(composite) for every element of this workgroup's chunk of row r, 4 loads per lane in flight.
 // xi: when not NULL, the column index that element i of a row stands for (the rows are then lists of
 // (value, index) pairs, such as Stage-1 candidates), else i itself.
@@ -164,51 +153,34 @@ __device__ __forceinline__ void for_chunk(const void *x, const int32_t *xi, int6
     }
 }
 
-template <int ELT>
-__global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, const int32_t *xi, int64_t n, const ExRowState *st,
-                                                              uint32_t *ghist, int shift, int width) {
-    __shared__ uint32_t lh[kExBins];
-    const int r = blockIdx.y;
-    if (st[r].done) return;  // uniform over the workgroup
-    const u64 prefix = st[r].prefix;
-    const u64 hi_mask = (shift + width >= 64) ? 0ull : (~0ull << (shift + width));
-    const uint32_t dmask = (1u << width) - 1u;
-    for (int i = threadIdx.x; i < kExBins; i += blockDim.x) lh[i] = 0;
-    __syncthreads();
-    for_chunk<ELT>(x, xi, n, r, blockIdx.x, [&](u64 c, bool ok) {
-        if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
-    });
-    __syncthreads();
-    uint32_t *gh = ghist + (int64_t)r * kExBins;
-    for (int i = threadIdx.x; i < kExBins; i += blockDim.x) {
-        const uint32_t v = lh[i];
-        if (v) atomicAdd(&gh[i], v);
-    }
-}
-
-// One workgroup (256 lanes) per row: pick the digit bucket that holds the need-th largest
-// element, update the row state, and leave the global histogram zeroed.
+// The digit bucket that holds the need-th largest element of row r, from the row's global
+// histogram `gh`; updates the row state and leaves the histogram zeroed.  Called by a whole
+// workgroup of at least 256 lanes (uniformly); wave_tot: four words of LDS.
+// The histogram is read and cleared with agent-scope atomic accesses: they act on memory, not
+// on one XCD's L2, as the atomics that filled it did.
+// FIRST: the first pass; the row state is not read (no digit decided, k elements needed) but set up.
 // filter_cap > 0 (first pass only): a row with at most that many elements in or above the chosen
 // bucket, and not finished by this pass alone, is handed to the copy-out path (mode 1).
-__global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t *ghist, int shift, int last_pass,
-                                                        uint32_t filter_cap) {
-    __shared__ uint32_t wave_tot[4];
-    const int r = blockIdx.x, tid = threadIdx.x;
-    if (st[r].done) return;
-    uint32_t *gh = ghist + (int64_t)r * kExBins;
-    const uint32_t need = st[r].need;
-    // lane t owns bins 2047-8t-7 .. 2047-8t: lane order is descending bin order
+template <bool FIRST>
+__device__ __forceinline__ void decide_row(ExRowState *st, uint32_t *gh, int r, u64 prefix, uint32_t need, int shift,
+                                           int last_pass, uint32_t filter_cap, uint32_t *wave_tot) {
+    const int tid = threadIdx.x;
+    // lane t of the first 256 owns bins 2047-8t-7 .. 2047-8t: lane order is descending bin order
+    const bool owner = tid < 256;
     uint32_t hb[8], s = 0;
-    const int base = kExBins - 8 - 8 * tid;
+    const int base = owner ? kExBins - 8 - 8 * tid : 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        hb[q] = owner ? __hip_atomic_load(&gh[base + q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-        hb[q] = gh[base + q];
-        gh[base + q] = 0;
+        if (hb[q]) __hip_atomic_store(&gh[base + q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s += hb[q];
     }
     const uint32_t incl = wave_incl_scan_u32(s);
-    if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+    if (owner && (tid & 63) == 63) wave_tot[tid >> 6] = incl;
     __syncthreads();
+    if (!owner) return;
     uint32_t above = incl - s;
     for (int w = 0; w < (tid >> 6); ++w) above += wave_tot[w];
 #pragma unroll
@@ -216,14 +188,72 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
         const uint32_t with = above + hb[q];
         if (above < need && with >= need) {
             const uint32_t left = need - above;
-            st[r].prefix |= (u64)(uint32_t)(base + q) << shift;
-            st[r].need = left;
             const bool done = hb[q] == left || last_pass;
-            st[r].done = done ? 1u : 0u;
-            if (filter_cap && !done && with <= filter_cap) st[r].mode = 1u;
+            ExRowState ns;
+            ns.prefix = prefix | ((u64)(uint32_t)(base + q) << shift);
+            ns.need = left;
+            ns.done = done ? 1u : 0u;
+            ns.cursor = FIRST ? 0u : st[r].cursor;
+            ns.mode = (filter_cap && !done && with <= filter_cap) ? 1u : (FIRST ? 0u : st[r].mode);
+            ns.cmax = FIRST ? 0ull : st[r].cmax;
+            st[r] = ns;
         }
         above = with;
     }
+}
+
+// One pass of the digit descent for row blockIdx.y: every workgroup counts the digits of its chunk
+// (LDS histogram, flushed to the row's global one with agent-scope atomics).
+// FUSED (launches of few workgroups, where a second launch costs as much as the sweep): the
+// workgroup that finishes the row last - a ticket, taken after its own counts have been
+// acknowledged - goes on to decide_row().  Big launches leave that to ex_decide_kernel: there the
+// wait for the acknowledgement at the end of every workgroup would idle lanes that could stream.
+template <int ELT, bool FIRST, bool FUSED>
+__global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st,
+                                                              uint32_t *ghist, int shift, int width, int last_pass,
+                                                              uint32_t filter_cap, uint32_t k) {
+    __shared__ uint32_t lh[kExBins];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t is_last;
+    const int r = blockIdx.y, tid = threadIdx.x;
+    if (!FIRST && st[r].done) return;  // uniform over the workgroup
+    const u64 prefix = FIRST ? 0ull : st[r].prefix;
+    const uint32_t need = FIRST ? k : st[r].need;
+    const u64 hi_mask = (shift + width >= 64) ? 0ull : (~0ull << (shift + width));
+    const uint32_t dmask = (1u << width) - 1u;
+    for (int i = tid; i < kExBins; i += blockDim.x) lh[i] = 0;
+    __syncthreads();
+    for_chunk<ELT>(x, xi, n, r, blockIdx.x, [&](u64 c, bool ok) {
+        if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
+    });
+    __syncthreads();
+    uint32_t *gh = ghist + (int64_t)r * kExRow;
+    for (int i = tid; i < kExBins; i += blockDim.x) {
+        const uint32_t v = lh[i];
+        if (v) __hip_atomic_fetch_add(&gh[i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (!FUSED) return;
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this lane's counts have been acknowledged (a barrier alone does not wait for them)
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t ticket = __hip_atomic_fetch_add(&gh[kExBins], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (ticket == gridDim.x - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    if (tid == 0) __hip_atomic_store(&gh[kExBins], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    decide_row<FIRST>(st, gh, r, prefix, need, shift, last_pass, filter_cap, wave_tot);
+}
+
+// The same decision as a launch of its own, one workgroup of 256 lanes per row.
+template <bool FIRST>
+__global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t *ghist, int shift, int last_pass,
+                                                        uint32_t filter_cap, uint32_t k) {
+    __shared__ uint32_t wave_tot[4];
+    const int r = blockIdx.x;
+    if (!FIRST && st[r].done) return;
+    decide_row<FIRST>(st, ghist + (int64_t)r * kExRow, r, FIRST ? 0ull : st[r].prefix, FIRST ? k : st[r].need, shift, last_pass,
+                      filter_cap, wave_tot);
 }
 
 // Every element at or above the row's threshold goes to sel[row][..] (exactly k of them, any order).
@@ -692,17 +722,33 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     u64 *sel = (u64 *)((unsigned char *)data + st_bytes);
     const dim3 sweep((unsigned)pl.chunks, (unsigned)m);
 
-    hipLaunchKernelGGL(ex_init_kernel, dim3((unsigned)ceil_div64(m, 256)), dim3(256), 0, stream, st, (int)m, (uint32_t)k);
     // Small k: after the first digit most rows have only a handful of elements left in play; those
     // are copied out in one more sweep and finished in LDS instead of being swept digit by digit.
     const bool filter = pl.filter;
     int idx_bits = 1;  // column indices are below 2^idx_bits
     while (((int64_t)1 << idx_bits) < pl.idx_n) ++idx_bits;
+    const bool fused = (int64_t)pl.chunks * m <= 1024;  // few workgroups: the row's last one also decides
     for (int p = 0; p < kExPasses; ++p) {
-        hipLaunchKernelGGL(ex_hist_kernel<ELT>, sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist, kExShift[p],
-                           kExWidth[p]);
-        hipLaunchKernelGGL(ex_decide_kernel, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p],
-                           p == kExPasses - 1 ? 1 : 0, (uint32_t)((p == 0 && filter) ? kFilterCap : 0));
+        const int last = p == kExPasses - 1 ? 1 : 0;
+        const uint32_t fcap = (uint32_t)((p == 0 && filter) ? kFilterCap : 0);
+#define ATK_HIST(FIRST, FUSED)                                                                                              \
+    hipLaunchKernelGGL((ex_hist_kernel<ELT, FIRST, FUSED>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist,        \
+                       kExShift[p], kExWidth[p], last, fcap, (uint32_t)k)
+        if (fused) {
+            if (p == 0) ATK_HIST(true, true);
+            else ATK_HIST(false, true);
+        } else {
+            if (p == 0) {
+                ATK_HIST(true, false);
+                hipLaunchKernelGGL(ex_decide_kernel<true>, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p], last,
+                                   fcap, (uint32_t)k);
+            } else {
+                ATK_HIST(false, false);
+                hipLaunchKernelGGL(ex_decide_kernel<false>, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p],
+                                   last, fcap, (uint32_t)k);
+            }
+        }
+#undef ATK_HIST
         if (p == 0 && filter) {
             u64 *fbuf = sel + m * k;
             hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, fbuf,

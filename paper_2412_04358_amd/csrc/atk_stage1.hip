@@ -226,10 +226,12 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
         // ------------------------------------------------------------ ticket
         // Cross-workgroup hand-over without cache-wide fences: the lists were written, and are
         // read below, with agent-scope atomic accesses (they go through to memory instead of
-        // staying in one XCD's L2); the barrier waits until this workgroup's stores have been
-        // acknowledged, and only then one lane takes the ticket.  Whoever draws the last one
-        // knows that every other workgroup's lists are complete.
+        // staying in one XCD's L2); every lane waits until its own stores have been acknowledged
+        // (a barrier alone does not: inside a workgroup the compiler lets global stores stay in
+        // flight across it), and only after the barrier one lane takes the ticket.  Whoever draws
+        // the last one knows that every other workgroup's lists are complete.
         if (p.fence_sync) __threadfence();
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
         __syncthreads();
         uint32_t *flag = (uint32_t *)smem;
         uint32_t *ticket_word = p.tickets + tk * kTicketStride;
