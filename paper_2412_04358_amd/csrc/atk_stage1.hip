@@ -252,17 +252,25 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
         // lists of splits s_first, s_first + s_step, ... of column `col`, merged into acc
         auto gather = [&](int col, int s_first, int s_step, u64(&acc)[KB]) {
             for (int s0 = s_first; s0 < p.S; s0 += s_step) {
+                // every load of the batch is issued, at an address clamped into the lists, and the
+                // ones past the end are dropped afterwards: loads under a condition would each sit
+                // in a branch of their own and wait for one another
                 u64 th[SU][KB];
 #pragma unroll
-                for (int u = 0; u < SU; ++u)
+                for (int u = 0; u < SU; ++u) {
+                    const int su = s0 + u < p.S ? s0 + u : p.S - 1;
 #pragma unroll
                     for (int j = 0; j < KB; ++j)
-                        th[u][j] = (s0 + u < p.S && j < p.k_b)
-                                       ? __hip_atomic_load(&src[((int64_t)(s0 + u) * p.b + col) * p.k_b + j],
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                       : 0ull;
+                        th[u][j] = __hip_atomic_load(&src[((int64_t)su * p.b + col) * p.k_b + (j < p.k_b ? j : p.k_b - 1)],
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
 #pragma unroll
-                for (int u = 0; u < SU; ++u) merge_topk<KB>(acc, th[u]);
+                for (int u = 0; u < SU; ++u) {
+#pragma unroll
+                    for (int j = 0; j < KB; ++j)
+                        if (s0 + u >= p.S || j >= p.k_b) th[u][j] = 0ull;
+                    merge_topk<KB>(acc, th[u]);
+                }
             }
         };
         auto put = [&](int col, const u64(&acc)[KB]) {
