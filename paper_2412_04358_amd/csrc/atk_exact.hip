@@ -11,6 +11,9 @@
 // finished as soon as its bucket holds exactly the number of elements still needed.  Then one
 // more sweep collects every element at or above the threshold, and the k survivors are
 // ordered: in LDS when they fit, else by a least-significant-digit radix sort in global memory.
+#include <cstdlib>
+#include <cstring>
+
 #include "atk_common.h"
 #include "atk_select.h"
 
@@ -30,6 +33,11 @@ constexpr int kPartTile = 4096;          // survivors per workgroup of the parti
 constexpr int kPartMaxBins = 2048;
 constexpr int kPartWaveMax = 512;        // largest bin that one wavefront orders on its own
 constexpr int kFilterMaxK = 1024;        // largest k that takes the copy-out path (its selection must fit 64 KB of LDS)
+constexpr int kSampleMaxK = 128;        // largest k whose threshold is first guessed from a sample of the row
+constexpr int kSampleChunk = 2048;       // the sample: every 16th run of 2048 elements
+constexpr int kSampleStride = 16;
+constexpr int64_t kSampleMinBytes = 128ll << 20;  // smaller inputs are not worth the extra launches
+constexpr uint32_t kSampledPass = 0xfffffffeu, kSampledLast = 0xffffffffu;  // in place of a copy-out limit: see decide_row()
 constexpr int kFilterCap = 4096;         // elements at or above the first digit's bucket that one workgroup selects from in LDS
 
 struct ExRowState {  // one per row, 32 bytes
@@ -64,6 +72,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.state_bytes = 0;
     p.lds_bytes = 0;
     p.filter = false;
+    p.sample = false;
     p.idx_n = n;
     if (m >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
     const int64_t lds = select_lds_bytes(n, (int)pow2_ceil64(k < (1 << 20) ? k : (1 << 20)));
@@ -84,6 +93,14 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     // copy-out buffer of the small-k path, as long as it stays modest (256 MB)
     p.filter = k <= kFilterMaxK && m * (int64_t)kFilterCap * 8 <= (256ll << 20);
     if (p.filter) bytes += m * (int64_t)kFilterCap * 8;
+    {
+        // ATK_PLAN="XS=1" takes the sampled threshold on small inputs too, "XS=0" never (tests, sweeps)
+        const char *e = getenv("ATK_PLAN");
+        const bool force = e && strstr(e, "XS=1"), off = e && strstr(e, "XS=0");
+        const int64_t es = (dtype == ATK_F32) ? 4 : 2;
+        p.sample = p.filter && !off && k <= kSampleMaxK && n >= 4 * (int64_t)kSampleChunk * kSampleStride &&
+                   (force || m * n * es >= kSampleMinBytes);
+    }
     if (k > kSortLdsMaxK) {
         bytes += m * k * 8;
         bytes += m * ceil_div64(k, kSortTile) * 256 * 4;
@@ -126,9 +143,10 @@ __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x,
 // xi: when not NULL, the column index that element i of a row stands for (the rows are then lists of
 // (value, index) pairs, such as Stage-1 candidates), else i itself.
 template <int ELT, typename F>
-__device__ __forceinline__ void for_chunk(const void *x, const int32_t *xi, int64_t n, int r, int chunk, F f) {
-    const int64_t e0 = (int64_t)chunk * kExChunk;
-    const int64_t e1 = (e0 + kExChunk < n) ? e0 + kExChunk : n;
+__device__ __forceinline__ void for_chunk(const void *x, const int32_t *xi, int64_t n, int r, int chunk, F f,
+                                          int chunk_elems = kExChunk) {
+    const int64_t e0 = (int64_t)chunk * chunk_elems;
+    const int64_t e1 = (e0 + chunk_elems < n) ? e0 + chunk_elems : n;
     const int T = blockDim.x;
     auto load_bits = [&](int64_t i) -> uint32_t {
         if (ELT == ATK_F32) return __builtin_nontemporal_load((const uint32_t *)x + (int64_t)r * n + i);
@@ -161,6 +179,9 @@ __device__ __forceinline__ void for_chunk(const void *x, const int32_t *xi, int6
 // FIRST: the first pass; the row state is not read (no digit decided, k elements needed) but set up.
 // filter_cap > 0 (first pass only): a row with at most that many elements in or above the chosen
 // bucket, and not finished by this pass alone, is handed to the copy-out path (mode 1).
+// filter_cap == kSampledPass (a pass over a sample of the row): the counts say nothing about the whole
+// row, so the row is never finished here; kSampledLast (the last such pass): the row goes to the
+// copy-out path with the digits decided so far as its threshold.
 template <bool FIRST>
 __device__ __forceinline__ void decide_row(ExRowState *st, uint32_t *gh, int r, u64 prefix, uint32_t need, int shift,
                                            int last_pass, uint32_t filter_cap, uint32_t *wave_tot) {
@@ -188,13 +209,16 @@ __device__ __forceinline__ void decide_row(ExRowState *st, uint32_t *gh, int r, 
         const uint32_t with = above + hb[q];
         if (above < need && with >= need) {
             const uint32_t left = need - above;
-            const bool done = hb[q] == left || last_pass;
+            const bool sampled = filter_cap >= kSampledPass;
+            const bool done = !sampled && (hb[q] == left || last_pass);
             ExRowState ns;
             ns.prefix = prefix | ((u64)(uint32_t)(base + q) << shift);
             ns.need = left;
             ns.done = done ? 1u : 0u;
             ns.cursor = FIRST ? 0u : st[r].cursor;
-            ns.mode = (filter_cap && !done && with <= filter_cap) ? 1u : (FIRST ? 0u : st[r].mode);
+            ns.mode = (filter_cap == kSampledLast || (!sampled && filter_cap && !done && with <= filter_cap))
+                          ? 1u
+                          : (FIRST ? 0u : st[r].mode);
             ns.cmax = FIRST ? 0ull : st[r].cmax;
             st[r] = ns;
         }
@@ -211,7 +235,8 @@ __device__ __forceinline__ void decide_row(ExRowState *st, uint32_t *gh, int r, 
 template <int ELT, bool FIRST, bool FUSED>
 __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st,
                                                               uint32_t *ghist, int shift, int width, int last_pass,
-                                                              uint32_t filter_cap, uint32_t k) {
+                                                              uint32_t filter_cap, uint32_t k, int chunk_elems,
+                                                              int chunk_stride) {
     __shared__ uint32_t lh[kExBins];
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t is_last;
@@ -223,9 +248,13 @@ __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, con
     const uint32_t dmask = (1u << width) - 1u;
     for (int i = tid; i < kExBins; i += blockDim.x) lh[i] = 0;
     __syncthreads();
-    for_chunk<ELT>(x, xi, n, r, blockIdx.x, [&](u64 c, bool ok) {
-        if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
-    });
+    // chunk_stride > 1: a sample of the row, in small chunks
+    for_chunk<ELT>(
+        x, xi, n, r, (int)blockIdx.x * chunk_stride,
+        [&](u64 c, bool ok) {
+            if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
+        },
+        chunk_elems);
     __syncthreads();
     uint32_t *gh = ghist + (int64_t)r * kExRow;
     for (int i = tid; i < kExBins; i += blockDim.x) {
@@ -355,6 +384,22 @@ __global__ void __launch_bounds__(kMaxThreads) ex_filter_select_kernel(const u64
     const int r = blockIdx.x;
     if (st[r].mode != 1u) return;  // uniform; read by every lane before lane 0 changes it below
     const int count = (int)st[r].cursor;
+    if (count > kFilterCap) {
+        // only after a threshold guessed from a sample: more elements reach it than were copied out.
+        // The row starts over, digit by digit over all its elements.
+        __syncthreads();  // every lane has read the state
+        if (threadIdx.x == 0) {
+            ExRowState ns;
+            ns.prefix = 0ull;
+            ns.need = (uint32_t)k;
+            ns.done = 0u;
+            ns.cursor = 0u;
+            ns.mode = 0u;
+            ns.cmax = 0ull;
+            st[r] = ns;
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < count; i += blockDim.x) cand[i] = buf[(int64_t)r * kFilterCap + i];
     __syncthreads();
     select_write<ELT>(cand, count, k, idx_bits, out_vals, out_idx, (int64_t)r);
@@ -724,21 +769,22 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
 
     // Small k: after the first digit most rows have only a handful of elements left in play; those
     // are copied out in one more sweep and finished in LDS instead of being swept digit by digit.
-    const bool filter = pl.filter;
     int idx_bits = 1;  // column indices are below 2^idx_bits
     while (((int64_t)1 << idx_bits) < pl.idx_n) ++idx_bits;
-    const bool fused = (int64_t)pl.chunks * m <= 1024;  // few workgroups: the row's last one also decides
-    for (int p = 0; p < kExPasses; ++p) {
+    // One pass of the digit descent over every `stride`-th chunk of the rows; small launches let the
+    // row's last workgroup decide, big ones take a launch of their own for it.
+    auto pass = [&](int p, bool first, uint32_t fcap, int elems, int stride, bool fuse) {
         const int last = p == kExPasses - 1 ? 1 : 0;
-        const uint32_t fcap = (uint32_t)((p == 0 && filter) ? kFilterCap : 0);
-#define ATK_HIST(FIRST, FUSED)                                                                                              \
-    hipLaunchKernelGGL((ex_hist_kernel<ELT, FIRST, FUSED>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist,        \
-                       kExShift[p], kExWidth[p], last, fcap, (uint32_t)k)
+        const dim3 grid((unsigned)ceil_div64(n, (int64_t)elems * stride), (unsigned)m);
+        const bool fused = fuse || (int64_t)grid.x * m <= 1024;
+#define ATK_HIST(FIRST, FUSED)                                                                                             \
+    hipLaunchKernelGGL((ex_hist_kernel<ELT, FIRST, FUSED>), grid, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist,        \
+                       kExShift[p], kExWidth[p], last, fcap, (uint32_t)k, elems, stride)
         if (fused) {
-            if (p == 0) ATK_HIST(true, true);
+            if (first) ATK_HIST(true, true);
             else ATK_HIST(false, true);
         } else {
-            if (p == 0) {
+            if (first) {
                 ATK_HIST(true, false);
                 hipLaunchKernelGGL(ex_decide_kernel<true>, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p], last,
                                    fcap, (uint32_t)k);
@@ -749,14 +795,30 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
             }
         }
 #undef ATK_HIST
-        if (p == 0 && filter) {
-            u64 *fbuf = sel + m * k;
-            hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, fbuf,
-                               (int64_t)kFilterCap);
-            const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
-            hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st,
-                               (int)k, idx_bits, out_vals, out_idx);
-        }
+    };
+    auto copy_out = [&]() {  // rows in mode 1: everything at or above their threshold so far, selected in LDS
+        u64 *fbuf = sel + m * k;
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, fbuf,
+                           (int64_t)kFilterCap);
+        const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
+        hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st, (int)k,
+                           idx_bits, out_vals, out_idx);
+    };
+    // Very small k on big inputs: the k-th largest of a sample (every 16th run of 2048 elements), to
+    // two digits, is a threshold that at least k elements of the row reach, and about 16 k of them on
+    // data without order along the row: one sweep copies them out, instead of one sweep to count the
+    // first digit and one to copy.  A row where more than kFilterCap reach it starts over below; the
+    // passes below then mostly find nothing to do, so they keep to one launch each.
+    const bool sample = pl.sample;
+    if (sample) {
+        pass(0, true, kSampledPass, kSampleChunk, kSampleStride, false);
+        pass(1, false, kSampledLast, kSampleChunk, kSampleStride, false);
+        copy_out();
+    }
+    for (int p = 0; p < kExPasses; ++p) {
+        const bool filter_now = p == 0 && pl.filter && !sample;
+        pass(p, p == 0 && !sample, filter_now ? (uint32_t)kFilterCap : 0u, kExChunk, 1, sample);
+        if (filter_now) copy_out();
     }
     if (k * kExChunk / n <= 1536)  // expected survivors per chunk
         hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k);

@@ -396,6 +396,30 @@ def test_exact_small_rows(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_sampled_threshold(dtype, monkeypatch):
+    """Very small k on big inputs: the threshold is first guessed from a sample of the row (every 16th
+    run of 2048 elements) and everything that reaches it is copied out in one sweep.  Rows where too
+    much reaches it (ties, few levels, an ascending row whose sample misses the large values) start
+    over digit by digit; finished and restarted rows share one call.  XS=1 takes that path on inputs
+    below the size from which the library would choose it."""
+    monkeypatch.setenv("ATK_PLAN", "XS=1")
+    n = (1 << 19) + 333
+    for k in (1, 64, 128):
+        run_exact(workloads.normal_rows(3, n, seed=600 + k, dtype=dtype), k)
+    run_exact(workloads.normal_rows(2, 1 << 20, seed=610, dtype=dtype), 100)
+    asc = torch.sort(workloads.normal_rows(1, n, seed=611, dtype="f32"), dim=1).values
+    desc = torch.flip(asc, dims=[1])
+    if dtype == "bf16":
+        asc, desc = asc.to(torch.bfloat16), desc.to(torch.bfloat16)
+    mixed = torch.cat([workloads.normal_rows(2, n, seed=612, dtype=dtype), asc, desc,
+                       workloads.few_levels(1, n, levels=2, seed=613, dtype=dtype),
+                       workloads.few_levels(1, n, levels=1, seed=614, dtype=dtype),
+                       workloads.special_values(1, n, seed=615, dtype=dtype)])
+    run_exact(mixed, 64)
+    run_exact(mixed, 128)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_exact_long_rows(dtype):
     """Rows that do not fit one workgroup: global radix select, then LDS or global ordering."""
     for m, n, k in [(3, 20000, 64), (2, 50000, 1), (2, 50000, 3000), (2, 100000, 5000), (1, 70001, 70001),
