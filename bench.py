@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also time every configuration of the paper's sweeps")
+    ap.add_argument("--probe-long", action="store_true",
+                    help="profiler run on the 128 x 2^20 rows (cfg4, k=64, k_b=1): 5 plain copies, 5 read-only kernels, "
+                         "20 approx_topk calls each at b=64 and b=1024; no timing")
     ap.add_argument("--probe", action="store_true",
                     help="short run for hardware-counter passes: 20 copy launches, 20 read-only launches and 20 "
                          "approx_topk launches per b, nothing else")
@@ -63,6 +66,27 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.probe_long:
+        n_long = 1 << 20
+        xl = workloads.normal_rows(M, n_long, seed=0).to(dev)
+        dst = torch.empty_like(xl)
+        sink = torch.zeros(65536 // 8, dtype=torch.int64, device=dev)
+        ov = torch.empty((M, K), dtype=torch.float32, device=dev)
+        oi = torch.empty((M, K), dtype=torch.int32, device=dev)
+        st = torch.cuda.current_stream().cuda_stream
+        for i in range(5):
+            lib.atk_copy(dst.data_ptr(), xl.data_ptr(), M * n_long * 4, st)
+        for i in range(5):
+            lib.atk_read_ceiling(xl.data_ptr(), M * n_long * 4, sink.data_ptr(), st)
+        for b in (64, 1024):
+            for i in range(20):
+                rc = lib.approx_topk(xl.data_ptr(), M, n_long, K, b, 1, atk.ATK_F32, ov.data_ptr(), oi.data_ptr(), st)
+                if rc != 0:
+                    raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "done", "copy_bytes": M * n_long * 4, "launches_each": 20, "b": [64, 1024]}))
+        return
 
     # ---- inputs resident in HBM before anything is timed
     ring = [workloads.normal_rows(M, N, seed=s).to(dev) for s in range(RING)]

@@ -165,8 +165,9 @@ int atk_advise(int64_t m, int64_t n, int64_t k, int dtype, double min_recall, in
  *
  * atk_read_ceiling: a read-only streaming kernel over `bytes` bytes (multiple of 16, 16-byte
  *   aligned) of device memory at x; every wave xors what it read into its own word of
- *   `sink`, a device buffer of ATK_CEILING_SINK_BYTES bytes.  It bounds from above what any
- *   single-pass kernel over x can reach.
+ *   `sink`, a device buffer of ATK_CEILING_SINK_BYTES bytes.  Contiguous slabs, eight 16-byte
+ *   loads per lane in flight, two workgroups of 256 lanes per CU (the fastest of the shapes
+ *   tried from 32 MB to 512 MB): the reference for what one pass over x costs on this machine.
  * atk_copy: a plain device-to-device copy kernel of `bytes` bytes (multiple of 16, both pointers
  *   16-byte aligned, buffers must not overlap).  Its read and write volumes are known exactly,
  *   which is what hardware traffic counters are scaled against.
