@@ -15,6 +15,8 @@
 #include <cstdlib>
 #include <cstring>
 
+#include <type_traits>
+
 #include "atk_common.h"
 #include "atk_select.h"
 
@@ -249,28 +251,43 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
         constexpr int SU = tail_split_batch(KB);
         const int ncols = c_hi - c_lo;
         const u64 *src = p.lists + (int64_t)r * p.S * p.b * p.k_b;
-        // lists of splits s_first, s_first + s_step, ... of column `col`, merged into acc
+        // The lists of NB consecutive splits from s0 on, merged into acc.  All NB loads are issued
+        // before the first merge; the k_b <= KB slots that exist are loaded, the rest stay empty.
+        // (Loads under a per-load condition would each sit in a branch of their own and wait for
+        // one another.)
+        auto batch = [&](auto nb_tag, int col, int s0, u64(&acc)[KB]) {
+            constexpr int NB = decltype(nb_tag)::value;
+            u64 th[NB][KB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u)
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    th[u][j] = __hip_atomic_load(&src[((int64_t)(s0 + u) * p.b + col) * p.k_b + (j < p.k_b ? j : p.k_b - 1)],
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    if (j >= p.k_b) th[u][j] = 0ull;
+                merge_topk<KB>(acc, th[u]);
+            }
+        };
+        // lists of the splits [s0, s0 + SU) for s0 = s_first, s_first + s_step, ... of column `col`, merged
+        // into acc; a batch cut short by the last split goes in pieces of 4, 2 and 1
         auto gather = [&](int col, int s_first, int s_step, u64(&acc)[KB]) {
-            for (int s0 = s_first; s0 < p.S; s0 += s_step) {
-                // every load of the batch is issued, at an address clamped into the lists, and the
-                // ones past the end are dropped afterwards: loads under a condition would each sit
-                // in a branch of their own and wait for one another
-                u64 th[SU][KB];
-#pragma unroll
-                for (int u = 0; u < SU; ++u) {
-                    const int su = s0 + u < p.S ? s0 + u : p.S - 1;
-#pragma unroll
-                    for (int j = 0; j < KB; ++j)
-                        th[u][j] = __hip_atomic_load(&src[((int64_t)su * p.b + col) * p.k_b + (j < p.k_b ? j : p.k_b - 1)],
-                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int s0 = s_first;
+            for (; s0 + SU <= p.S; s0 += s_step) batch(std::integral_constant<int, SU>(), col, s0, acc);
+            if (s0 < p.S) {  // s_step >= SU: at most one batch is cut short
+                const int rem = p.S - s0;
+                if (SU > 4 && (rem & 4)) {
+                    batch(std::integral_constant<int, 4>(), col, s0, acc);
+                    s0 += 4;
                 }
-#pragma unroll
-                for (int u = 0; u < SU; ++u) {
-#pragma unroll
-                    for (int j = 0; j < KB; ++j)
-                        if (s0 + u >= p.S || j >= p.k_b) th[u][j] = 0ull;
-                    merge_topk<KB>(acc, th[u]);
+                if (SU > 2 && (rem & 2)) {
+                    batch(std::integral_constant<int, 2>(), col, s0, acc);
+                    s0 += 2;
                 }
+                if (rem & 1) batch(std::integral_constant<int, 1>(), col, s0, acc);
             }
         };
         auto put = [&](int col, const u64(&acc)[KB]) {
