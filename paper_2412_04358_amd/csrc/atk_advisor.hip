@@ -58,7 +58,7 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     if (split || stage2) us += 2.0;
     if (stage2) us += 2.5 + 0.0015 * cand;
     double floor_us = 4.0;
-    if (split && !(stage2 && m >= 128)) floor_us = 7.5 + bytes / 16.0e6 + (stage2 ? 4.0 + 0.0015 * cand : 0.0);
+    if (split && !(stage2 && m >= 128)) floor_us = 6.5 + bytes / 12.0e6 + (stage2 ? 3.0 + 0.0015 * cand : 0.0);
     if (us < floor_us) us = floor_us;
     // few rows: many splits per row, merged by the workgroup that finishes the row
     if (split && splits > 2.0) us += 0.04 * splits * (stage2 ? std::max(1.0, cand / 256.0) : 1.0);
