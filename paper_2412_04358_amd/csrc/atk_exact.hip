@@ -33,9 +33,10 @@ constexpr int kPartTile = 4096;          // survivors per workgroup of the parti
 constexpr int kPartMaxBins = 2048;
 constexpr int kPartWaveMax = 512;        // largest bin that one wavefront orders on its own
 constexpr int kFilterMaxK = 1024;        // largest k that takes the copy-out path (its selection must fit 64 KB of LDS)
-constexpr int kSampleMaxK = 128;        // largest k whose threshold is first guessed from a sample of the row
+constexpr int kSampleMaxK = 512;        // largest k whose threshold is first guessed from a sample of the row
 constexpr int kSampleChunk = 2048;       // the sample: every 16th run of 2048 elements
-constexpr int kSampleStride = 16;
+constexpr int kSampleStride = 16;         // ... for k <= 128; every 8th up to 256, every 4th up to 512: about 2048 elements reach the guess
+inline int sample_stride(int64_t k) { return k <= 128 ? kSampleStride : (k <= 256 ? kSampleStride / 2 : kSampleStride / 4); }
 constexpr int64_t kSampleMinBytes = 128ll << 20;  // smaller inputs are not worth the extra launches
 constexpr uint32_t kSampledPass = 0xfffffffeu, kSampledLast = 0xffffffffu;  // in place of a copy-out limit: see decide_row()
 constexpr int kFilterCap = 4096;         // elements at or above the first digit's bucket that one workgroup selects from in LDS
@@ -811,8 +812,8 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     // passes below then mostly find nothing to do, so they keep to one launch each.
     const bool sample = pl.sample;
     if (sample) {
-        pass(0, true, kSampledPass, kSampleChunk, kSampleStride, false);
-        pass(1, false, kSampledLast, kSampleChunk, kSampleStride, false);
+        pass(0, true, kSampledPass, kSampleChunk, sample_stride(k), false);
+        pass(1, false, kSampledLast, kSampleChunk, sample_stride(k), false);
         copy_out();
     }
     for (int p = 0; p < kExPasses; ++p) {

@@ -417,6 +417,8 @@ def test_exact_sampled_threshold(dtype, monkeypatch):
                        workloads.special_values(1, n, seed=615, dtype=dtype)])
     run_exact(mixed, 64)
     run_exact(mixed, 128)
+    run_exact(mixed, 200)  # every 8th run of 2048 elements sampled
+    run_exact(mixed, 512)  # every 4th
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
