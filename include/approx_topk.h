@@ -127,7 +127,7 @@ int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype);
  * buf (NUL-terminated, truncated to buflen).  Host only; used by tests and the benchmark log.
  * The plan can be overridden for tuning and tests with the environment variable ATK_PLAN, a comma
  * separated list of: T=<threads per workgroup: 64..1024>, S=<workgroups a row is split over>,
- * V=<columns per lane: 1, 2, 4, 8>, P=<lanes of a workgroup sharing a column group: 1, 2, 4>,
+ * V=<columns per lane: 1, 2, 4, 8>, P=<lanes of a workgroup sharing a column group: a power of two up to 64>,
  * PK=0 (bf16: no packed queue words), XS=0 / XS=1 (exact_topk with k <= 512: never / also on small
  * inputs guess the threshold from a sample of the row first).  Values the kernels cannot take are
  * ignored or clamped; results never depend on the plan.

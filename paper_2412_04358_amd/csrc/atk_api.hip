@@ -158,14 +158,23 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int p_want = 1;
     if (p.KB >= 8 && p.G >= T && !T_forced)
         while (p_want < 4 && m * p.G * p_want < 64 * 4 * (int64_t)kNumCU && p.L >= 4 * p_want * 2) p_want <<= 1;
+    bool P_forced = false;
     {
         const char *e = getenv("ATK_PLAN");
         const char *q = e ? strstr(e, "P=") : nullptr;
-        if (q && (q == e || q[-1] == ',') && (atoi(q + 2) == 1 || atoi(q + 2) == 2 || atoi(q + 2) == 4)) p_want = atoi(q + 2);
+        if (q && (q == e || q[-1] == ',')) {
+            const int v = atoi(q + 2);
+            if (v >= 1 && v <= 64 && (v & (v - 1)) == 0) {
+                p_want = v;
+                P_forced = true;
+            }
+        }
     }
 
+    // column groups side by side in a workgroup, row phases, LDS areas: for p_want lanes per column group
     int64_t lds = 0;
-    for (;;) {
+    auto layout = [&](int p_want) {
+      for (;;) {
         p.Gw = (int)((p.G < T / p_want) ? p.G : T / p_want);
         p.P = T / p.Gw;
         if (p.P > p.L) p.P = (int)p.L;
@@ -191,13 +200,17 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         }
         if (lds <= kLdsBudget || T <= kWave) break;
         T >>= 1;
-    }
+      }
+      p.lds_bytes = (int)lds;
+      T = p.T;
+      p.colblocks = (int)ceil_div(p.G, p.Gw);
+    };
+    layout(p_want);
     if (p.stage2 && b * k_b > kStage2MaxCand) return ATK_ERR_UNSUPPORTED;
     if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
-    p.lds_bytes = (int)lds;
-    T = p.T;
-    p.colblocks = (int)ceil_div(p.G, p.Gw);
 
+    // row splits for the layout just chosen
+    auto row_splits = [&]() -> int64_t {
     int64_t base = m * p.colblocks;
     int64_t S = want_threads / (base * (lanes_per_wg ? lanes_per_wg : T));
     int64_t s_rows = p.L / ((int64_t)p.P * 4);       // every lane keeps at least 4 loads
@@ -221,6 +234,34 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
             return ceil_div(tail_cols, T / tpc) * ceil_div(s, tpc * tail_split_batch(p.KB));
         };
         while (S > 1 && batches(S) > 4) S = (S + 1) / 2;
+    }
+    return S;
+    };
+    int64_t S = row_splits();
+    // Without Stage 2 nothing ties the columns of a row together, and a workgroup that owns whole
+    // buckets needs no hand-over at all: as long as rows would be split, and a workgroup's piece of
+    // a matrix row stays 128 bytes or more, halve the workgroup's column groups instead (measured on
+    // 128 x 65536 f32, b = 64: 9.3 -> 8.2 us; one row of 2^20: 10.8 -> 6.6 us).
+    // Only for rows that start on 128-byte lines: pieces that straddle lines are read twice, once by each
+    // of the two workgroups (n = 100003: 15.2 -> 17.5 us).
+    if (p.KB == 1 && !p.stage2 && p.P > 1 && !P_forced && !S_forced && (n * es) % 128 == 0) {
+        int gw = p.Gw;
+        int64_t s = S;
+        while (s >= 2 && (gw & 1) == 0 && (int64_t)(gw / 2) * p.V * es >= 128 && p.G % (gw / 2) == 0) {
+            gw >>= 1;
+            s >>= 1;
+        }
+        if (gw != p.Gw) {
+            // f32: the narrower workgroup also does better with four wavefronts than with eight (few rows of
+            // 65536: 7.3 -> 6.0 us at m = 32; level at m = 128); it still counts as 512 lanes for the splits
+            if (dtype == ATK_F32 && T == 512 && !T_forced) {
+                T = 256;
+                lanes_per_wg = 512;
+            }
+            layout(T / gw);
+            if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
+            S = row_splits();
+        }
     }
     if (S_forced) S = S_forced;
     if (S > p.L / p.P) S = p.L / p.P;

@@ -194,6 +194,37 @@ def test_forced_plans(plan, monkeypatch):
             run_case(x, k, b, k_b, tag=plan)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_column_split_plans(dtype):
+    """k_b = 1 without Stage 2 on rows that start on 128-byte lines: the workgroups of a row take 128-byte
+    pieces of the matrix rows - whole buckets each, no hand-over - alone (enough rows) or with row splits
+    on top (few rows); ragged last matrix rows, ties and special values included.  Also with P forced."""
+    es = 4 if dtype == "f32" else 2
+    dt = atk.ATK_F32 if dtype == "f32" else atk.ATK_BF16
+    cases = [(128, 65536, 64, 64, 1), (128, 65536, 128, 128, 1), (128, 65536, 512, 512, 1), (5, 1000000, 64, 64, 1),
+             (3, 65600, 128, 128, 1), (33, 16384, 96, 96, 1), (1, 1 << 20, 64, 64, 1), (8, 1 << 18, 256, 256, 1)]
+    split = 0
+    for i, (m, n, k, b, k_b) in enumerate(cases):
+        assert (n * es) % 128 == 0
+        plan = atk.plan_describe(m, n, k, b, k_b, dt)
+        split += " colblocks=1 " not in plan and " direct=0" in plan
+        rows = [0, 1, 63, 64, 127] if m == 128 else None
+        run_case(workloads.normal_rows(m, n, seed=700 + i, dtype=dtype), k, b, k_b, rows=rows, tag="colsplit")
+    assert split >= 4  # the plans this test is about are the ones the library picks
+    run_case(workloads.few_levels(6, 65536, levels=3, seed=720, dtype=dtype), 64, 64, 1, tag="colsplit ties")
+    run_case(workloads.special_values(6, 65536, seed=721, dtype=dtype), 128, 128, 1, tag="colsplit specials")
+
+
+@pytest.mark.parametrize("plan", ["P=8", "P=16,T=256", "P=32,T=512,S=3", "P=64,T=512", "P=64,T=256,S=2"])
+def test_forced_column_blocks(plan, monkeypatch):
+    """Narrow column blocks forced on shapes with and without Stage 2, several slots per bucket, ragged rows."""
+    monkeypatch.setenv("ATK_PLAN", plan)
+    for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (3, 32768, 128, 64, 2),
+                                           (2, 32768, 256, 128, 4), (3, 32771, 64, 64, 1), (2, 32776, 128, 128, 1)]):
+        for dtype in ["f32", "bf16"]:
+            run_case(workloads.normal_rows(m, n, seed=740 + i, dtype=dtype), k, b, k_b, tag=plan)
+
+
 @pytest.mark.parametrize("lanes", ["V=1", "V=2", "V=4", "V=8"])
 def test_forced_lane_widths(lanes, monkeypatch):
     """Every compiled (type, columns per lane, slots) instance gives the same results."""

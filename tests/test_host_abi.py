@@ -99,13 +99,21 @@ def test_plan_shapes(lib):
     # every lane owns whole buckets: straight from registers, one workgroup column block per 1024 columns
     p = parse_plan(atk.plan_describe(128, 65536, 16384, 16384, 1))
     assert p["direct"] == 1 and p["P"] == 1 and p["S"] == 1 and p["colblocks"] == 16 and p["stage2"] == 0
-    # few buckets: lanes share columns (P > 1, merged inside the wavefront) and rows are split
-    # over workgroups, merged via scratch
+    # few buckets: lanes share columns (P > 1, merged inside the wavefront).  Without Stage 2 the
+    # workgroups of a row take 128-byte pieces of the matrix rows (whole buckets each) rather than
+    # splitting the rows, so no scratch
     p = parse_plan(atk.plan_describe(128, 65536, 64, 64, 1))
-    assert p["V"] == 4 and p["Gw"] == 16 and p["P"] * p["Gw"] == p["T"] and p["wave_merge"] == 1
-    assert p["S"] > 1 and p["scratch"] == 1 and p["direct"] == 0 and p["nparts"] == p["T"] // 64
+    assert p["V"] == 4 and p["Gw"] == 8 and p["colblocks"] == 2 and p["P"] * p["Gw"] == p["T"] and p["wave_merge"] == 1
+    assert p["S"] == 1 and p["scratch"] == 0 and p["direct"] == 0 and p["nparts"] == p["T"] // 64
+    assert p["grid"] == 256
+    # fewer rows than that fills the chip with: rows are split on top, merged via scratch
+    p = parse_plan(atk.plan_describe(32, 65536, 64, 64, 1))
+    assert p["Gw"] == 8 and p["colblocks"] == 2 and p["S"] > 1 and p["scratch"] == 1
     assert p["S"] * p["rows_per_split"] >= 1024 and (p["S"] - 1) * p["rows_per_split"] < 1024
     assert p["rows_per_split"] % p["P"] == 0
+    # with Stage 2 one workgroup must see every candidate of the row: the columns stay together
+    p = parse_plan(atk.plan_describe(32, 65536, 64, 128, 1))
+    assert p["Gw"] == 32 and p["colblocks"] == 1 and p["S"] > 1 and p["scratch"] == 1
     # Stage 2 fused
     p = parse_plan(atk.plan_describe(128, 65536, 64, 1024, 1))
     assert p["stage2"] == 1 and p["lds"] >= (1024 + 64) * 8
@@ -203,8 +211,9 @@ def test_plan_override_env(lib, monkeypatch):
 
 def test_workspace_bytes(lib):
     assert lib.atk_workspace_bytes(128, 65536, 16384, 16384, 1, 0) == 0
-    p = parse_plan(atk.plan_describe(128, 65536, 64, 64, 1))
-    assert lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0) == p["scratch_bytes"] > 0
+    assert lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0) == 0  # whole buckets per workgroup: no hand-over
+    p = parse_plan(atk.plan_describe(32, 65536, 64, 64, 1))
+    assert lib.atk_workspace_bytes(32, 65536, 64, 64, 1, 0) == p["scratch_bytes"] > 0
     assert lib.atk_workspace_bytes(128, 65536, 64, 32, 1, 0) == PARAMS
     assert lib.atk_stage2_max_candidates() >= 1024
     # more candidates than one workgroup holds: Stage 1 writes them to scratch (values + indices) for the second step
