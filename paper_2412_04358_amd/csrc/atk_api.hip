@@ -244,7 +244,12 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // 128 x 65536 f32, b = 64: 9.3 -> 8.2 us; one row of 2^20: 10.8 -> 6.6 us).
     // Only for rows that start on 128-byte lines: pieces that straddle lines are read twice, once by each
     // of the two workgroups (n = 100003: 15.2 -> 17.5 us).
-    if (p.KB == 1 && !p.stage2 && p.P > 1 && !P_forced && !S_forced && (n * es) % 128 == 0) {
+    // Queues of two slots take it the same way (128 x 65536, b = 128, k_b = 2: 11.8 -> 9.3 us); with four
+    // slots the lanes that the row splits would have added are worth more as soon as rows get longer
+    // (2^18: 32.6 us with the splits, 38.9 without; 2^20: 100 against 119), so only up to 256 KB per row
+    // (128 x 65536, b = 256, k_b = 4: 15.8 -> 12.1 us).
+    if ((p.KB <= 2 || (p.KB == 4 && n * es <= (256 << 10))) && !p.stage2 && p.P > 1 && !P_forced && !S_forced &&
+        (n * es) % 128 == 0) {
         int gw = p.Gw;
         int64_t s = S;
         while (s >= 2 && (gw & 1) == 0 && (int64_t)(gw / 2) * p.V * es >= 128 && p.G % (gw / 2) == 0) {
