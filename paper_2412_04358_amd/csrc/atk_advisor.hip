@@ -52,6 +52,15 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     const double groups = (double)b / (double)stage1_pick_v(dtype, KB, 0, b);
     double splits = 256.0 / ((double)m * std::max(1.0, groups / 64.0));
     splits = std::min(splits, std::min((double)n / 8192.0, (double)(n / b) / 4.0));
+    // without Stage 2 (and with small queues) the workgroups of a row first share out its columns, in
+    // 128-byte pieces of the matrix rows, which costs no hand-over
+    if (!stage2 && KB <= 2 && ((double)n * es) == std::floor((double)n * es / 128.0) * 128.0) {
+        double pieces = (double)b * es / 128.0;
+        while (pieces >= 2.0 && splits >= 2.0) {
+            pieces /= 2.0;
+            splits /= 2.0;
+        }
+    }
     if (stage2 && splits > 16.0) splits = 16.0;
     if (splits > 128.0) splits = 128.0;
     const bool split = splits >= 2.0;

@@ -440,9 +440,23 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
                 for (int u = 0; u < U; ++u) ATK_FEED_VEC(v[u], t + u * step);
             }
         }
-        for (; t < t1; t += step) {
-            RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)t * row_bytes);
-            ATK_FEED_VEC(v, t);
+        if (t < t1) {
+            // Fewer than U rows are left: they go in pieces of U/2, U/4, ... 1 rows, each piece's loads
+            // issued together.  One row at a time, every load would wait out a full memory latency, which
+            // on rows of a few batches per lane is most of the kernel (n = 128256 against 131072: +3 us).
+            const int nr = (t1 - t + step - 1) / step;
+#define ATK_PIECE(NP)                                                                                          \
+    if (NP < U && (nr & NP)) {                                                                                 \
+        RowVec<ELT, V> v[NP];                                                                                  \
+        _Pragma("unroll") for (int u = 0; u < NP; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes); \
+        _Pragma("unroll") for (int u = 0; u < NP; ++u) ATK_FEED_VEC(v[u], t + u * step);                       \
+        t += NP * step;                                                                                        \
+    }
+            ATK_PIECE(8)
+            ATK_PIECE(4)
+            ATK_PIECE(2)
+            ATK_PIECE(1)
+#undef ATK_PIECE
         }
         // The (virtual) row does not end on a matrix row: the last matrix row holds only its
         // first `remr` columns (the short buckets of Figure 2).  It has the highest indices, so
