@@ -656,8 +656,13 @@ __global__ void __launch_bounds__(MAXT) contig_kernel(S1Params p) {
                 bj[u] = ok ? jj : -1;
                 r0[u] = a0;
                 has[u] = ok && (int64_t)q * V < a1 - a0;
-                if (has[u]) v[u] = load_vec<ELT, V>((const unsigned char *)p.x + ((int64_t)r * p.n + a0 + (int64_t)q * V) * ES);
             }
+            // all loads of the batch are issued together; a lane without an element of its own re-reads the
+            // start of the row and drops it (a load under a condition would wait for the one before it)
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                v[u] = load_vec<ELT, V>((const unsigned char *)p.x +
+                                        ((int64_t)r * p.n + (has[u] ? r0[u] + (int64_t)q * V : 0)) * ES);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float val[KB];
@@ -744,9 +749,20 @@ __global__ void __launch_bounds__(MAXT) contig_kernel(S1Params p) {
 #pragma unroll
             for (int u = 0; u < U; ++u) feed(v[u], c + u * p.Gs);
         }
-        for (; c < c1; c += p.Gs) {
-            RowVec<ELT, V> v = load_vec<ELT, V>(base + (int64_t)c * (V * ES));
-            feed(v, c);
+        if (c < c1) {  // fewer than U loads left: in pieces of U/2 ... 1, each piece's loads issued together
+            const int nr = (c1 - c + p.Gs - 1) >> p.gs_shift;
+#define ATK_PIECE(NP)                                                                                                  \
+    if (NP < U && (nr & NP)) {                                                                                         \
+        RowVec<ELT, V> v[NP];                                                                                          \
+        _Pragma("unroll") for (int u = 0; u < NP; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(c + u * p.Gs) * (V * ES)); \
+        _Pragma("unroll") for (int u = 0; u < NP; ++u) feed(v[u], c + u * p.Gs);                                       \
+        c += NP * p.Gs;                                                                                                \
+    }
+            ATK_PIECE(8)
+            ATK_PIECE(4)
+            ATK_PIECE(2)
+            ATK_PIECE(1)
+#undef ATK_PIECE
         }
     }
     u64 comp[KB];
