@@ -191,9 +191,14 @@ __device__ __forceinline__ void decide_row(ExRowState *st, uint32_t *gh, int r, 
     const bool owner = tid < 256;
     uint32_t hb[8], s = 0;
     const int base = owner ? kExBins - 8 - 8 * tid : 0;
+    // one condition around the eight loads, so that they are issued together (a condition per load
+    // puts each in a branch of its own, where it waits for the one before it)
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-        hb[q] = owner ? __hip_atomic_load(&gh[base + q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+    for (int q = 0; q < 8; ++q) hb[q] = 0u;
+    if (owner) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) hb[q] = __hip_atomic_load(&gh[base + q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
         if (hb[q]) __hip_atomic_store(&gh[base + q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -443,10 +448,17 @@ __global__ void __launch_bounds__(256) part_hist_kernel(const u64 *sel, const Ex
     __syncthreads();
     const int64_t e0 = (int64_t)blockIdx.x * kPartTile;
     const u64 *row = sel + (int64_t)r * k;
+    // the tile's loads are all issued before the first is used (a load under `if (i < k)` would sit in a
+    // branch of its own and wait for the one before it): past the end the last element is re-read and dropped
+    u64 c[kPartTile / 256];
+#pragma unroll
     for (int j = 0; j < kPartTile / 256; ++j) {
         const int64_t i = e0 + j * 256 + tid;
-        if (i < k) atomicAdd(&lh[(uint32_t)((row[i] - thr) >> shift)], 1u);
+        c[j] = row[i < k ? i : k - 1];
     }
+#pragma unroll
+    for (int j = 0; j < kPartTile / 256; ++j)
+        if (e0 + j * 256 + tid < k) atomicAdd(&lh[(uint32_t)((c[j] - thr) >> shift)], 1u);
     __syncthreads();
     uint32_t *gc = counts + (int64_t)r * nb;
     for (int i = tid; i < nb; i += 256) {
@@ -510,9 +522,13 @@ __global__ void __launch_bounds__(256) part_scatter_kernel(const u64 *sel, u64 *
     u64 c[kPartTile / 256];
     uint32_t bin[kPartTile / 256];
 #pragma unroll
-    for (int j = 0; j < kPartTile / 256; ++j) {
+    for (int j = 0; j < kPartTile / 256; ++j) {  // all loads first, as in part_hist_kernel
         const int64_t i = e0 + j * 256 + tid;
-        c[j] = (i < k) ? row[i] : 0ull;
+        c[j] = row[i < k ? i : k - 1];
+    }
+#pragma unroll
+    for (int j = 0; j < kPartTile / 256; ++j) {
+        if (e0 + j * 256 + tid >= k) c[j] = 0ull;
         bin[j] = c[j] ? (uint32_t)((c[j] - thr) >> shift) : 0u;
         if (c[j]) atomicAdd(&lh[bin[j]], 1u);
     }
