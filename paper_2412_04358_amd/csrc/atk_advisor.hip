@@ -67,6 +67,8 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     if (split || stage2) us += 2.0;
     if (stage2) us += 2.5 + 0.0015 * cand;
     double floor_us = 4.0;
+    // lanes share column groups and merge inside the workgroup when the rows alone cannot fill the chip
+    if ((double)m * groups < 16384.0) floor_us = 6.0 + bytes / 16.0e6;
     if (split && !(stage2 && m >= 128)) floor_us = 6.5 + bytes / 12.0e6 + (stage2 ? 3.0 + 0.0015 * cand : 0.0);
     if (us < floor_us) us = floor_us;
     // few rows: many splits per row, merged by the workgroup that finishes the row
