@@ -213,7 +213,9 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     auto row_splits = [&]() -> int64_t {
     int64_t base = m * p.colblocks;
     int64_t S = want_threads / (base * (lanes_per_wg ? lanes_per_wg : T));
-    int64_t s_rows = p.L / ((int64_t)p.P * 4);       // every lane keeps at least 4 loads
+    // every lane keeps at least 4 loads; a running maximum at least one full batch of 8 (one row of 2^20,
+    // b = 64: 8.5 us with 128 splits of 4 loads per lane, 6.6 us with 64 of 8)
+    int64_t s_rows = p.L / ((int64_t)p.P * (p.KB == 1 && !p.stage2 ? 8 : 4));  // (with Stage 2 more, shorter splits still measured faster)
     int64_t s_traffic = (p.L * es) / (32 * k_b);     // partial lists (written + read back) below half the bytes streamed
     int64_t s_fill = ceil_div(kNumCU, base);         // splits that give every CU a workgroup
     if (S > s_traffic) S = s_traffic > s_fill ? s_traffic : (S < s_fill ? S : s_fill);  // filling the chip comes first
