@@ -108,8 +108,9 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int64_t want_threads = n_vec / 16;
     if (want_threads < 512 * (int64_t)kNumCU) want_threads = 512 * (int64_t)kNumCU;
     if (want_threads > 2048 * (int64_t)kNumCU) want_threads = 2048 * (int64_t)kNumCU;
-    // with queues, a lane that sees more rows inserts less often: half as many lanes measured faster
-    if (p.KB >= 4 && want_threads > 1024 * (int64_t)kNumCU) want_threads = 1024 * (int64_t)kNumCU;
+    // with queues, a lane that sees more rows inserts less often, and every split less is a list less
+    // through memory: half as many lanes measured faster (k_b = 2 on 128 x 2653751 bf16: 153 -> 136 us)
+    if (p.KB >= 2 && want_threads > 1024 * (int64_t)kNumCU) want_threads = 1024 * (int64_t)kNumCU;
     // A running maximum costs a lane next to nothing, so k_b = 1 is bound by the memory system alone,
     // and that likes few, long streams: about one workgroup per CU measured fastest on long rows
     // (128 x 2^20, b = 64: 85.6 us with 1024 workgroups of 512 lanes, 80.1 with 256, 75.5 with 256
