@@ -162,7 +162,7 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
 // sel has room for pow2_ceil(k) words; rk: LDS, kRankMax zeroed words (used when k <= kRankMax).
 // All threads of the workgroup call it, after a barrier that made sel (and the zeroed rk) visible.
 template <int ELT>
-__device__ void order_write(u64 *sel, int k, uint32_t *rk, void *out_vals, int32_t *out_idx, int64_t row_out) {
+__device__ __forceinline__ void order_write(u64 *sel, int k, uint32_t *rk, void *out_vals, int32_t *out_idx, int64_t row_out) {
     const int tid = threadIdx.x, T = blockDim.x;
     const int kp = pow2_ceil_dev(k);
     if (k <= kRankMax) {
@@ -217,7 +217,7 @@ __device__ void order_write(u64 *sel, int k, uint32_t *rk, void *out_vals, int32
 // (LDS), written largest first to row `row_out`.  Needs (pow2_ceil(k) + kSelWredWords) * 8 +
 // kSelU32Words * 4 bytes of LDS behind cand.
 template <int ELT>
-__device__ void select_radix_write(u64 *cand, int count, int k, void *out_vals, int32_t *out_idx, int64_t row_out) {
+__device__ __forceinline__ void select_radix_write(u64 *cand, int count, int k, void *out_vals, int32_t *out_idx, int64_t row_out) {
     const int tid = threadIdx.x, T = blockDim.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6, n_waves = T >> 6;
     const int kp = pow2_ceil_dev(k);
@@ -343,7 +343,7 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
                                                    int32_t *out_idx, int64_t row_out);
 
 template <int ELT>
-__device__ void select_write(u64 *cand, int count, int k, int idx_bits, void *out_vals, int32_t *out_idx,
+__device__ __forceinline__ void select_write(u64 *cand, int count, int k, int idx_bits, void *out_vals, int32_t *out_idx,
                              int64_t row_out) {
     const int T = blockDim.x;
     if (count > kBkSlots * T || T > kBkBins) {
@@ -376,7 +376,8 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
     const int lane = tid & (kWave - 1), n_waves = T >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // LDS behind the candidates (16-byte aligned pieces): counts, "above" table, small words
-    uint32_t *cnt = (uint32_t *)(((uintptr_t)(cand + count) + 15) & ~(uintptr_t)15);  // [2048]
+    // (cand is 16-byte aligned; plain pointer arithmetic, so that the compiler still knows this is LDS)
+    uint32_t *cnt = (uint32_t *)(cand + ((count + 1) & ~1));  // [2048], 16-byte aligned
     uint32_t *abv = cnt + kBkBins;   // abv[b + 4] = elements in bins above b, for b = -1 .. 2047
     uint32_t *misc = abv + kBkBins + 8;  // [0] overflow flag, [1] min key, [2] max key, [3] OR of keys, [8..24) wavefront totals
 
