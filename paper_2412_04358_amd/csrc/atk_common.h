@@ -54,6 +54,7 @@ inline int stage1_pick_v(int dtype, int KB, int want, int64_t b) {
 }
 constexpr int kStage2MaxCand = 4096;      // composites held in LDS by the fused Stage 2
 constexpr int kLdsBudget = 64 * 1024;     // static+dynamic LDS per workgroup we allow ourselves
+constexpr int kLdsBudgetWholeRow = 160 * 1024;  // ... for exact_topk's one-workgroup-per-row kernel: all of a CU's LDS (gfx950)
 constexpr int kNumCU = 256;               // MI355X
 constexpr int kTicketStride = 32;          // words between row tickets: one 128-byte line each, so that
                                           // atomics of different rows do not queue up on one line

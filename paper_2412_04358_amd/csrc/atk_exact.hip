@@ -77,7 +77,10 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.idx_n = n;
     if (m >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
     const int64_t lds = select_lds_bytes(n, (int)pow2_ceil64(k < (1 << 20) ? k : (1 << 20)));
-    p.single_wg = lds <= kLdsBudget;
+    // One workgroup per row while the row fits 64 KB of LDS; up to all 160 KB of a CU (about 18000
+    // elements) when there is at most one row per CU: one launch instead of ten (128 x 8192: 41 -> 24 us).
+    // With more rows the sweeps of the long-row path use the chip better (2048 x 8192: 110 against 270 us).
+    p.single_wg = lds <= kLdsBudget || (lds <= kLdsBudgetWholeRow && m <= kNumCU);
     if (p.single_wg) {
         p.lds_bytes = (int)lds;
         *pl = p;
@@ -774,6 +777,12 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     if (pl.single_wg) {
         int small_bits = 1;
         while (((int64_t)1 << small_bits) < pl.idx_n) ++small_bits;
+        if (pl.lds_bytes > 64 * 1024) {
+            // more dynamic LDS than a launch may ask for by default: the kernel is told so
+            hipError_t ea = hipFuncSetAttribute((const void *)exact_small_kernel<ELT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                kLdsBudgetWholeRow);
+            if (ea != hipSuccess) return ea;
+        }
         hipLaunchKernelGGL(exact_small_kernel<ELT>, dim3((unsigned)m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x, xi, (int)n,
                            (int)k, small_bits, out_vals, out_idx);
         return hipGetLastError();

@@ -420,7 +420,9 @@ def test_repeatable():
 # ------------------------------------------------------------------------------- exact_topk
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_exact_small_rows(dtype):
-    for m, n, k in [(4, 4096, 64), (3, 1000, 1), (3, 1000, 1000), (2, 3000, 777), (5, 2048, 2048), (7, 33, 5)]:
+    # (few rows of up to about 18000 elements take one workgroup each, with up to 160 KB of LDS)
+    for m, n, k in [(4, 4096, 64), (3, 1000, 1), (3, 1000, 1000), (2, 3000, 777), (5, 2048, 2048), (7, 33, 5),
+                    (3, 8192, 512), (2, 12000, 12000), (3, 18000, 64), (300, 16384, 100)]:
         run_exact(workloads.normal_rows(m, n, seed=300 + n, dtype=dtype), k)
         run_exact(workloads.few_levels(m, n, levels=2, seed=301 + n, dtype=dtype), k)
         run_exact(workloads.special_values(m, n, seed=302 + n, dtype=dtype), k)
@@ -485,7 +487,7 @@ def test_exact_long_rows(dtype):
 
 def test_exact_many_long_rows():
     """More long rows than a grid dimension holds: they go through in blocks of rows."""
-    x = workloads.normal_rows(66000, 9000, seed=41)  # 9000 f32 per row do not fit one workgroup's LDS
+    x = workloads.normal_rows(66000, 9000, seed=41)  # 9000 f32 per row do not fit 64 KB of LDS
     run_exact(x, 10, rows=[0, 1, 65534, 65535, 65536, 65999])
 
 
