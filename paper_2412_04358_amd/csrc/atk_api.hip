@@ -146,7 +146,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     }
     // many column groups but few rows: smaller workgroups rather than row splits
     if (p.G > 256)
-        while (T > kWave && m * ceil_div(p.G, T) < (int64_t)kNumCU) T >>= 1;
+        while (T > kWave && m * ceil_div(p.G, T) < (int64_t)kNumCU) T = (int)(ceil_div(T / 2, kWave) * kWave);  // whole wavefronts (T may be 384)
     if (T_forced) { T = T_forced; lanes_per_wg = 0; }
     if (T > t_max) T = t_max;
 
@@ -200,7 +200,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
             lds = 16 + lds_xch;
         }
         if (lds <= kLdsBudget || T <= kWave) break;
-        T >>= 1;
+        T = (int)(ceil_div(T / 2, kWave) * kWave);
       }
       p.lds_bytes = (int)lds;
       T = p.T;

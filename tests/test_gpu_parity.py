@@ -136,6 +136,7 @@ SHAPES = [
     (4, 16384, 512, 64, 8),
     (4, 16384, 2048, 128, 16),
     (4, 16384, 100, 128, 16),
+    (5, 1677, 371, 371, 2),       # Stage 2 asks for 384 lanes, few rows ask for smaller workgroups: whole wavefronts
     (4, 16384, 16384, 16384, 1),  # bucket length 1: identity
     (4, 16384, 8192, 8192, 1),
     (4, 16384, 4096, 1024, 4),    # bucket length 16, keep 4

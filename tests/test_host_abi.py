@@ -134,7 +134,7 @@ def test_plan_shapes(lib):
     # the grid always covers every matrix row and column exactly once, LDS stays within 64 KB
     for (m, n, k, b, kb) in [(1, 4096, 64, 64, 1), (3, 12288, 96, 96, 1), (7, 1 << 20, 64, 8, 8),
                              (128, 1 << 20, 1 << 18, 1 << 15, 8), (5, 8192, 1, 1, 1), (4, 16384, 100, 128, 16),
-                             (1, 1 << 18, 64, 512, 1), (130, 4096, 64, 128, 1)]:
+                             (1, 1 << 18, 64, 512, 1), (130, 4096, 64, 128, 1), (5, 1677, 371, 371, 2), (3, 3000, 700, 350, 2)]:
         p = parse_plan(atk.plan_describe(m, n, k, b, kb))
         assert p["grid"] == m * p["S"] * p["colblocks"]
         assert p["colblocks"] * p["Gw"] * p["V"] >= b
