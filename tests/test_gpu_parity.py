@@ -266,6 +266,55 @@ def test_random_shapes(dtype):
         run_case(x, k, b, k_b, tag="random%d contiguous" % i, assignment=atk.ATK_CONTIGUOUS)
 
 
+def wide_cases(seed, count):
+    """Seeded cases over a wider range than random_cases: up to 300 rows, row lengths up to 300000 that are
+    multiples of 1, 8, 32, 64 or 256 elements, power-of-two and odd bucket counts, tie-heavy and special-valued inputs."""
+    rng = np.random.default_rng(seed)
+    lib = atk.load_library()
+    out = []
+    while len(out) < count:
+        m = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 130, 300]))
+        align = int(rng.choice([1, 8, 32, 64, 256]))
+        n = int(rng.choice([rng.integers(64, 2000), rng.integers(2000, 40000), rng.integers(40000, 300000)]))
+        n = max(align, n // align * align)
+        if m * n > 6_000_000:
+            m = max(1, 6_000_000 // n)
+        k_b = int(rng.choice([1, 1, 1, 1, 2, 2, 3, 4, 8, 16]))
+        if k_b > n:
+            continue
+        b_max = n // k_b
+        b = int(rng.choice([2 ** int(rng.integers(0, 13)), rng.integers(1, min(b_max, 64) + 1), rng.integers(1, b_max + 1),
+                            4 * int(rng.integers(1, 600))]))
+        b = max(1, min(b, b_max))
+        hi = b * k_b
+        if hi > 8192 and rng.random() < 0.7:
+            k = hi
+        else:
+            k = int(rng.choice([hi, rng.integers(k_b, hi + 1), max(k_b, hi // 2), max(k_b, hi // 16)]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        kind = int(rng.integers(0, 10))
+        if lib.atk_check_approx(m, n, k, b, k_b, atk.ATK_F32 if dtype == "f32" else atk.ATK_BF16) != 0:
+            continue
+        out.append((m, n, k, b, k_b, dtype, kind, int(rng.integers(1 << 30)), float(rng.random()), float(rng.random()),
+                    int(rng.integers(1, min(n, 5000) + 1))))
+    return out
+
+
+def test_wide_random_shapes():
+    for (m, n, k, b, k_b, dtype, kind, seed, r_contig, r_exact, k_exact) in wide_cases(20241128, 1000):
+        if kind == 0:
+            x = workloads.few_levels(m, n, levels=1 + seed % 4, seed=seed, dtype=dtype)
+        elif kind == 1:
+            x = workloads.special_values(m, n, seed=seed, dtype=dtype)
+        else:
+            x = workloads.normal_rows(m, n, seed=seed, dtype=dtype)
+        run_case(x, k, b, k_b, tag="wide")
+        if r_contig < 0.3:
+            run_case(x, k, b, k_b, tag="wide contiguous", assignment=atk.ATK_CONTIGUOUS)
+        if r_exact < 0.3:
+            run_exact(x, k_exact)
+
+
 def test_many_short_rows():
     """More rows than a grid dimension holds, each a few matrix rows long."""
     x = workloads.normal_rows(70000, 64, seed=9)
