@@ -254,10 +254,14 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if ((p.KB <= 2 || (p.KB == 4 && n * es <= (256 << 10))) && !p.stage2 && p.P > 1 && !P_forced && !S_forced &&
         (n * es) % 128 == 0) {
         int gw = p.Gw;
-        int64_t s = S;
-        while (s >= 2 && (gw & 1) == 0 && (int64_t)(gw / 2) * p.V * es >= 128 && p.G % (gw / 2) == 0) {
+        int64_t s = S, cb = p.colblocks;
+        // ... and as long as the launch has fewer workgroups than the chip has CUs (rows that allow no
+        // more splits: 64 x 128256 bf16, b = 256 came out with 128 workgroups)
+        while ((s >= 2 || m * cb * s < (int64_t)kNumCU) && (gw & 1) == 0 && (int64_t)(gw / 2) * p.V * es >= 128 &&
+               p.G % (gw / 2) == 0) {
             gw >>= 1;
-            s >>= 1;
+            cb <<= 1;
+            s = s >= 2 ? s >> 1 : 1;
         }
         if (gw != p.Gw) {
             // f32: the narrower workgroup also does better with four wavefronts than with eight (few rows of

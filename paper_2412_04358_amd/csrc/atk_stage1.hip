@@ -462,7 +462,23 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
             // Fewer than U rows are left: they go in pieces of U/2, U/4, ... 1 rows, each piece's loads
             // issued together.  One row at a time, every load would wait out a full memory latency, which
             // on rows of a few batches per lane is most of the kernel (n = 128256 against 131072: +3 us).
-            const int nr = (t1 - t + step - 1) / step;
+            int nr = (t1 - t + step - 1) / step;
+            if (KB == 1 && U >= 8 && nr > U / 2) {
+                // more than half a batch: a whole batch at once, the loads past the end re-reading row t
+                // (for a running maximum a row fed twice changes nothing) - one memory latency, not three
+                RowVec<ELT, V> v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int tu = t + u * step;
+                    v[u] = load_vec<ELT, V>(base + (int64_t)(tu < t1 ? tu : t) * row_bytes);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int tu = t + u * step;
+                    ATK_FEED_VEC(v[u], tu < t1 ? tu : t);
+                }
+                nr = 0;
+            }
 #define ATK_PIECE(NP)                                                                                          \
     if (NP < U && (nr & NP)) {                                                                                 \
         RowVec<ELT, V> v[NP];                                                                                  \
