@@ -778,10 +778,17 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         int small_bits = 1;
         while (((int64_t)1 << small_bits) < pl.idx_n) ++small_bits;
         if (pl.lds_bytes > 64 * 1024) {
-            // more dynamic LDS than a launch may ask for by default: the kernel is told so
-            hipError_t ea = hipFuncSetAttribute((const void *)exact_small_kernel<ELT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                kLdsBudgetWholeRow);
+            // more dynamic LDS than a launch may ask for by default: the kernel is told so, once per device
+            static bool told[64] = {};
+            int dev = 0;
+            hipError_t ea = hipGetDevice(&dev);
             if (ea != hipSuccess) return ea;
+            if (dev < 0 || dev >= 64 || !told[dev]) {
+                ea = hipFuncSetAttribute((const void *)exact_small_kernel<ELT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         kLdsBudgetWholeRow);
+                if (ea != hipSuccess) return ea;
+                if (dev >= 0 && dev < 64) told[dev] = true;
+            }
         }
         hipLaunchKernelGGL(exact_small_kernel<ELT>, dim3((unsigned)m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x, xi, (int)n,
                            (int)k, small_bits, out_vals, out_idx);
