@@ -765,9 +765,12 @@ __global__ void __launch_bounds__(256) ex_decode_kernel(const u64 *sorted, const
                                                         void *out_vals, int32_t *out_idx) {
     const int r = blockIdx.y;
     if (st[r].mode != 3u) return;
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t i = (int64_t)r * k + j;
-    if (j < k && i < total) write_composite<ELT>(sorted[i], out_vals, out_idx, i);
+    // a few workgroups per row stride over it: for the usual launch, in which no row is in this mode,
+    // thousands of workgroups that exit at once would cost ten times a small grid's launch
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < k; j += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = (int64_t)r * k + j;
+        if (i < total) write_composite<ELT>(sorted[i], out_vals, out_idx, i);
+    }
 }
 
 template <int ELT>
@@ -907,7 +910,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         cur ^= 1;
     }
     const int64_t total = m * k;
-    hipLaunchKernelGGL(ex_decode_kernel<ELT>, dim3((unsigned)ceil_div64(k, 256), (unsigned)m), dim3(256), 0, stream, bufs[cur],
+    hipLaunchKernelGGL(ex_decode_kernel<ELT>, dim3((unsigned)std::min<int64_t>(ceil_div64(k, 256), 32), (unsigned)m), dim3(256), 0, stream, bufs[cur],
                        st, k, total, out_vals, out_idx);
     return hipGetLastError();
 }
