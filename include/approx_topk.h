@@ -129,7 +129,8 @@ int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype);
  * separated list of: T=<threads per workgroup: 64..1024>, S=<workgroups a row is split over>,
  * V=<columns per lane: 1, 2, 4, 8>, P=<lanes of a workgroup sharing a column group: a power of two up to 64>,
  * PK=0 (bf16: no packed queue words), XS=0 / XS=1 (exact_topk with k <= 512: never / also on small
- * inputs guess the threshold from a sample of the row first).  Values the kernels cannot take are
+ * inputs guess the threshold from a sample of the row first), XC=<elements of a row per workgroup of
+ * exact_topk's sweeps: a power of two from 1024 to 16384>.  Values the kernels cannot take are
  * ignored or clamped; results never depend on the plan.
  */
 int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,

@@ -25,7 +25,9 @@ constexpr int kExBins = 2048;            // 11-bit digits
 constexpr int kExPasses = 6;             // 64 bits = 11+11+10 (value key) + 11+11+10 (index field)
 constexpr int kExShift[kExPasses] = {53, 42, 32, 21, 10, 0};
 constexpr int kExWidth[kExPasses] = {11, 11, 10, 11, 11, 10};
-constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps
+constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps (inputs that fill the chip with that)
+constexpr int kExChunkMin = 4096;        // ... down to this on smaller inputs, while a sweep stays within kExFusedMaxWgs workgroups
+constexpr int kExFusedMaxWgs = 1024;     // largest sweep whose last workgroup per row also decides the digit (see ex_hist_kernel)
 constexpr int kExRow = kExBins + kTicketStride;  // words per row of the global histograms: the bins, then the row's ticket
 constexpr int kSortTile = 2048;          // elements per workgroup of the global sort
 constexpr int kSortLdsMaxK = 4096;       // survivors ordered in LDS by one workgroup
@@ -69,6 +71,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.k = k;
     p.T = kMaxThreads;
     p.chunks = 1;
+    p.chunk_elems = kExChunk;
     p.scratch_bytes = 0;
     p.state_bytes = 0;
     p.lds_bytes = 0;
@@ -86,7 +89,16 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
         *pl = p;
         return ATK_OK;
     }
-    p.chunks = (int)ceil_div64(n, kExChunk);
+    // inputs that do not fill the chip with 16384-element chunks: smaller ones, as long as the sweep stays a launch
+    // whose last workgroup per row decides the digit (128 x 65536, k = 64: 55 -> 44 us; 1 x 2^20: 47 -> 34 us)
+    while (p.chunk_elems > kExChunkMin && m * ceil_div64(n, p.chunk_elems / 2) <= kExFusedMaxWgs) p.chunk_elems >>= 1;
+    if (const char *e = getenv("ATK_PLAN")) {  // "XC=<elements>": the sweep's chunk, a power of two from 1024 to 16384 (sweeps, tests)
+        if (const char *q = strstr(e, "XC=")) {
+            const int v = atoi(q + 3);
+            if (v >= 1024 && v <= kExChunk && (v & (v - 1)) == 0) p.chunk_elems = v;
+        }
+    }
+    p.chunks = (int)ceil_div64(n, p.chunk_elems);
     if (m > 65535) return ATK_ERR_UNSUPPORTED;  // rows are the grid's y dimension: exact_topk() passes blocks of rows
     // state pool: global histograms (left zero by every call)
     p.state_bytes = m * (int64_t)kExRow * 4;
@@ -306,7 +318,7 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
 // quarter of a chunk does.
 template <int ELT, bool FILTER, int kStash>
 __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st, u64 *sel,
-                                                                 int64_t k) {
+                                                                 int64_t k, int chunk_elems) {
     __shared__ u64 stash[kStash];
     __shared__ uint32_t wave_cnt[kMaxThreads / kWave];
     __shared__ uint32_t wave_base[kMaxThreads / kWave];
@@ -333,7 +345,7 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
             if (keep && at < (uint32_t)kStash) stash[at] = c;
             mine += cnt;
         }
-    });
+    }, chunk_elems);
     if (lane == 0) wave_cnt[wave] = mine;
     if (!FILTER) {  // the row's largest survivor, for the partition sort's bins
         u64 lo = ~0ull, hi = cmax_local;
@@ -364,7 +376,7 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
         if (keep && pos < (uint32_t)k) dst[pos] = c;
         cursor += (uint32_t)__popcll(mask);
-    });
+    }, chunk_elems);
 }
 
 // k <= kSortLdsMaxK: one workgroup per row orders the survivors in LDS and writes the outputs.
@@ -812,7 +824,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     auto pass = [&](int p, bool first, uint32_t fcap, int elems, int stride, bool fuse) {
         const int last = p == kExPasses - 1 ? 1 : 0;
         const dim3 grid((unsigned)ceil_div64(n, (int64_t)elems * stride), (unsigned)m);
-        const bool fused = fuse || (int64_t)grid.x * m <= 1024;
+        const bool fused = fuse || (int64_t)grid.x * m <= kExFusedMaxWgs;
 #define ATK_HIST(FIRST, FUSED)                                                                                             \
     hipLaunchKernelGGL((ex_hist_kernel<ELT, FIRST, FUSED>), grid, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist,        \
                        kExShift[p], kExWidth[p], last, fcap, (uint32_t)k, elems, stride)
@@ -835,7 +847,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     auto copy_out = [&]() {  // rows in mode 1: everything at or above their threshold so far, selected in LDS
         u64 *fbuf = sel + m * k;
         hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, fbuf,
-                           (int64_t)kFilterCap);
+                           (int64_t)kFilterCap, pl.chunk_elems);
         const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
         hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st, (int)k,
                            idx_bits, out_vals, out_idx);
@@ -853,13 +865,13 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     }
     for (int p = 0; p < kExPasses; ++p) {
         const bool filter_now = p == 0 && pl.filter && !sample;
-        pass(p, p == 0 && !sample, filter_now ? (uint32_t)kFilterCap : 0u, kExChunk, 1, sample);
+        pass(p, p == 0 && !sample, filter_now ? (uint32_t)kFilterCap : 0u, pl.chunk_elems, 1, sample);
         if (filter_now) copy_out();
     }
-    if (k * kExChunk / n <= 1536)  // expected survivors per chunk
-        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k);
+    if (k * pl.chunk_elems / n <= 1536)  // expected survivors per chunk
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k, pl.chunk_elems);
     else
-        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 6144>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k);
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 6144>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k, pl.chunk_elems);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 

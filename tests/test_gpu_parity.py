@@ -504,6 +504,20 @@ def test_exact_sampled_threshold(dtype, monkeypatch):
     run_exact(mixed, 512)  # every 4th
 
 
+@pytest.mark.parametrize("chunk", [1024, 4096, 8192, 16384])
+def test_exact_sweep_chunks(chunk, monkeypatch):
+    """The sweeps of the long-row path take 4096 to 16384 elements of a row per workgroup, by the size of
+    the input; XC=<elements> fixes it.  Every size gives the same results: rows with a ragged last chunk,
+    the copy-out path, the digit descent, and many survivors per chunk (the second sweep of the collect step)."""
+    monkeypatch.setenv("ATK_PLAN", "XC=%d" % chunk)
+    for dtype in ("f32", "bf16"):
+        run_exact(workloads.normal_rows(3, 70001, seed=700 + chunk % 7, dtype=dtype), 64)
+        run_exact(workloads.normal_rows(2, 50000, seed=701, dtype=dtype), 3000)
+        run_exact(workloads.normal_rows(2, 50000, seed=702, dtype=dtype), 30000)
+        run_exact(workloads.few_levels(2, 40000, levels=2, seed=703, dtype=dtype), 500)
+        run_exact(workloads.special_values(2, 40000, seed=704, dtype=dtype), 6000)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_exact_long_rows(dtype):
     """Rows that do not fit one workgroup: global radix select, then LDS or global ordering."""
