@@ -36,7 +36,7 @@ constexpr int kPartMaxBins = 2048;
 constexpr int kPartWaveMax = 512;        // largest bin that one wavefront orders on its own
 constexpr int kFilterMaxK = 1024;        // largest k that takes the copy-out path (its selection must fit 64 KB of LDS)
 constexpr int kSampleMaxK = 512;        // largest k whose threshold is first guessed from a sample of the row
-constexpr int kSampleChunk = 2048;       // the sample: every 16th run of 2048 elements
+constexpr int kSampleChunk = 4096;       // the sample: every 16th run of 4096 elements
 constexpr int kSampleStride = 16;         // ... for k <= 128; every 8th up to 256, every 4th up to 512: about 2048 elements reach the guess
 inline int sample_stride(int64_t k) { return k <= 128 ? kSampleStride : (k <= 256 ? kSampleStride / 2 : kSampleStride / 4); }
 constexpr int64_t kSampleMinBytes = 128ll << 20;  // smaller inputs are not worth the extra launches
@@ -155,22 +155,59 @@ __global__ void __launch_bounds__(kMaxThreads) exact_small_kernel(const void *x,
 }
 
 // ------------------------------------------------------------------------------------ long rows
-// Calls f(composite) for every element of this workgroup's chunk of row r, 4 loads per lane in flight.
+// Calls f(composite, valid) for every element of this workgroup's chunk of row r, in an order that only
+// depends on the launch (two sweeps of a chunk see the same order), four loads per lane in flight.
 // xi: when not NULL, the column index that element i of a row stands for (the rows are then lists of
 // (value, index) pairs, such as Stage-1 candidates), else i itself.
+// Rows of a whole number of 16-byte vectors at a 16-byte aligned base, without xi, are read 16 bytes per
+// load (a lane then takes 4 or 8 adjacent elements): with 4-byte loads a CU has too few bytes in flight
+// to keep HBM busy (a first-digit pass over 128 x 65536 fp32 took 16 us, the bytes alone take 5).
+typedef uint32_t ex_v4u __attribute__((ext_vector_type(4)));
 template <int ELT, typename F>
 __device__ __forceinline__ void for_chunk(const void *x, const int32_t *xi, int64_t n, int r, int chunk, F f,
                                           int chunk_elems = kExChunk) {
     const int64_t e0 = (int64_t)chunk * chunk_elems;
     const int64_t e1 = (e0 + chunk_elems < n) ? e0 + chunk_elems : n;
     const int T = blockDim.x;
+    // both paths keep whole wavefronts together (f may use wavefront-wide operations and carry
+    // wavefront-uniform state): their loop conditions only look at the wavefront's first element
+    const int lane = threadIdx.x & (kWave - 1);
+    constexpr int VE = (ELT == ATK_F32) ? 4 : 8;  // elements per 16-byte vector
+    if (!xi && n % VE == 0 && ((uintptr_t)x & 15) == 0) {  // uniform over the launch; e0, e1 are then multiples of VE too
+        const ex_v4u *row = (const ex_v4u *)((const unsigned char *)x + ((int64_t)r * n + e0) * (ELT == ATK_F32 ? 4 : 2));
+        const int nv = (int)((e1 - e0) / VE);
+        auto feed = [&](const ex_v4u &q, int v, bool ok) {
+            const int64_t i = e0 + (int64_t)v * VE;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (ELT == ATK_F32) {
+                    f(ok ? make_composite(q[j], (int32_t)(i + j)) : 0ull, ok);
+                } else {
+                    f(ok ? make_composite(q[j] << 16, (int32_t)(i + 2 * j)) : 0ull, ok);
+                    f(ok ? make_composite(q[j] & 0xffff0000u, (int32_t)(i + 2 * j + 1)) : 0ull, ok);
+                }
+            }
+        };
+        int v = threadIdx.x;
+        for (; v - lane + 3 * T + (kWave - 1) < nv; v += 4 * T) {
+            const ex_v4u q0 = __builtin_nontemporal_load(row + v), q1 = __builtin_nontemporal_load(row + v + T),
+                         q2 = __builtin_nontemporal_load(row + v + 2 * T), q3 = __builtin_nontemporal_load(row + v + 3 * T);
+            feed(q0, v, true);
+            feed(q1, v + T, true);
+            feed(q2, v + 2 * T, true);
+            feed(q3, v + 3 * T, true);
+        }
+        for (; v - lane < nv; v += T) {
+            const bool ok = v < nv;
+            const ex_v4u q = __builtin_nontemporal_load(row + (ok ? v : 0));  // lanes past the end re-read the chunk's first vector
+            feed(q, v, ok);
+        }
+        return;
+    }
     auto load_bits = [&](int64_t i) -> uint32_t {
         if (ELT == ATK_F32) return __builtin_nontemporal_load((const uint32_t *)x + (int64_t)r * n + i);
         return ((uint32_t)__builtin_nontemporal_load((const uint16_t *)x + (int64_t)r * n + i)) << 16;
     };
-    // both loops keep whole wavefronts together (f may use wavefront-wide operations and carry
-    // wavefront-uniform state): their conditions only look at the wavefront's first element
-    const int lane = threadIdx.x & (kWave - 1);
     int64_t i = e0 + threadIdx.x;
     auto index_of = [&](int64_t i) -> int32_t { return xi ? xi[(int64_t)r * n + i] : (int32_t)i; };
     for (; i - lane + 3 * T + (kWave - 1) < e1; i += 4 * T) {
@@ -257,7 +294,7 @@ template <int ELT, bool FIRST, bool FUSED>
 __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st,
                                                               uint32_t *ghist, int shift, int width, int last_pass,
                                                               uint32_t filter_cap, uint32_t k, int chunk_elems,
-                                                              int chunk_stride) {
+                                                              int chunk_stride, int runs) {
     __shared__ uint32_t lh[kExBins];
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t is_last;
@@ -269,13 +306,17 @@ __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, con
     const uint32_t dmask = (1u << width) - 1u;
     for (int i = tid; i < kExBins; i += blockDim.x) lh[i] = 0;
     __syncthreads();
-    // chunk_stride > 1: a sample of the row, in small chunks
-    for_chunk<ELT>(
-        x, xi, n, r, (int)blockIdx.x * chunk_stride,
-        [&](u64 c, bool ok) {
-            if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
-        },
-        chunk_elems);
+    // chunk_stride > 1: a sample of the row, in small chunks; runs > 1: several chunks per workgroup
+    for (int q = 0; q < runs; ++q) {
+        const int64_t chunk = ((int64_t)blockIdx.x * runs + q) * chunk_stride;
+        if (chunk * chunk_elems >= n) break;  // uniform over the workgroup
+        for_chunk<ELT>(
+            x, xi, n, r, (int)chunk,
+            [&](u64 c, bool ok) {
+                if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
+            },
+            chunk_elems);
+    }
     __syncthreads();
     uint32_t *gh = ghist + (int64_t)r * kExRow;
     for (int i = tid; i < kExBins; i += blockDim.x) {
@@ -821,13 +862,17 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     while (((int64_t)1 << idx_bits) < pl.idx_n) ++idx_bits;
     // One pass of the digit descent over every `stride`-th chunk of the rows; small launches let the
     // row's last workgroup decide, big ones take a launch of their own for it.
-    auto pass = [&](int p, bool first, uint32_t fcap, int elems, int stride, bool fuse) {
+    // few: a pass with little to do (a sample of the rows; most rows finished): as many chunks per workgroup
+    // as keep it a launch of the first kind
+    auto pass = [&](int p, bool first, uint32_t fcap, int elems, int stride, bool few) {
         const int last = p == kExPasses - 1 ? 1 : 0;
-        const dim3 grid((unsigned)ceil_div64(n, (int64_t)elems * stride), (unsigned)m);
-        const bool fused = fuse || (int64_t)grid.x * m <= kExFusedMaxWgs;
+        const int64_t per_row = ceil_div64(n, (int64_t)elems * stride);
+        const int runs = few ? (int)ceil_div64(per_row * m, kExFusedMaxWgs) : 1;
+        const dim3 grid((unsigned)ceil_div64(per_row, runs), (unsigned)m);
+        const bool fused = (int64_t)grid.x * m <= kExFusedMaxWgs;
 #define ATK_HIST(FIRST, FUSED)                                                                                             \
     hipLaunchKernelGGL((ex_hist_kernel<ELT, FIRST, FUSED>), grid, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist,        \
-                       kExShift[p], kExWidth[p], last, fcap, (uint32_t)k, elems, stride)
+                       kExShift[p], kExWidth[p], last, fcap, (uint32_t)k, elems, stride, runs)
         if (fused) {
             if (first) ATK_HIST(true, true);
             else ATK_HIST(false, true);
@@ -852,15 +897,15 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st, (int)k,
                            idx_bits, out_vals, out_idx);
     };
-    // Very small k on big inputs: the k-th largest of a sample (every 16th run of 2048 elements), to
+    // Very small k on big inputs: the k-th largest of a sample (every 16th run of 4096 elements), to
     // two digits, is a threshold that at least k elements of the row reach, and about 16 k of them on
     // data without order along the row: one sweep copies them out, instead of one sweep to count the
     // first digit and one to copy.  A row where more than kFilterCap reach it starts over below; the
-    // passes below then mostly find nothing to do, so they keep to one launch each.
+    // passes below then mostly find nothing to do, so they are launches of few workgroups, each with many chunks.
     const bool sample = pl.sample;
     if (sample) {
-        pass(0, true, kSampledPass, kSampleChunk, sample_stride(k), false);
-        pass(1, false, kSampledLast, kSampleChunk, sample_stride(k), false);
+        pass(0, true, kSampledPass, kSampleChunk, sample_stride(k), true);
+        pass(1, false, kSampledLast, kSampleChunk, sample_stride(k), true);
         copy_out();
     }
     for (int p = 0; p < kExPasses; ++p) {

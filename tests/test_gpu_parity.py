@@ -481,7 +481,7 @@ def test_exact_small_rows(dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_exact_sampled_threshold(dtype, monkeypatch):
     """Very small k on big inputs: the threshold is first guessed from a sample of the row (every 16th
-    run of 2048 elements) and everything that reaches it is copied out in one sweep.  Rows where too
+    run of 4096 elements) and everything that reaches it is copied out in one sweep.  Rows where too
     much reaches it (ties, few levels, an ascending row whose sample misses the large values) start
     over digit by digit; finished and restarted rows share one call.  XS=1 takes that path on inputs
     below the size from which the library would choose it."""
@@ -500,7 +500,7 @@ def test_exact_sampled_threshold(dtype, monkeypatch):
                        workloads.special_values(1, n, seed=615, dtype=dtype)])
     run_exact(mixed, 64)
     run_exact(mixed, 128)
-    run_exact(mixed, 200)  # every 8th run of 2048 elements sampled
+    run_exact(mixed, 200)  # every 8th run of 4096 elements sampled
     run_exact(mixed, 512)  # every 4th
 
 
