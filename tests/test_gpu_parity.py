@@ -31,13 +31,24 @@ def as_bits(t):
     return a.view(torch.int16).numpy().view(np.uint16)
 
 
-def run_case(x_cpu, k, b, k_b, rows=None, tag="", assignment=None):
+def to_gpu(x_cpu, shift=0):
+    """x on the GPU; shift > 0: in a buffer whose first element lies that many elements past a 256-byte boundary."""
+    if not shift:
+        return x_cpu.cuda()
+    buf = torch.empty(x_cpu.numel() + shift, dtype=x_cpu.dtype, device="cuda")
+    view = buf[shift:].view(x_cpu.shape)
+    view.copy_(x_cpu)
+    assert view.is_contiguous() and view.data_ptr() == buf.data_ptr() + shift * x_cpu.element_size()
+    return view
+
+
+def run_case(x_cpu, k, b, k_b, rows=None, tag="", assignment=None, shift=0):
     print("case %s shape=%s dtype=%s k=%d b=%d k_b=%d plan=[%s]" % (
         tag, tuple(x_cpu.shape), x_cpu.dtype, k, b, k_b,
         atk.plan_describe(x_cpu.shape[0], x_cpu.shape[1], k, b, k_b,
                           atk.ATK_F32 if x_cpu.dtype == torch.float32 else atk.ATK_BF16,
                           assignment or atk.ATK_INTERLEAVED)), flush=True)
-    xg = x_cpu.cuda()
+    xg = to_gpu(x_cpu, shift)
     vals, idx = atk.approx_topk(xg, k, b, k_b, assignment=assignment)
     torch.cuda.synchronize()
     gv, gi = as_bits(vals), idx.cpu().numpy()
@@ -55,9 +66,9 @@ def run_case(x_cpu, k, b, k_b, rows=None, tag="", assignment=None):
     assert np.array_equal(gv, ovb), "values differ"
 
 
-def run_exact(x_cpu, k, rows=None):
-    print("exact shape=%s dtype=%s k=%d" % (tuple(x_cpu.shape), x_cpu.dtype, k), flush=True)
-    xg = x_cpu.cuda()
+def run_exact(x_cpu, k, rows=None, shift=0):
+    print("exact shape=%s dtype=%s k=%d shift=%d" % (tuple(x_cpu.shape), x_cpu.dtype, k, shift), flush=True)
+    xg = to_gpu(x_cpu, shift)
     vals, idx = atk.exact_topk(xg, k)
     torch.cuda.synchronize()
     gv, gi = as_bits(vals), idx.cpu().numpy()
@@ -502,6 +513,25 @@ def test_exact_sampled_threshold(dtype, monkeypatch):
     run_exact(mixed, 128)
     run_exact(mixed, 200)  # every 8th run of 4096 elements sampled
     run_exact(mixed, 512)  # every 4th
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_input_off_a_vector_boundary(dtype):
+    """x may start at any multiple of its element size: the 16-byte loads of both entry points are only
+    taken from a 16-byte aligned base (rows of a whole number of vectors), everything else goes the
+    element-wise way."""
+    for shift in (1, 2, 3, 5):
+        run_case(workloads.normal_rows(3, 8192, seed=800 + shift, dtype=dtype), 64, 64, 1, shift=shift, tag="shifted")
+        run_case(workloads.normal_rows(2, 65536, seed=810 + shift, dtype=dtype), 64, 256, 1, shift=shift, tag="shifted")
+        run_case(workloads.normal_rows(2, 16384, seed=820 + shift, dtype=dtype), 128, 64, 4, shift=shift, tag="shifted")
+        run_case(workloads.normal_rows(2, 16384, seed=830 + shift, dtype=dtype), 128, 32, 4, shift=shift, tag="shifted",
+                 assignment=atk.ATK_CONTIGUOUS)
+        run_exact(workloads.normal_rows(2, 4096, seed=840 + shift, dtype=dtype), 100, shift=shift)
+        run_exact(workloads.normal_rows(2, 65536, seed=850 + shift, dtype=dtype), 64, shift=shift)
+        run_exact(workloads.normal_rows(2, 65536, seed=860 + shift, dtype=dtype), 9000, shift=shift)
+    # bf16 rows of a multiple of 4 but not of 8 elements: whole vectors only every other row
+    run_exact(workloads.normal_rows(3, 65540, seed=870, dtype=dtype), 64)
+    run_exact(workloads.normal_rows(3, 65540, seed=871, dtype=dtype), 64, shift=4)
 
 
 @pytest.mark.parametrize("chunk", [1024, 4096, 8192, 16384])
