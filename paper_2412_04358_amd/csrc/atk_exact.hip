@@ -30,6 +30,7 @@ constexpr int kExChunkMin = 4096;        // ... down to this on smaller inputs, 
 constexpr int kExFusedMaxWgs = 1024;     // largest sweep whose last workgroup per row also decides the digit (see ex_hist_kernel)
 constexpr int kExRow = kExBins + kTicketStride;  // words per row of the global histograms: the bins, then the row's ticket
 constexpr int kSortTile = 2048;          // elements per workgroup of the global sort
+constexpr int kSortScanInScatter = 32;    // rows of up to this many tiles: the scatter step of the global sort scans the tile counts itself
 constexpr int kSortLdsMaxK = 4096;       // survivors ordered in LDS by one workgroup
 constexpr int kPartTile = 4096;          // survivors per workgroup of the partition sort's sweeps
 constexpr int kPartMaxBins = 2048;
@@ -769,15 +770,36 @@ __global__ void __launch_bounds__(256) sort_scan_kernel(uint32_t *tile_hist, con
 
 // stable scatter of one tile: the tile is walked in rounds of 256 consecutive elements; inside a
 // round an element's rank among equal bins is its rank among the lanes of its wavefront with
-// that bin (eight ballots) plus the counts of the lower wavefronts
+// that bin (eight ballots) plus the counts of the lower wavefronts.
+// SCAN (rows of few tiles): tile_hist holds the counts as sort_hist_kernel left them, and every
+// workgroup works out its own starting places from them - what sort_scan_kernel does for all tiles
+// at once, without its launch.
+template <bool SCAN>
 __global__ void __launch_bounds__(256) sort_scatter_kernel(const u64 *src, u64 *dst, const ExRowState *st, int64_t k,
                                                            int tiles, const uint32_t *tile_hist, int shift) {
     __shared__ uint32_t running[256];
     __shared__ uint32_t wcnt[4][256];
+    __shared__ uint32_t wave_tot[4];
     const int r = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
     if (st[r].mode != 3u) return;
     const int lane = tid & 63, wave = tid >> 6;
-    running[tid] = tile_hist[((int64_t)r * tiles + tile) * 256 + tid];
+    if (SCAN) {
+        const uint32_t *th = tile_hist + (int64_t)r * tiles * 256;
+        uint32_t total = 0, before = 0;  // of bin tid: in the whole row, in the tiles before this one
+        for (int t = 0; t < tiles; ++t) {
+            const uint32_t c = th[t * 256 + tid];
+            total += c;
+            if (t < tile) before += c;
+        }
+        const uint32_t incl = wave_incl_scan_u32(total);
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        uint32_t start = incl - total + before;
+        for (int w = 0; w < wave; ++w) start += wave_tot[w];
+        running[tid] = start;
+    } else {
+        running[tid] = tile_hist[((int64_t)r * tiles + tile) * 256 + tid];
+    }
 #pragma unroll
     for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
     __syncthreads();
@@ -961,9 +983,14 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         if (shift < 32 && shift >= idx_bits + 1) continue;
         const dim3 grid((unsigned)tiles, (unsigned)m);
         hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(256), 0, stream, bufs[cur], st, k, tiles, tile_hist, shift);
-        hipLaunchKernelGGL(sort_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, tile_hist, st, tiles);
-        hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], st, k, tiles,
-                           tile_hist, shift);
+        if (tiles <= kSortScanInScatter) {
+            hipLaunchKernelGGL(sort_scatter_kernel<true>, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], st, k, tiles,
+                               tile_hist, shift);
+        } else {
+            hipLaunchKernelGGL(sort_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, tile_hist, st, tiles);
+            hipLaunchKernelGGL(sort_scatter_kernel<false>, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], st, k, tiles,
+                               tile_hist, shift);
+        }
         cur ^= 1;
     }
     const int64_t total = m * k;
