@@ -489,6 +489,18 @@ __device__ __forceinline__ uint32_t part_shift(u64 span, int nb) {  // smallest 
     return bits > lg ? (uint32_t)(bits - lg) : 0u;
 }
 
+// The bins are linear in a squeezed form of the composite, from which the bits that are the same in
+// every element are taken out: the low `drop` bits of the order key (16 for bf16) and the high bits of
+// the index field (column indices are below 2^(keep - 1)).  The map keeps the order, and it puts equal
+// values with different indices `1` apart per index step instead of burying the index under 2^32:
+// bins then also divide long runs of ties (bf16 rows hold few distinct values).
+struct Squeeze {
+    int drop, keep;
+    __device__ __forceinline__ u64 operator()(u64 c) const {
+        return ((c >> (32 + drop)) << keep) | (c & ((1ull << keep) - 1ull));
+    }
+};
+
 __global__ void __launch_bounds__(256) part_zero_kernel(uint32_t *words, int64_t count) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) words[i] = 0u;
@@ -496,11 +508,11 @@ __global__ void __launch_bounds__(256) part_zero_kernel(uint32_t *words, int64_t
 
 // counts[row][bin] += elements of this tile in bin
 __global__ void __launch_bounds__(256) part_hist_kernel(const u64 *sel, const ExRowState *st, int64_t k, int nb,
-                                                        uint32_t *counts) {
+                                                        uint32_t *counts, Squeeze sq) {
     __shared__ uint32_t lh[kPartMaxBins];
     const int r = blockIdx.y, tid = threadIdx.x;
-    const u64 thr = st[r].prefix;
-    const uint32_t shift = part_shift(st[r].cmax - thr, nb);
+    const u64 thr = sq(st[r].prefix);
+    const uint32_t shift = part_shift(sq(st[r].cmax) - thr, nb);
     for (int i = tid; i < nb; i += 256) lh[i] = 0;
     __syncthreads();
     const int64_t e0 = (int64_t)blockIdx.x * kPartTile;
@@ -515,7 +527,7 @@ __global__ void __launch_bounds__(256) part_hist_kernel(const u64 *sel, const Ex
     }
 #pragma unroll
     for (int j = 0; j < kPartTile / 256; ++j)
-        if (e0 + j * 256 + tid < k) atomicAdd(&lh[(uint32_t)((c[j] - thr) >> shift)], 1u);
+        if (e0 + j * 256 + tid < k) atomicAdd(&lh[(uint32_t)((sq(c[j]) - thr) >> shift)], 1u);
     __syncthreads();
     uint32_t *gc = counts + (int64_t)r * nb;
     for (int i = tid; i < nb; i += 256) {
@@ -566,12 +578,12 @@ __global__ void __launch_bounds__(256) part_scan_kernel(ExRowState *st, int nb, 
 
 // every element of the tile goes to its bin's segment of dst (any order inside the bin)
 __global__ void __launch_bounds__(256) part_scatter_kernel(const u64 *sel, u64 *dst, const ExRowState *st, int64_t k, int nb,
-                                                           const uint32_t *starts, uint32_t *cursors) {
+                                                           const uint32_t *starts, uint32_t *cursors, Squeeze sq) {
     __shared__ uint32_t lh[kPartMaxBins];    // count of the tile per bin, then position of the next element
     const int r = blockIdx.y, tid = threadIdx.x;
     if (st[r].mode == 3u) return;
-    const u64 thr = st[r].prefix;
-    const uint32_t shift = part_shift(st[r].cmax - thr, nb);
+    const u64 thr = sq(st[r].prefix);
+    const uint32_t shift = part_shift(sq(st[r].cmax) - thr, nb);
     for (int i = tid; i < nb; i += 256) lh[i] = 0;
     __syncthreads();
     const int64_t e0 = (int64_t)blockIdx.x * kPartTile;
@@ -586,7 +598,7 @@ __global__ void __launch_bounds__(256) part_scatter_kernel(const u64 *sel, u64 *
 #pragma unroll
     for (int j = 0; j < kPartTile / 256; ++j) {
         if (e0 + j * 256 + tid >= k) c[j] = 0ull;
-        bin[j] = c[j] ? (uint32_t)((c[j] - thr) >> shift) : 0u;
+        bin[j] = c[j] ? (uint32_t)((sq(c[j]) - thr) >> shift) : 0u;
         if (c[j]) atomicAdd(&lh[bin[j]], 1u);
     }
     __syncthreads();
@@ -610,6 +622,7 @@ __global__ void __launch_bounds__(256) part_scatter_kernel(const u64 *sel, u64 *
 // files every element into its sub-bin's segment, and an element's rank is its segment's start
 // plus the larger elements of that segment.
 constexpr int kPartSub = 512;
+constexpr int kPartCrowd = 24;  // a sub-bin with more elements than this sends the bin to the bitonic sort
 constexpr int kPartSlots = kPartWaveMax / kWave;  // elements a lane holds
 __device__ __forceinline__ void wave_sync_lds() {  // orders this wavefront's LDS writes before its later reads
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -619,7 +632,8 @@ __device__ __forceinline__ void wave_sync_lds() {  // orders this wavefront's LD
 template <int ELT>
 __global__ void __launch_bounds__(256) part_sort_small_kernel(const u64 *src, const ExRowState *st, int64_t k, int nb,
                                                               int64_t total_bins, const uint32_t *counts,
-                                                              const uint32_t *starts, void *out_vals, int32_t *out_idx) {
+                                                              const uint32_t *starts, uint32_t *big, Squeeze sq,
+                                                              void *out_vals, int32_t *out_idx) {
     __shared__ u64 filed[4][kPartWaveMax];
     __shared__ uint32_t sub_cnt[4][kPartSub];
     __shared__ uint32_t sub_off[4][kPartSub + 8];  // [sb + 1] = start of sub-bin sb's segment, [0] = end of sub-bin 0's
@@ -645,8 +659,9 @@ __global__ void __launch_bounds__(256) part_sort_small_kernel(const u64 *src, co
 #pragma unroll
     for (int e = 0; e < kPartSlots; ++e)
         if (c[e]) {
-            lo = c[e] < lo ? c[e] : lo;
-            hi = c[e] > hi ? c[e] : hi;
+            const u64 q = sq(c[e]);
+            lo = q < lo ? q : lo;
+            hi = q > hi ? q : hi;
         }
     for (int i = lane; i < kPartSub; i += kWave) sc[i] = 0u;
     wave_min_max_u64(lo, hi);
@@ -655,7 +670,7 @@ __global__ void __launch_bounds__(256) part_sort_small_kernel(const u64 *src, co
     wave_sync_lds();
 #pragma unroll
     for (int e = 0; e < kPartSlots; ++e) {
-        sb[e] = c[e] ? (uint32_t)((c[e] - lo) >> sh) : 0u;
+        sb[e] = c[e] ? (uint32_t)((sq(c[e]) - lo) >> sh) : 0u;
         if (c[e]) atomicAdd(&sc[sb[e]], 1u);
     }
     wave_sync_lds();
@@ -663,9 +678,19 @@ __global__ void __launch_bounds__(256) part_sort_small_kernel(const u64 *src, co
         // lane l owns the Q sub-bins below kPartSub - Q*l: lane order is descending sub-bin order
         constexpr int Q = kPartSub / kWave;
         const int top = kPartSub - 1 - lane * Q;
-        uint32_t sum = 0;
+        uint32_t sum = 0, crowd = 0;
 #pragma unroll
-        for (int q = 0; q < Q; ++q) sum += sc[top - q];
+        for (int q = 0; q < Q; ++q) {
+            sum += sc[top - q];
+            crowd = sc[top - q] > crowd ? sc[top - q] : crowd;
+        }
+        // Elements piled on a few places of the bin's range (several values with many ties each: the sub-bins
+        // tell the values apart, not the indices) would be ranked by comparing each with all of its sub-bin:
+        // such a bin joins the list of part_sort_big_kernel, which runs after this launch.
+        if (__ballot(crowd > (uint32_t)kPartCrowd)) {  // uniform over the wavefront
+            if (lane == 0) big[1 + atomicAdd(&big[0], 1u)] = (uint32_t)r * kPartMaxBins + (uint32_t)bin;
+            return;
+        }
         uint32_t run = wave_incl_scan_u32(sum) - sum;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
@@ -964,12 +989,16 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         // the list's counter and the counts start from zero (a fill kernel, so that the call can be captured in a graph)
         hipLaunchKernelGGL(part_zero_kernel, dim3((unsigned)ceil_div64(64 + 2 * total_bins, 256)), dim3(256), 0, stream, big,
                            64 + 2 * total_bins);
-        hipLaunchKernelGGL(part_hist_kernel, dim3((unsigned)ptiles, (unsigned)m), dim3(256), 0, stream, sel, st, k, nb, counts);
+        Squeeze sq;
+        sq.drop = ELT == ATK_BF16 ? 16 : 0;
+        sq.keep = idx_bits + 1;  // the index field: 0x7fffffff - idx, then the zero-sign flag
+        hipLaunchKernelGGL(part_hist_kernel, dim3((unsigned)ptiles, (unsigned)m), dim3(256), 0, stream, sel, st, k, nb, counts,
+                           sq);
         hipLaunchKernelGGL(part_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, st, nb, counts, starts, cursors, big);
         hipLaunchKernelGGL(part_scatter_kernel, dim3((unsigned)ptiles, (unsigned)m), dim3(256), 0, stream, sel, bufs[1], st, k,
-                           nb, starts, cursors);
+                           nb, starts, cursors, sq);
         hipLaunchKernelGGL(part_sort_small_kernel<ELT>, dim3((unsigned)ceil_div64(total_bins, 4)), dim3(256), 0, stream,
-                           bufs[1], st, k, nb, total_bins, counts, starts, out_vals, out_idx);
+                           bufs[1], st, k, nb, total_bins, counts, starts, big, sq, out_vals, out_idx);
         hipLaunchKernelGGL(part_sort_big_kernel<ELT>, dim3(1024), dim3(256), 0, stream, bufs[1], st, k, nb, counts, starts,
                            big, out_vals, out_idx);
         e = hipGetLastError();

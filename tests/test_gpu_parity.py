@@ -577,6 +577,11 @@ def test_exact_long_rows(dtype):
                            workloads.few_levels(1, 150000, levels=2, seed=25, dtype=dtype),
                            workloads.special_values(1, 150000, seed=26, dtype=dtype)])
     run_exact(big_mixed, 30000)
+    # values on a grid (about a thousand levels among the survivors, tens of ties each): bins of the partition
+    # sort that hold a few levels; the ties of a level land in one sub-bin, and such bins go to the bitonic sort
+    grid = torch.round(workloads.normal_rows(3, 100000, seed=27, dtype="f32") * 256) / 256
+    run_exact(grid if dtype == "f32" else grid.to(torch.bfloat16), 20000)
+    run_exact(grid if dtype == "f32" else grid.to(torch.bfloat16), 6000)
 
 
 def test_exact_many_long_rows():
