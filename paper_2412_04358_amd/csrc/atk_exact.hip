@@ -22,9 +22,7 @@ namespace atk {
 namespace {
 
 constexpr int kExBins = 2048;            // 11-bit digits
-constexpr int kExPasses = 6;             // 64 bits = 11+11+10 (value key) + 11+11+10 (index field)
-constexpr int kExShift[kExPasses] = {53, 42, 32, 21, 10, 0};
-constexpr int kExWidth[kExPasses] = {11, 11, 10, 11, 11, 10};
+constexpr int kExDigit = 11;             // bits per pass of the digit descent (the last pass takes what is left)
 constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps (inputs that fill the chip with that)
 constexpr int kExChunkMin = 4096;        // ... down to this on smaller inputs, while a sweep stays within kExFusedMaxWgs workgroups
 constexpr int kExFusedMaxWgs = 1024;     // largest sweep whose last workgroup per row also decides the digit (see ex_hist_kernel)
@@ -45,7 +43,7 @@ constexpr uint32_t kSampledPass = 0xfffffffeu, kSampledLast = 0xffffffffu;  // i
 constexpr int kFilterCap = 4096;         // elements at or above the first digit's bucket that one workgroup selects from in LDS
 
 struct ExRowState {  // one per row, 32 bytes
-    u64 prefix;      // decided high bits of the threshold
+    u64 prefix;      // decided high bits of the threshold (of its squeezed form: see Squeeze)
     uint32_t need;   // elements still needed inside the current bucket
     uint32_t done;   // threshold known
     uint32_t cursor; // survivors written so far
@@ -225,6 +223,31 @@ __device__ __forceinline__ void for_chunk(const void *x, const int32_t *xi, int6
     }
 }
 
+// The radix select and the partition sort work on a squeezed form of the composite, from which the bits
+// that carry nothing are taken out: the low `drop` bits of the order key (16 for bf16: they only repeat
+// the sign) and the high bits of the index field (column indices are below 2^(keep - 1), so the bits
+// of 0x7fffffff - idx above them are all ones).  The map keeps the order and loses nothing on the
+// elements of one call.  The digit descent then has (32 - drop) + keep bits to decide instead of 64
+// (bf16, n = 65536: 3 passes instead of 6 when ties take it down to the index), and equal values with
+// different indices lie `1` apart per index step instead of 2^32: linear bins also divide long runs
+// of ties (bf16 rows hold few distinct values).
+struct Squeeze {
+    int drop, keep;
+    __device__ __forceinline__ u64 operator()(u64 c) const {
+        return ((c >> (32 + drop)) << keep) | (c & ((1ull << keep) - 1ull));
+    }
+    // The composite that t is the squeezed form of, with the bits that were taken out put back as the
+    // elements of this call have them: for an element c, c >= expand(t) exactly when (*this)(c) >= t
+    // (the sweep that collects the survivors compares composites as they are: it has no instruction to spare).
+    __device__ __forceinline__ u64 expand(u64 t) const {
+        const u64 kh = t >> keep;  // the key without its low `drop` bits
+        u64 key = kh << drop;
+        if (drop && !((kh >> (31 - drop)) & 1ull)) key |= (1ull << drop) - 1ull;  // keys of negative bf16 values end in ones
+        const u64 kept = (1ull << keep) - 1ull;
+        return (key << 32) | (0xffffffffull & ~kept) | (t & kept);
+    }
+};
+
 // The digit bucket that holds the need-th largest element of row r, from the row's global
 // histogram `gh`; updates the row state and leaves the histogram zeroed.  Called by a whole
 // workgroup of at least 256 lanes (uniformly); wave_tot: four words of LDS.
@@ -295,7 +318,7 @@ template <int ELT, bool FIRST, bool FUSED>
 __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st,
                                                               uint32_t *ghist, int shift, int width, int last_pass,
                                                               uint32_t filter_cap, uint32_t k, int chunk_elems,
-                                                              int chunk_stride, int runs) {
+                                                              int chunk_stride, int runs, Squeeze sq) {
     __shared__ uint32_t lh[kExBins];
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t is_last;
@@ -308,15 +331,30 @@ __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, con
     for (int i = tid; i < kExBins; i += blockDim.x) lh[i] = 0;
     __syncthreads();
     // chunk_stride > 1: a sample of the row, in small chunks; runs > 1: several chunks per workgroup
+    // A digit that lies in the key alone (the first pass always does) is read off the composite with one
+    // shift; only a digit that reaches into the index field needs the squeezed form of every element.
+    const bool key_digit = shift >= sq.keep;  // uniform over the launch
+    const int key_shift = 32 + sq.drop, dshift = shift - sq.keep;
+    const u64 key_mask = hi_mask >> sq.keep, key_prefix = prefix >> sq.keep;
     for (int q = 0; q < runs; ++q) {
         const int64_t chunk = ((int64_t)blockIdx.x * runs + q) * chunk_stride;
         if (chunk * chunk_elems >= n) break;  // uniform over the workgroup
-        for_chunk<ELT>(
-            x, xi, n, r, (int)chunk,
-            [&](u64 c, bool ok) {
-                if (ok && (c & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(c >> shift) & dmask], 1u);
-            },
-            chunk_elems);
+        if (key_digit)
+            for_chunk<ELT>(
+                x, xi, n, r, (int)chunk,
+                [&](u64 c, bool ok) {
+                    const u64 q = c >> key_shift;
+                    if (ok && (q & key_mask) == key_prefix) atomicAdd(&lh[(uint32_t)(q >> dshift) & dmask], 1u);
+                },
+                chunk_elems);
+        else
+            for_chunk<ELT>(
+                x, xi, n, r, (int)chunk,
+                [&](u64 c, bool ok) {
+                    const u64 q = sq(c);
+                    if (ok && (q & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(q >> shift) & dmask], 1u);
+                },
+                chunk_elems);
     }
     __syncthreads();
     uint32_t *gh = ghist + (int64_t)r * kExRow;
@@ -360,14 +398,14 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
 // quarter of a chunk does.
 template <int ELT, bool FILTER, int kStash>
 __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st, u64 *sel,
-                                                                 int64_t k, int chunk_elems) {
+                                                                 int64_t k, int chunk_elems, Squeeze sq) {
     __shared__ u64 stash[kStash];
     __shared__ uint32_t wave_cnt[kMaxThreads / kWave];
     __shared__ uint32_t wave_base[kMaxThreads / kWave];
     __shared__ uint32_t stash_n, first_pos;
     const int r = blockIdx.y;
     if (FILTER ? st[r].mode != 1u : st[r].mode == 2u) return;  // uniform over the workgroup
-    const u64 thr = st[r].prefix;
+    const u64 thr = sq.expand(st[r].prefix);
     u64 *dst = sel + (int64_t)r * k;  // k: the row stride of sel (kFilterCap for FILTER)
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
     if (threadIdx.x == 0) stash_n = 0;
@@ -489,18 +527,6 @@ __device__ __forceinline__ uint32_t part_shift(u64 span, int nb) {  // smallest 
     return bits > lg ? (uint32_t)(bits - lg) : 0u;
 }
 
-// The bins are linear in a squeezed form of the composite, from which the bits that are the same in
-// every element are taken out: the low `drop` bits of the order key (16 for bf16) and the high bits of
-// the index field (column indices are below 2^(keep - 1)).  The map keeps the order, and it puts equal
-// values with different indices `1` apart per index step instead of burying the index under 2^32:
-// bins then also divide long runs of ties (bf16 rows hold few distinct values).
-struct Squeeze {
-    int drop, keep;
-    __device__ __forceinline__ u64 operator()(u64 c) const {
-        return ((c >> (32 + drop)) << keep) | (c & ((1ull << keep) - 1ull));
-    }
-};
-
 __global__ void __launch_bounds__(256) part_zero_kernel(uint32_t *words, int64_t count) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) words[i] = 0u;
@@ -511,7 +537,7 @@ __global__ void __launch_bounds__(256) part_hist_kernel(const u64 *sel, const Ex
                                                         uint32_t *counts, Squeeze sq) {
     __shared__ uint32_t lh[kPartMaxBins];
     const int r = blockIdx.y, tid = threadIdx.x;
-    const u64 thr = sq(st[r].prefix);
+    const u64 thr = st[r].prefix;  // squeezed already
     const uint32_t shift = part_shift(sq(st[r].cmax) - thr, nb);
     for (int i = tid; i < nb; i += 256) lh[i] = 0;
     __syncthreads();
@@ -582,7 +608,7 @@ __global__ void __launch_bounds__(256) part_scatter_kernel(const u64 *sel, u64 *
     __shared__ uint32_t lh[kPartMaxBins];    // count of the tile per bin, then position of the next element
     const int r = blockIdx.y, tid = threadIdx.x;
     if (st[r].mode == 3u) return;
-    const u64 thr = sq(st[r].prefix);
+    const u64 thr = st[r].prefix;  // squeezed already
     const uint32_t shift = part_shift(sq(st[r].cmax) - thr, nb);
     for (int i = tid; i < nb; i += 256) lh[i] = 0;
     __syncthreads();
@@ -911,26 +937,33 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     // row's last workgroup decide, big ones take a launch of their own for it.
     // few: a pass with little to do (a sample of the rows; most rows finished): as many chunks per workgroup
     // as keep it a launch of the first kind
+    Squeeze sq;
+    sq.drop = ELT == ATK_BF16 ? 16 : 0;
+    sq.keep = idx_bits + 1;  // the index field: 0x7fffffff - idx, then the zero-sign flag
+    const int sq_bits = 32 - sq.drop + sq.keep;                    // bits the descent has to decide
+    const int n_passes = (sq_bits + kExDigit - 1) / kExDigit;      // 2..6; digits of 11 bits from the top, the last one narrower
+    auto digit_shift = [&](int p) { return p == n_passes - 1 ? 0 : sq_bits - kExDigit * (p + 1); };
+    auto digit_width = [&](int p) { return p == n_passes - 1 ? sq_bits - kExDigit * (n_passes - 1) : kExDigit; };
     auto pass = [&](int p, bool first, uint32_t fcap, int elems, int stride, bool few) {
-        const int last = p == kExPasses - 1 ? 1 : 0;
+        const int last = p == n_passes - 1 ? 1 : 0;
         const int64_t per_row = ceil_div64(n, (int64_t)elems * stride);
         const int runs = few ? (int)ceil_div64(per_row * m, kExFusedMaxWgs) : 1;
         const dim3 grid((unsigned)ceil_div64(per_row, runs), (unsigned)m);
         const bool fused = (int64_t)grid.x * m <= kExFusedMaxWgs;
 #define ATK_HIST(FIRST, FUSED)                                                                                             \
     hipLaunchKernelGGL((ex_hist_kernel<ELT, FIRST, FUSED>), grid, dim3(kMaxThreads), 0, stream, x, xi, n, st, ghist,        \
-                       kExShift[p], kExWidth[p], last, fcap, (uint32_t)k, elems, stride, runs)
+                       digit_shift(p), digit_width(p), last, fcap, (uint32_t)k, elems, stride, runs, sq)
         if (fused) {
             if (first) ATK_HIST(true, true);
             else ATK_HIST(false, true);
         } else {
             if (first) {
                 ATK_HIST(true, false);
-                hipLaunchKernelGGL(ex_decide_kernel<true>, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p], last,
+                hipLaunchKernelGGL(ex_decide_kernel<true>, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, digit_shift(p), last,
                                    fcap, (uint32_t)k);
             } else {
                 ATK_HIST(false, false);
-                hipLaunchKernelGGL(ex_decide_kernel<false>, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, kExShift[p],
+                hipLaunchKernelGGL(ex_decide_kernel<false>, dim3((unsigned)m), dim3(256), 0, stream, st, ghist, digit_shift(p),
                                    last, fcap, (uint32_t)k);
             }
         }
@@ -939,7 +972,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     auto copy_out = [&]() {  // rows in mode 1: everything at or above their threshold so far, selected in LDS
         u64 *fbuf = sel + m * k;
         hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, fbuf,
-                           (int64_t)kFilterCap, pl.chunk_elems);
+                           (int64_t)kFilterCap, pl.chunk_elems, sq);
         const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
         hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st, (int)k,
                            idx_bits, out_vals, out_idx);
@@ -955,15 +988,15 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         pass(1, false, kSampledLast, kSampleChunk, sample_stride(k), true);
         copy_out();
     }
-    for (int p = 0; p < kExPasses; ++p) {
+    for (int p = 0; p < n_passes; ++p) {
         const bool filter_now = p == 0 && pl.filter && !sample;
         pass(p, p == 0 && !sample, filter_now ? (uint32_t)kFilterCap : 0u, pl.chunk_elems, 1, sample);
         if (filter_now) copy_out();
     }
     if (k * pl.chunk_elems / n <= 1536)  // expected survivors per chunk
-        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k, pl.chunk_elems);
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k, pl.chunk_elems, sq);
     else
-        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 6144>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k, pl.chunk_elems);
+        hipLaunchKernelGGL((ex_collect_kernel<ELT, false, 6144>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, sel, k, pl.chunk_elems, sq);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -989,9 +1022,6 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         // the list's counter and the counts start from zero (a fill kernel, so that the call can be captured in a graph)
         hipLaunchKernelGGL(part_zero_kernel, dim3((unsigned)ceil_div64(64 + 2 * total_bins, 256)), dim3(256), 0, stream, big,
                            64 + 2 * total_bins);
-        Squeeze sq;
-        sq.drop = ELT == ATK_BF16 ? 16 : 0;
-        sq.keep = idx_bits + 1;  // the index field: 0x7fffffff - idx, then the zero-sign flag
         hipLaunchKernelGGL(part_hist_kernel, dim3((unsigned)ptiles, (unsigned)m), dim3(256), 0, stream, sel, st, k, nb, counts,
                            sq);
         hipLaunchKernelGGL(part_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, st, nb, counts, starts, cursors, big);
