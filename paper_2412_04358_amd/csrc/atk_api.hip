@@ -94,7 +94,17 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int T_forced = 0, S_forced = 0, V_forced = 0;
     plan_override(&T_forced, &S_forced, &V_forced);
     // (vector loads need a 16-byte aligned x and b a multiple of V)
-    p.V = stage1_pick_v(dtype, p.KB, !ptr16 ? 1 : V_forced, b);
+    int v_want = !ptr16 ? 1 : V_forced;
+    // bf16 queues of 8 and 16 slots over wide bucket layouts, on inputs that give the chip only a wavefront or
+    // two per SIMD: one column per lane instead of two doubles the lanes, and the insertions, which bound
+    // these shapes, spread over them (128 x 65536, b = 1024, k_b = 16: 29.1 -> 25.3 us; b = 2048, k_b = 8:
+    // 13.7 -> 12.0 us; 64 rows, k_b = 16: 28.5 -> 22.4 us).  Past two (16 slots) or four (8 slots) wavefronts per
+    // SIMD two columns per lane win again (256 rows, k_b = 16: 34.5 against 49.3 us), and so they do on fewer
+    // lanes than one wavefront per SIMD, where the plan below puts several lanes on a column.
+    if (!v_want && dtype == ATK_BF16 && p.KB >= 8 && b >= 1024 && m * b >= 256 * (int64_t)kNumCU &&
+        m * b <= (p.KB >= 16 ? 512 : 1024) * (int64_t)kNumCU)
+        v_want = 1;
+    p.V = stage1_pick_v(dtype, p.KB, v_want, b);
     p.G = b / p.V;
     p.L = n / b;
     p.stage2 = b * k_b > k;
