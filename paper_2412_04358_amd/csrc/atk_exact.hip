@@ -114,7 +114,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
         const bool force = e && strstr(e, "XS=1"), off = e && strstr(e, "XS=0");
         const int64_t es = (dtype == ATK_F32) ? 4 : 2;
         p.sample = p.filter && !off && k <= kSampleMaxK && n >= 4 * (int64_t)kSampleChunk * kSampleStride &&
-                   (force || m * n * es >= kSampleMinBytes);
+                   (force || m * n * es >= kSampleMinBytes * (k > 256 ? 2 : 1));  // (64 x 2^19 f32, k = 512: 75 us without, 86 with)
     }
     if (k > kSortLdsMaxK) {
         bytes += m * k * 8;
