@@ -5,12 +5,18 @@
 //
 // Long rows: the RadixSelect scheme on the 64-bit composite (value key, then index, so that
 // ties at the k-th value resolve to the lowest indices - the "second collect step" the
-// listing's caption mentions), most significant digit first, 11-bit digits.  One pass =
-// a histogram kernel over the whole row (every workgroup a chunk, LDS histogram flushed to a
-// global one) + a small kernel that picks the digit bucket holding the k-th element.  A row is
-// finished as soon as its bucket holds exactly the number of elements still needed.  Then one
-// more sweep collects every element at or above the threshold, and the k survivors are
-// ordered: in LDS when they fit, else by a least-significant-digit radix sort in global memory.
+// listing's caption mentions), most significant digit first, 11-bit digits over the bits of the
+// composite that can differ between elements (see Squeeze).  One pass = a histogram kernel over
+// the whole row (every workgroup a chunk, LDS histogram flushed to a global one), whose last
+// workgroup per row - or, on big launches, a small kernel - picks the digit bucket holding the
+// k-th element.  A row is finished as soon as its bucket holds exactly the number of elements
+// still needed.  Then one more sweep collects every element at or above the threshold, and the
+// k survivors are ordered: in LDS when they fit, else by a partition sort (bins that are linear
+// in the squeezed composite, one wavefront per bin), with a least-significant-digit radix sort
+// in global memory for rows whose values pile up in a few bins.
+// Small k has two shortcuts: rows whose first digit leaves few elements in play have them copied
+// out and selected in LDS, and on big inputs the threshold for that copy is first guessed from a
+// sample of the row (rows where the guess lets too much through start over digit by digit).
 #include <cstdlib>
 #include <cstring>
 
