@@ -515,6 +515,20 @@ def test_exact_sampled_threshold(dtype, monkeypatch):
     run_exact(mixed, 512)  # every 4th
 
 
+def test_bf16_long_queues_one_column_per_lane():
+    """bf16 with k_b >= 8 over b >= 1024 buckets: the planner gives a lane one column instead of two when
+    that leaves the chip one to two (k_b = 16) or four (k_b = 8) wavefronts per SIMD; shapes on both sides
+    of those bounds, with the plan checked so that the case keeps meaning what it says."""
+    for m, n, b, k_b, v in [(128, 65536, 1024, 16, 1), (128, 65536, 2048, 8, 1), (64, 32768, 1024, 16, 1),
+                            (100, 31775, 1025, 16, 1), (256, 32768, 1024, 16, 2), (32, 32768, 1024, 8, 2),
+                            (128, 65536, 4096, 4, 2)]:
+        plan = atk.plan_describe(m, n, b * k_b, b, k_b, atk.ATK_BF16)
+        assert plan.startswith("V=%d " % v), plan
+        run_case(workloads.normal_rows(m, n, seed=900 + m + k_b, dtype="bf16"), b * k_b, b, k_b, tag="bf16 queues")
+    run_case(workloads.few_levels(64, 32768, levels=3, seed=910, dtype="bf16"), 16384, 1024, 16, tag="bf16 queues, ties")
+    run_case(workloads.normal_rows(128, 65536, seed=911, dtype="bf16"), 500, 1024, 16, tag="bf16 queues, Stage 2")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_input_off_a_vector_boundary(dtype):
     """x may start at any multiple of its element size: the 16-byte loads of both entry points are only
