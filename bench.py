@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--probe-long", action="store_true",
                     help="profiler run on the 128 x 2^20 rows (cfg4, k=64, k_b=1): 5 plain copies, 5 read-only kernels, "
                          "20 approx_topk calls each at b=64 and b=1024; no timing")
+    ap.add_argument("--probe-exact", action="store_true",
+                    help="profiler run of exact_topk: 10 calls each on 128 x 65536 f32 (k=64, k=16384) and on "
+                         "128 x 2^20 f32 (k=64, k=2^18); no timing")
     ap.add_argument("--probe", action="store_true",
                     help="short run for hardware-counter passes: 20 copy launches, 20 read-only launches and 20 "
                          "approx_topk launches per b, nothing else")
@@ -66,6 +69,22 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.probe_exact:
+        st = torch.cuda.current_stream().cuda_stream
+        cases = [(1 << 16, 64), (1 << 16, 16384), (1 << 20, 64), (1 << 20, 1 << 18)]
+        for n_row, k in cases:
+            xe = workloads.normal_rows(M, n_row, seed=0).to(dev)
+            ov = torch.empty((M, k), dtype=torch.float32, device=dev)
+            oi = torch.empty((M, k), dtype=torch.int32, device=dev)
+            for i in range(10):
+                rc = atk.exact_topk_raw(xe.data_ptr(), M, n_row, k, atk.ATK_F32, ov.data_ptr(), oi.data_ptr(), st)
+                if rc != 0:
+                    raise RuntimeError("exact_topk failed: %s" % atk.strerror(rc))
+            torch.cuda.synchronize()
+            del xe, ov, oi
+        print(json.dumps({"probe": "done", "calls_each": 10, "cases": [[M, n_row, k] for n_row, k in cases]}))
+        return
 
     if args.probe_long:
         n_long = 1 << 20
