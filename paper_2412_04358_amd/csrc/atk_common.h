@@ -132,6 +132,7 @@ struct ExactPlan {
     int chunks;             // workgroups per row of the global path
     int chunk_elems;        // elements of a row that one of them sweeps
     bool filter;            // small k: rows may finish through the copy-out buffer
+    int filter_cap;         // ... of this many elements per row
     bool sample;            // very small k on big inputs: the copy-out threshold is first guessed from a sample of the row
     int64_t scratch_bytes;  // data pool
     int64_t state_bytes;    // zeroed-state pool

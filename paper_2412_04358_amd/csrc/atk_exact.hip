@@ -40,6 +40,8 @@ constexpr int kPartTile = 4096;          // survivors per workgroup of the parti
 constexpr int kPartMaxBins = 2048;
 constexpr int kPartWaveMax = 512;        // largest bin that one wavefront orders on its own
 constexpr int kFilterMaxK = 1024;        // largest k that takes the copy-out path (its selection must fit 64 KB of LDS)
+constexpr int kFilterMaxKBig = 4096;     // ... with at most one row per CU: the selection may take all of a CU's LDS
+constexpr int kFilterCapBig = 8192;      // ... and chooses from this many elements
 constexpr int kSampleMaxK = 512;        // largest k whose threshold is first guessed from a sample of the row
 constexpr int kSampleChunk = 4096;       // the sample: every 16th run of 4096 elements
 constexpr int kSampleStride = 16;         // ... for k <= 128; every 8th up to 256, every 4th up to 512: about 2048 elements reach the guess
@@ -81,6 +83,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     p.state_bytes = 0;
     p.lds_bytes = 0;
     p.filter = false;
+    p.filter_cap = kFilterCap;
     p.sample = false;
     p.idx_n = n;
     if (m >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
@@ -113,7 +116,13 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     bytes += m * k * 8;
     // copy-out buffer of the small-k path, as long as it stays modest (256 MB)
     p.filter = k <= kFilterMaxK && m * (int64_t)kFilterCap * 8 <= (256ll << 20);
-    if (p.filter) bytes += m * (int64_t)kFilterCap * 8;
+    if (!p.filter && k <= kFilterMaxKBig && m <= kNumCU) {
+        // k up to 4096 on few rows: twice the elements, selected in up to 160 KB of LDS (128 x 2^20, k = 4096:
+        // two sweeps instead of four or five)
+        p.filter = true;
+        p.filter_cap = kFilterCapBig;
+    }
+    if (p.filter) bytes += m * (int64_t)p.filter_cap * 8;
     {
         // ATK_PLAN="XS=1" takes the sampled threshold on small inputs too, "XS=0" never (tests, sweeps)
         const char *e = getenv("ATK_PLAN");
@@ -399,7 +408,7 @@ __global__ void __launch_bounds__(256) ex_decide_kernel(ExRowState *st, uint32_t
 // the same counter).  Few survivors (small k) are written from LDS; if they did not all fit,
 // the chunk is swept a second time and written straight from registers.
 // FILTER: the same sweep for the rows in mode 1, whose threshold so far is just the first digit:
-// at most kFilterCap elements per row reach it, and they go to a buffer of that stride.
+// at most the plan's filter_cap elements per row reach it, and they go to a buffer of that stride.
 // kStash: 2048 keeps the sweep's occupancy up when few survive; 6144 saves the second sweep when about a
 // quarter of a chunk does.
 template <int ELT, bool FILTER, int kStash>
@@ -412,7 +421,7 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
     const int r = blockIdx.y;
     if (FILTER ? st[r].mode != 1u : st[r].mode == 2u) return;  // uniform over the workgroup
     const u64 thr = sq.expand(st[r].prefix);
-    u64 *dst = sel + (int64_t)r * k;  // k: the row stride of sel (kFilterCap for FILTER)
+    u64 *dst = sel + (int64_t)r * k;  // k: the row stride of sel (the buffer's for FILTER)
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
     if (threadIdx.x == 0) stash_n = 0;
     __syncthreads();
@@ -481,17 +490,17 @@ __global__ void __launch_bounds__(kMaxThreads) ex_order_lds_kernel(const u64 *se
     order_write<ELT>(s, k, rk, out_vals, out_idx, (int64_t)r);
 }
 
-// Rows in mode 1: the copied-out elements (at most kFilterCap) contain the k largest; one workgroup
+// Rows in mode 1: the copied-out elements (at most cap) contain the k largest; one workgroup
 // selects and orders them in LDS, writes the outputs and marks the row finished.
 template <int ELT>
 __global__ void __launch_bounds__(kMaxThreads) ex_filter_select_kernel(const u64 *buf, ExRowState *st, int k, int idx_bits,
-                                                                       void *out_vals, int32_t *out_idx) {
+                                                                       int cap, void *out_vals, int32_t *out_idx) {
     extern __shared__ __align__(16) unsigned char smem[];
     u64 *cand = (u64 *)smem;
     const int r = blockIdx.x;
     if (st[r].mode != 1u) return;  // uniform; read by every lane before lane 0 changes it below
     const int count = (int)st[r].cursor;
-    if (count > kFilterCap) {
+    if (count > cap) {
         // only after a threshold guessed from a sample: more elements reach it than were copied out.
         // The row starts over, digit by digit over all its elements.
         __syncthreads();  // every lane has read the state
@@ -507,7 +516,7 @@ __global__ void __launch_bounds__(kMaxThreads) ex_filter_select_kernel(const u64
         }
         return;
     }
-    for (int i = threadIdx.x; i < count; i += blockDim.x) cand[i] = buf[(int64_t)r * kFilterCap + i];
+    for (int i = threadIdx.x; i < count; i += blockDim.x) cand[i] = buf[(int64_t)r * cap + i];
     __syncthreads();
     select_write<ELT>(cand, count, k, idx_bits, out_vals, out_idx, (int64_t)r);
     if (threadIdx.x == 0) {
@@ -905,6 +914,19 @@ __global__ void __launch_bounds__(256) ex_decode_kernel(const u64 *sorted, const
     }
 }
 
+// A kernel that is about to be launched with more dynamic LDS than a launch may ask for by default is
+// told so, once per device (told: that kernel's own flags).
+static hipError_t allow_whole_cu_lds(const void *kernel, bool (&told)[64]) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && told[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudgetWholeRow);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64) told[dev] = true;
+    return hipSuccess;
+}
+
 template <int ELT>
 static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32_t *xi, void *out_vals, int32_t *out_idx,
                                  void *state, void *data, hipStream_t stream) {
@@ -913,17 +935,9 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         int small_bits = 1;
         while (((int64_t)1 << small_bits) < pl.idx_n) ++small_bits;
         if (pl.lds_bytes > 64 * 1024) {
-            // more dynamic LDS than a launch may ask for by default: the kernel is told so, once per device
             static bool told[64] = {};
-            int dev = 0;
-            hipError_t ea = hipGetDevice(&dev);
+            const hipError_t ea = allow_whole_cu_lds((const void *)exact_small_kernel<ELT>, told);
             if (ea != hipSuccess) return ea;
-            if (dev < 0 || dev >= 64 || !told[dev]) {
-                ea = hipFuncSetAttribute((const void *)exact_small_kernel<ELT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         kLdsBudgetWholeRow);
-                if (ea != hipSuccess) return ea;
-                if (dev >= 0 && dev < 64) told[dev] = true;
-            }
         }
         hipLaunchKernelGGL(exact_small_kernel<ELT>, dim3((unsigned)m), dim3(pl.T), (size_t)pl.lds_bytes, stream, x, xi, (int)n,
                            (int)k, small_bits, out_vals, out_idx);
@@ -978,15 +992,20 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     auto copy_out = [&]() {  // rows in mode 1: everything at or above their threshold so far, selected in LDS
         u64 *fbuf = sel + m * k;
         hipLaunchKernelGGL((ex_collect_kernel<ELT, true, 2048>), sweep, dim3(kMaxThreads), 0, stream, x, xi, n, st, fbuf,
-                           (int64_t)kFilterCap, pl.chunk_elems, sq);
-        const size_t flds = (size_t)select_lds_bytes(kFilterCap, (int)pow2_ceil64(k));
+                           (int64_t)pl.filter_cap, pl.chunk_elems, sq);
+        const size_t flds = (size_t)select_lds_bytes(pl.filter_cap, (int)pow2_ceil64(k));
         hipLaunchKernelGGL(ex_filter_select_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), flds, stream, fbuf, st, (int)k,
-                           idx_bits, out_vals, out_idx);
+                           idx_bits, pl.filter_cap, out_vals, out_idx);
     };
+    if (pl.filter && select_lds_bytes(pl.filter_cap, (int)pow2_ceil64(k)) > 64 * 1024) {
+        static bool told[64] = {};
+        const hipError_t ea = allow_whole_cu_lds((const void *)ex_filter_select_kernel<ELT>, told);
+        if (ea != hipSuccess) return ea;
+    }
     // Very small k on big inputs: the k-th largest of a sample (every 16th run of 4096 elements), to
     // two digits, is a threshold that at least k elements of the row reach, and about 16 k of them on
     // data without order along the row: one sweep copies them out, instead of one sweep to count the
-    // first digit and one to copy.  A row where more than kFilterCap reach it starts over below; the
+    // first digit and one to copy.  A row where more than the buffer holds reach it starts over below; the
     // passes below then mostly find nothing to do, so they are launches of few workgroups, each with many chunks.
     const bool sample = pl.sample;
     if (sample) {
@@ -996,7 +1015,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     }
     for (int p = 0; p < n_passes; ++p) {
         const bool filter_now = p == 0 && pl.filter && !sample;
-        pass(p, p == 0 && !sample, filter_now ? (uint32_t)kFilterCap : 0u, pl.chunk_elems, 1, sample);
+        pass(p, p == 0 && !sample, filter_now ? (uint32_t)pl.filter_cap : 0u, pl.chunk_elems, 1, sample);
         if (filter_now) copy_out();
     }
     if (k * pl.chunk_elems / n <= 1536)  // expected survivors per chunk
