@@ -581,6 +581,8 @@ def test_exact_long_rows(dtype):
                        workloads.special_values(1, 60000, seed=13, dtype=dtype)])
     run_exact(mixed, 100)
     run_exact(mixed, 1024)
+    run_exact(mixed, 3000)  # few rows: the copy-out path up to k = 4096, with 8192 elements per row
+    run_exact(mixed, 4096)
     # many survivors: partition sort (one wavefront per bin), its bitonic path for crowded bins (k of a
     # million: more than 512 per bin), and rows whose values pile up on a few levels, which fall back to
     # the digit-by-digit sort - all three kinds of row in one call as well
