@@ -116,11 +116,17 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     bytes += m * k * 8;
     // copy-out buffer of the small-k path, as long as it stays modest (256 MB)
     p.filter = k <= kFilterMaxK && m * (int64_t)kFilterCap * 8 <= (256ll << 20);
-    if (!p.filter && k <= kFilterMaxKBig && m <= kNumCU) {
-        // k up to 4096 on few rows: twice the elements, selected in up to 160 KB of LDS (128 x 2^20, k = 4096:
-        // two sweeps instead of four or five)
-        p.filter = true;
-        p.filter_cap = kFilterCapBig;
+    if (!p.filter && k <= kFilterMaxKBig) {
+        // k up to 4096: twice the elements, selected in up to 160 KB of LDS, one row per CU at a time (128 x 2^20,
+        // k = 4096: two sweeps instead of four or five).  With more rows than CUs the selections queue up, about
+        // 50 us per round of rows: then only where the saved sweeps are worth more (384 x 2^19: 600 -> 476 us;
+        // 2048 x 32768 would go from 327 to 526 us).
+        const int64_t es = (dtype == ATK_F32) ? 4 : 2;
+        const int64_t rounds = ceil_div64(m, kNumCU);
+        if (rounds == 1 || (m * n * es > rounds * (120ll << 20) && m * (int64_t)kFilterCapBig * 8 <= (256ll << 20))) {
+            p.filter = true;
+            p.filter_cap = kFilterCapBig;
+        }
     }
     if (p.filter) bytes += m * (int64_t)p.filter_cap * 8;
     {

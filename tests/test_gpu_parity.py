@@ -606,6 +606,13 @@ def test_exact_many_long_rows():
     run_exact(x, 10, rows=[0, 1, 65534, 65535, 65536, 65999])
 
 
+def test_exact_copy_out_more_rows_than_cus():
+    """k up to 4096 with more rows than CUs: the copy-out path is taken when the input is big enough to pay
+    for the rounds of one-row-per-CU selections (here 300 rows of 2^18: two rounds)."""
+    x = workloads.normal_rows(300, 1 << 18, seed=43)
+    run_exact(x, 3000, rows=[0, 1, 255, 256, 257, 299])
+
+
 def test_exact_cfg4():
     x = workloads.config_input("cfg4")
     rows = [0, 1, 64, 127]
