@@ -120,12 +120,17 @@ int64_t atk_stage2_max_candidates(void);
 int64_t atk_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
 int64_t atk_workspace_bytes_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment);
 int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype);
+/* The two parts of exact_topk's scratch, which live in separate pools: *state_bytes (words every kernel leaves
+ * zeroed: histograms, tickets) and *data_bytes (row states, survivors, copy-out buffers).  Each covers every
+ * block of rows the call is run in.  Returns ATK_OK or an error code. */
+int atk_exact_workspace_parts(int64_t m, int64_t n, int64_t k, int dtype, int64_t *state_bytes, int64_t *data_bytes);
 
 /*
  * Writes a one-line, human-readable description of the launch plan the library would use
  * (threads per workgroup, lanes per bucket column, row splits, fused Stage 2, ...) into
  * buf (NUL-terminated, truncated to buflen).  Host only; used by tests and the benchmark log.
- * The plan can be overridden for tuning and tests with the environment variable ATK_PLAN, a comma
+ * The plan can be overridden for tuning and tests with the environment variable ATK_PLAN (read once, when
+ * the library is loaded) or with atk_set_plan_override(), a comma
  * separated list of: T=<threads per workgroup: 64..1024>, S=<workgroups a row is split over>,
  * V=<columns per lane: 1, 2, 4, 8>, P=<lanes of a workgroup sharing a column group: a power of two up to 64>,
  * PK=0 (bf16: no packed queue words), XS=0 / XS=1 (exact_topk with k <= 512: never / also on small
@@ -138,6 +143,9 @@ int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, i
 /* The same for approx_topk_assign (for ATK_CONTIGUOUS: lanes per bucket Gs, workgroups across the buckets, splits). */
 int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
                              char *buf, int64_t buflen);
+/* Replaces the plan override by `spec` (the syntax of ATK_PLAN; NULL or "" = no override).  Host only, process
+ * wide, not synchronised with calls running on other threads: meant for sweeps and tests.  Returns ATK_OK. */
+int atk_set_plan_override(const char *spec);
 
 /*
  * Choosing (b, k_b) (Section 3 and Appendices C-E).  Host only, no HIP call.

@@ -20,5 +20,6 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     plan_describe,
+    set_plan_override,
     strerror,
 )

@@ -66,8 +66,12 @@ def load_library():
     lib.atk_workspace_bytes_assign.restype = i64
     lib.atk_exact_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.atk_exact_workspace_bytes.restype = i64
+    lib.atk_exact_workspace_parts.argtypes = [i64, i64, i64, ci, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.atk_exact_workspace_parts.restype = ci
     lib.atk_plan_describe.argtypes = [i64, i64, i64, i64, i64, ci, ctypes.c_char_p, i64]
     lib.atk_plan_describe.restype = ci
+    lib.atk_set_plan_override.argtypes = [ctypes.c_char_p]
+    lib.atk_set_plan_override.restype = ci
     dbl = ctypes.c_double
     lib.atk_expected_recall.argtypes = [i64, i64, i64]
     lib.atk_expected_recall.restype = dbl
@@ -174,6 +178,11 @@ def plan_describe(m, n, k, b, k_b, dtype=ATK_F32, assignment=ATK_INTERLEAVED) ->
     buf = ctypes.create_string_buffer(512)
     _check(load_library().atk_plan_describe_assign(m, n, k, b, k_b, dtype, assignment, buf, 512))
     return buf.value.decode()
+
+
+def set_plan_override(spec=None) -> None:
+    """Launch-plan override in the syntax of ATK_PLAN ("T=256,S=2"); None removes it.  For sweeps and tests."""
+    _check(load_library().atk_set_plan_override(spec.encode() if spec else None))
 
 
 def expected_recall(k, b, k_b) -> float:

@@ -47,35 +47,48 @@ static int check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b,
 }
 
 // ------------------------------------------------------------------------------------ plan override
-// ATK_PLAN="T=128,S=4,V=2": tuning knobs for sweeps; values are clamped to what the kernels accept.
-static void plan_override(int *T, int *S, int *V) {
-    const char *e = getenv("ATK_PLAN");
-    if (!e) return;
-    const char *p = strstr(e, "T=");
-    if (p && T) {
-        int v = atoi(p + 2);
-        if (v == 64 || v == 128 || v == 256 || v == 512 || v == 1024) *T = v;
+// "T=128,S=4,V=2,...": tuning knobs for sweeps and tests; values the kernels cannot take are dropped here.
+static PlanOverride parse_plan_override(const char *e) {
+    PlanOverride o;
+    memset(&o, 0, sizeof o);
+    if (!e) return o;
+    auto field = [&](const char *name) -> const char * {  // the text behind "name=" at the start of an item
+        const size_t len = strlen(name);
+        for (const char *q = e; (q = strstr(q, name)) != nullptr; q += len)
+            if ((q == e || q[-1] == ',') && q[len] == '=') return q + len + 1;
+        return nullptr;
+    };
+    if (const char *q = field("T")) {
+        const int v = atoi(q);
+        if (v == 64 || v == 128 || v == 256 || v == 512 || v == 1024) o.T = v;
     }
-    p = strstr(e, "S=");
-    if (p && S) {
-        int v = atoi(p + 2);
-        if (v >= 1 && v <= 4096) *S = v;
+    if (const char *q = field("S")) {
+        const int v = atoi(q);
+        if (v >= 1 && v <= 4096) o.S = v;
     }
-    p = strstr(e, "V=");
-    if (p && V) {
-        int v = atoi(p + 2);
-        if (v == 1 || v == 2 || v == 4 || v == 8) *V = v;
+    if (const char *q = field("V")) {
+        const int v = atoi(q);
+        if (v == 1 || v == 2 || v == 4 || v == 8) o.V = v;
     }
+    if (const char *q = field("P")) {
+        const int v = atoi(q);
+        if (v >= 1 && v <= 64 && (v & (v - 1)) == 0) o.P = v;
+    }
+    if (const char *q = field("PK")) o.pk_off = atoi(q) == 0;
+    if (const char *q = field("XS")) o.xs = atoi(q) == 0 ? -1 : 1;
+    if (const char *q = field("XC")) {
+        const int v = atoi(q);
+        if (v >= 1024 && v <= 16384 && (v & (v - 1)) == 0) o.xc = v;
+    }
+    if (const char *q = field("HF")) o.hf = atoi(q) == 0 ? -1 : 1;
+    if (const char *q = field("HQ")) {
+        const int v = atoi(q);
+        if (v >= 1 && v <= 63) o.hq = v;
+    }
+    return o;
 }
-
-// ATK_PLAN="..,PK=0": switches an optional code path off (for tests and sweeps)
-static bool plan_flag_off(const char *name) {
-    const char *e = getenv("ATK_PLAN");
-    if (!e) return false;
-    char key[16];
-    snprintf(key, sizeof key, "%s=0", name);
-    return strstr(e, key) != nullptr;
-}
+static PlanOverride g_plan_override = parse_plan_override(getenv("ATK_PLAN"));  // read once, at load
+const PlanOverride &plan_override() { return g_plan_override; }
 
 // ------------------------------------------------------------------------------------ approx plan
 static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, bool ptr16,
@@ -91,8 +104,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.k_b = (int)k_b;
     p.KB = (int)pow2_ceil(k_b);
     // columns per lane: the default instance for (dtype, KB), or the widest one within V_forced
-    int T_forced = 0, S_forced = 0, V_forced = 0;
-    plan_override(&T_forced, &S_forced, &V_forced);
+    const PlanOverride &ov = plan_override();
+    const int T_forced = ov.T, S_forced = ov.S, V_forced = ov.V;
     // (vector loads need a 16-byte aligned x and b a multiple of V)
     int v_want = !ptr16 ? 1 : V_forced;
     // bf16 queues of 8 and 16 slots over wide bucket layouts, on inputs that give the chip only a wavefront or
@@ -169,18 +182,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int p_want = 1;
     if (p.KB >= 8 && p.G >= T && !T_forced)
         while (p_want < 4 && m * p.G * p_want < 64 * 4 * (int64_t)kNumCU && p.L >= 4 * p_want * 2) p_want <<= 1;
-    bool P_forced = false;
-    {
-        const char *e = getenv("ATK_PLAN");
-        const char *q = e ? strstr(e, "P=") : nullptr;
-        if (q && (q == e || q[-1] == ',')) {
-            const int v = atoi(q + 2);
-            if (v >= 1 && v <= 64 && (v & (v - 1)) == 0) {
-                p_want = v;
-                P_forced = true;
-            }
-        }
-    }
+    const bool P_forced = ov.P != 0;
+    if (P_forced) p_want = ov.P;
 
     // column groups side by side in a workgroup, row phases, LDS areas: for p_want lanes per column group
     int64_t lds = 0;
@@ -294,7 +297,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.S = (int)S;
     p.rows_per_split = (int)rps;
 
-    p.packed = dtype == ATK_BF16 && p.KB >= 4 && p.rows_per_split + 2 < 32768 && !plan_flag_off("PK");
+    p.packed = dtype == ATK_BF16 && p.KB >= 4 && p.rows_per_split + 2 < 32768 && !ov.pk_off;
     p.tail_tpc = tail_lanes_per_column(p.stage2 ? b : std::min<int64_t>(b, (int64_t)p.Gw * p.V), p.T, p.KB, p.S);
     p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
     p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
@@ -336,8 +339,7 @@ int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, in
     p.stage2 = b * k_b > k;
     const int vfull = 16 / es;
     p.V = (ptr16 && n % b == 0 && p.L % vfull == 0) ? vfull : 1;
-    int T_forced = 0, S_forced = 0, V_forced = 0;
-    plan_override(&T_forced, &S_forced, &V_forced);
+    const int T_forced = plan_override().T, S_forced = plan_override().S, V_forced = plan_override().V;
     if (V_forced == 1) p.V = 1;
     const int t_max = max_threads_for_kb(p.KB);
     const int64_t chunks = ceil_div(n, b) / p.V;  // of the longest bucket (V > 1: of every bucket)
@@ -549,6 +551,27 @@ struct FullPlan {
 static const int64_t kExactRowsPerPass = 65535;  // long rows are the y dimension of their grids
 static int64_t align256(int64_t v) { return (v + 255) / 256 * 256; }
 
+// Plan of exact_topk over m rows: `first` is the plan of the first block of rows (all rows when the
+// rows go one per workgroup), and the pool sizes cover every block.  The last block has fewer rows and
+// is planned on its own by run_exact(): with fewer rows it may take paths the full blocks do not (the
+// copy-out buffer, a finer sweep), so its needs are not bounded by the first block's.
+static int make_exact_plans(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *first, int64_t *state_bytes,
+                            int64_t *data_bytes) {
+    int rc = make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, n, k, dtype, first);
+    if (rc == ATK_OK && first->single_wg) rc = make_exact_plan(m, n, k, dtype, first);
+    if (rc != ATK_OK) return rc;
+    *state_bytes = first->state_bytes;
+    *data_bytes = first->scratch_bytes;
+    if (!first->single_wg && m > kExactRowsPerPass && m % kExactRowsPerPass) {
+        ExactPlan last;
+        rc = make_exact_plan(m % kExactRowsPerPass, n, k, dtype, &last);
+        if (rc != ATK_OK) return rc;
+        *state_bytes = std::max(*state_bytes, last.state_bytes);
+        *data_bytes = std::max(*data_bytes, last.scratch_bytes);
+    }
+    return ATK_OK;
+}
+
 static int make_full_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
                           bool ptr16, FullPlan *fp) {
     if (assignment != ATK_INTERLEAVED && assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
@@ -562,22 +585,24 @@ static int make_full_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     fp->state_bytes = fp->s1.scratch_ticket_bytes;
     fp->data_bytes = fp->s1.scratch_lists_bytes;
     if (!fp->two_step) return ATK_OK;
-    rc = make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, nc, k, dtype, &fp->ex);
-    if (rc == ATK_OK && fp->ex.single_wg) rc = make_exact_plan(m, nc, k, dtype, &fp->ex);
+    int64_t ex_state = 0, ex_data = 0;
+    rc = make_exact_plans(m, nc, k, dtype, &fp->ex, &ex_state, &ex_data);
     if (rc != ATK_OK) return rc;
     fp->ex.idx_n = n;
     fp->cand_vals_off = align256(fp->s1.scratch_lists_bytes);
     fp->cand_idx_off = fp->cand_vals_off + align256(m * nc * es);
     fp->ex_data_off = fp->cand_idx_off + align256(m * nc * 4);
     fp->ex_state_off = align256(fp->s1.scratch_ticket_bytes);
-    fp->data_bytes = fp->ex_data_off + fp->ex.scratch_bytes;
-    fp->state_bytes = fp->ex_state_off + fp->ex.state_bytes;
+    fp->data_bytes = fp->ex_data_off + ex_data;
+    fp->state_bytes = fp->ex_state_off + ex_state;
     return ATK_OK;
 }
 
 // exact selection over the rows of x (values) / xi (their indices, or NULL), in blocks of rows
+// state_cap, data_cap: bytes of the two scratch areas (make_exact_plans() sized them for every block)
 static int run_exact(const ExactPlan &first, const void *x, const int32_t *xi, int64_t m, int64_t n, int64_t k, int dtype,
-                     void *out_vals, int32_t *out_idx, void *state, void *data, hipStream_t stream) {
+                     void *out_vals, int32_t *out_idx, void *state, int64_t state_cap, void *data, int64_t data_cap,
+                     hipStream_t stream) {
     const int es = (dtype == ATK_F32) ? 4 : 2;
     if (first.single_wg) {  // one workgroup per row, rows along x: no limit on m
         hipError_t e = launch_exact(first, x, xi, out_vals, out_idx, state, data, stream);
@@ -590,6 +615,7 @@ static int run_exact(const ExactPlan &first, const void *x, const int32_t *xi, i
             if (rc != ATK_OK) return rc;
             pl.idx_n = first.idx_n;
         }
+        if (pl.state_bytes > state_cap || pl.scratch_bytes > data_cap) return ATK_ERR_UNSUPPORTED;  // never: a planning mistake must not become a stray write
         hipError_t e = launch_exact(pl, (const unsigned char *)x + r0 * n * es, xi ? xi + r0 * n : nullptr,
                                     (unsigned char *)out_vals + r0 * k * es, out_idx + r0 * k, state, data, stream);
         if (e != hipSuccess) return hip_fail(e);
@@ -627,7 +653,8 @@ static int run_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b,
     if (e != hipSuccess) return hip_fail(e);
     if (!fp.two_step) return ATK_OK;
     return run_exact(fp.ex, s1_vals, s1_idx, m, b * k_b, k, dtype, out_vals, out_idx,
-                     (unsigned char *)state + fp.ex_state_off, (unsigned char *)data + fp.ex_data_off, (hipStream_t)stream);
+                     (unsigned char *)state + fp.ex_state_off, fp.state_bytes - fp.ex_state_off,
+                     (unsigned char *)data + fp.ex_data_off, fp.data_bytes - fp.ex_data_off, (hipStream_t)stream);
 }
 
 int atk_check_approx(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
@@ -641,7 +668,13 @@ int atk_check_exact(int64_t m, int64_t n, int64_t k, int dtype) {
     int rc = check_common(m, n, k, dtype);
     if (rc != ATK_OK) return rc;
     ExactPlan pl;
-    return make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, n, k, dtype, &pl);
+    int64_t state_bytes = 0, data_bytes = 0;
+    return make_exact_plans(m, n, k, dtype, &pl, &state_bytes, &data_bytes);
+}
+
+int atk_set_plan_override(const char *spec) {
+    g_plan_override = parse_plan_override(spec);
+    return ATK_OK;
 }
 
 int64_t atk_stage2_max_candidates(void) { return kStage2MaxCand; }
@@ -663,10 +696,18 @@ int64_t atk_exact_workspace_bytes(int64_t m, int64_t n, int64_t k, int dtype) {
     int rc = check_common(m, n, k, dtype);
     if (rc != ATK_OK) return rc;
     ExactPlan pl;
-    rc = make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, n, k, dtype, &pl);
-    if (rc == ATK_OK && pl.single_wg) rc = make_exact_plan(m, n, k, dtype, &pl);
+    int64_t state_bytes = 0, data_bytes = 0;
+    rc = make_exact_plans(m, n, k, dtype, &pl, &state_bytes, &data_bytes);
     if (rc != ATK_OK) return rc;
-    return pl.scratch_bytes + pl.state_bytes;
+    return state_bytes + data_bytes;
+}
+
+int atk_exact_workspace_parts(int64_t m, int64_t n, int64_t k, int dtype, int64_t *state_bytes, int64_t *data_bytes) {
+    if (!state_bytes || !data_bytes) return ATK_ERR_NULL_PTR;
+    int rc = check_common(m, n, k, dtype);
+    if (rc != ATK_OK) return rc;
+    ExactPlan pl;
+    return make_exact_plans(m, n, k, dtype, &pl, state_bytes, data_bytes);
 }
 
 int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
@@ -720,15 +761,16 @@ int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *
     if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
     if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
     ExactPlan pl;
-    rc = make_exact_plan(m > kExactRowsPerPass ? kExactRowsPerPass : m, n, k, dtype, &pl);
-    if (rc == ATK_OK && pl.single_wg) rc = make_exact_plan(m, n, k, dtype, &pl);
+    int64_t state_bytes = 0, data_bytes = 0;
+    rc = make_exact_plans(m, n, k, dtype, &pl, &state_bytes, &data_bytes);
     if (rc != ATK_OK) return rc;
     void *state = nullptr, *data = nullptr;
-    hipError_t e = get_pool(kPoolState, (size_t)pl.state_bytes, &state);
+    hipError_t e = get_pool(kPoolState, (size_t)state_bytes, &state);
     if (e != hipSuccess) return hip_fail(e);
-    e = get_pool(kPoolData, (size_t)pl.scratch_bytes, &data);
+    e = get_pool(kPoolData, (size_t)data_bytes, &data);
     if (e != hipSuccess) return hip_fail(e);
-    return run_exact(pl, x, nullptr, m, n, k, dtype, out_vals, out_idx, state, data, (hipStream_t)stream);
+    return run_exact(pl, x, nullptr, m, n, k, dtype, out_vals, out_idx, state, state_bytes, data, data_bytes,
+                     (hipStream_t)stream);
 }
 
 int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream) {

@@ -69,6 +69,18 @@ inline int tail_lanes_per_column(int64_t cols, int T, int KB, int64_t S) {
 }
 constexpr int kEmptyT = 0x7fffffff;       // "no element yet" row marker of a register slot
 
+// Launch-plan overrides for sweeps and tests: the ATK_PLAN environment variable, read once when the
+// library is loaded, or whatever atk_set_plan_override() was last given.  0 / false = not set.
+struct PlanOverride {
+    int T, S, V, P;   // threads per workgroup, row splits, columns per lane, lanes sharing a column group
+    bool pk_off;      // PK=0: no packed bf16 queue words
+    int xs;           // exact_topk sampled threshold: 0 not set, 1 forced on (XS=1), -1 off (XS=0)
+    int xc;           // exact_topk sweep chunk in elements
+    int hf;           // helper/finisher hand-over: 0 not set, 1 forced on where legal (HF=1), -1 off (HF=0)
+    int hq;           // helper's share of the matrix rows in 64ths (HQ=..), 0 not set
+};
+const PlanOverride &plan_override();
+
 // ------------------------------------------------------------------------------------
 // Launch plan of approx_topk (host side, filled by make_plan()).
 //
@@ -213,13 +225,6 @@ __device__ __forceinline__ void store_val(void *out_vals, int64_t pos, uint32_t 
     else
         ((uint16_t *)out_vals)[pos] = (uint16_t)(bits32 >> 16);
 }
-
-// Exact top-k of `count` distinct composites held in LDS at cand[0..count): the k largest,
-// written largest first to out_vals/out_idx of row `row_out` (row stride k).
-// All threads of the workgroup must call it.  sel: LDS, >= next_pow2(k) words; hist: LDS, 256+8 words.
-template <int ELT>
-__device__ void select_sort_write(u64 *cand, int count, int k, u64 *sel, uint32_t *hist, void *out_vals,
-                                  int32_t *out_idx, int64_t row_out);
 
 #endif  // __HIPCC__
 

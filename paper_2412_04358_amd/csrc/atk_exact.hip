@@ -100,12 +100,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     // inputs that do not fill the chip with 16384-element chunks: smaller ones, as long as the sweep stays a launch
     // whose last workgroup per row decides the digit (128 x 65536, k = 64: 55 -> 44 us; 1 x 2^20: 47 -> 34 us)
     while (p.chunk_elems > kExChunkMin && m * ceil_div64(n, p.chunk_elems / 2) <= kExFusedMaxWgs) p.chunk_elems >>= 1;
-    if (const char *e = getenv("ATK_PLAN")) {  // "XC=<elements>": the sweep's chunk, a power of two from 1024 to 16384 (sweeps, tests)
-        if (const char *q = strstr(e, "XC=")) {
-            const int v = atoi(q + 3);
-            if (v >= 1024 && v <= kExChunk && (v & (v - 1)) == 0) p.chunk_elems = v;
-        }
-    }
+    if (plan_override().xc) p.chunk_elems = plan_override().xc;  // "XC=<elements>": the sweep's chunk (sweeps, tests)
     p.chunks = (int)ceil_div64(n, p.chunk_elems);
     if (m > 65535) return ATK_ERR_UNSUPPORTED;  // rows are the grid's y dimension: exact_topk() passes blocks of rows
     // state pool: global histograms (left zero by every call)
@@ -131,8 +126,7 @@ int make_exact_plan(int64_t m, int64_t n, int64_t k, int dtype, ExactPlan *pl) {
     if (p.filter) bytes += m * (int64_t)p.filter_cap * 8;
     {
         // ATK_PLAN="XS=1" takes the sampled threshold on small inputs too, "XS=0" never (tests, sweeps)
-        const char *e = getenv("ATK_PLAN");
-        const bool force = e && strstr(e, "XS=1"), off = e && strstr(e, "XS=0");
+        const bool force = plan_override().xs > 0, off = plan_override().xs < 0;
         const int64_t es = (dtype == ATK_F32) ? 4 : 2;
         p.sample = p.filter && !off && k <= kSampleMaxK && n >= 4 * (int64_t)kSampleChunk * kSampleStride &&
                    (force || m * n * es >= kSampleMinBytes * (k > 256 ? 2 : 1));  // (64 x 2^19 f32, k = 512: 75 us without, 86 with)
@@ -384,7 +378,9 @@ __global__ void __launch_bounds__(kMaxThreads) ex_hist_kernel(const void *x, con
         if (v) __hip_atomic_fetch_add(&gh[i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (!FUSED) return;
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this lane's counts have been acknowledged (a barrier alone does not wait for them)
+    // this lane's counts have been acknowledged (a barrier alone does not wait for them); the memory clobber keeps the
+    // compiler from moving the atomics above past it, or the ticket below before it
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
         const uint32_t ticket = __hip_atomic_fetch_add(&gh[kExBins], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -38,7 +38,6 @@ struct S1Params {
     int nparts;          // partial lists per column left after the wavefront merge
     int lds_xch_off, lds_cand_off;  // byte offsets of the exchange and candidate areas in LDS
     int cb_shift, s_shift, gw_shift;  // log2 of colblocks, S, Gw when those are powers of two, else -1
-    int fence_sync;      // debugging aid: add full agent-scope fences around the ticket
     int tail_tpc_shift;  // log2 of the lanes that share a column in the last workgroup's merge
     int wgs_per_ticket;  // workgroups that share a ticket: a row's (Stage 2), else a column block's row splits
     // contiguous assignment only
@@ -228,12 +227,13 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
         // ------------------------------------------------------------ ticket
         // Cross-workgroup hand-over without cache-wide fences: the lists were written, and are
         // read below, with agent-scope atomic accesses (they go through to memory instead of
-        // staying in one XCD's L2); every lane waits until its own stores have been acknowledged
-        // (a barrier alone does not: inside a workgroup the compiler lets global stores stay in
-        // flight across it), and only after the barrier one lane takes the ticket.  Whoever draws
-        // the last one knows that every other workgroup's lists are complete.
-        if (p.fence_sync) __threadfence();
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+        // staying in one XCD's L2, so there is nothing for a cache write-back or invalidate to do);
+        // every lane waits until its own stores have been acknowledged (a barrier alone does not:
+        // inside a workgroup the compiler lets global stores stay in flight across it), and only
+        // after the barrier one lane takes the ticket.  Whoever draws the last one knows that every
+        // other workgroup's lists are complete.  The wait is an asm statement with a memory clobber,
+        // so the compiler can move neither the stores below it nor the ticket above it.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         uint32_t *flag = (uint32_t *)smem;
         uint32_t *ticket_word = p.tickets + tk * kTicketStride;
@@ -243,7 +243,6 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
         }
         __syncthreads();
         if (flag[0] == 0) return;
-        if (p.fence_sync) __threadfence();
         if (tid == 0)  // ready for the next call
             __hip_atomic_store(ticket_word, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
@@ -901,10 +900,6 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.gw_shift = log2_exact(pl.Gw);
     const uintptr_t ov = (uintptr_t)out_vals, oi = (uintptr_t)out_idx;
     prm.vec_store = ((ov | oi) & 15u) == 0;
-    {
-        const char *e = getenv("ATK_SYNC");
-        prm.fence_sync = (e && strcmp(e, "fence") == 0) ? 1 : 0;
-    }
 #define ATK_CASE(ELT, VV, KK, UU) \
     if (pl.dtype == ELT && pl.V == VV && pl.KB == KK) return launch_one<ELT, VV, KK, UU>(pl, prm, stream);
     ATK_STAGE1_INSTANCES(ATK_CASE)
@@ -951,10 +946,6 @@ hipError_t launch_approx_contig(const Plan &pl, const void *x, void *out_vals, i
     prm.chunks_per_split = pl.chunks_per_split;
     prm.NB = pl.NB;
     prm.rem = (int)(pl.n % pl.b);
-    {
-        const char *e = getenv("ATK_SYNC");
-        prm.fence_sync = (e && strcmp(e, "fence") == 0) ? 1 : 0;
-    }
     if (prm.gs_shift < 0) return hipErrorInvalidValue;
 #define ATK_CASE(ELT, VV, KK, UU) \
     if (pl.dtype == ELT && pl.V == VV && pl.KB == KK) return launch_contig_one<ELT, VV, KK, UU>(pl, prm, stream);

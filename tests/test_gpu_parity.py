@@ -101,10 +101,11 @@ def test_cfg3_large_k_sweep_kb():
 
 
 def test_cfg4_long_rows():
+    """Every row of every case: these are the plans whose workgroups hand lists over through scratch and a ticket,
+    and a fault in the hand-over would hit any row."""
     x = workloads.config_input("cfg4")
-    rows = [0, 1, 17, 63, 64, 126, 127]  # the oracle checks these rows of the full-size run
     for k, b, k_b in workloads.CONFIGS["cfg4"]["cases"]:
-        run_case(x, k, b, k_b, rows=rows, tag="cfg4")
+        run_case(x, k, b, k_b, tag="cfg4")
 
 
 def test_cfg5_attention_scores_bf16():
@@ -121,9 +122,8 @@ def test_vocab_shape_bf16():
 
 def test_kg_shape_bf16():
     x = workloads.config_input("kg")
-    rows = [0, 1, 77, 127]
     for k, b, k_b in workloads.CONFIGS["kg"]["cases"]:
-        run_case(x, k, b, k_b, rows=rows, tag="kg")
+        run_case(x, k, b, k_b, tag="kg")
 
 
 # ------------------------------------------------------------------------------- shapes spanning tiles and tails
@@ -193,9 +193,9 @@ def test_shapes(dtype):
 
 @pytest.mark.parametrize("plan", ["T=64,S=1", "T=64,S=7", "T=128,S=3", "T=256,S=2", "T=256,S=64", "T=512,S=1", "T=1024,S=2", "T=1024,S=5",
                                   "P=2", "P=4", "T=128,P=2,S=3"])
-def test_forced_plans(plan, monkeypatch):
+def test_forced_plans(plan, plan_override):
     """The same results whatever the launch geometry (threads per workgroup, row splits)."""
-    monkeypatch.setenv("ATK_PLAN", plan)
+    plan_override(plan)
     for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (3, 32768, 2048, 2048, 1),
                                            (3, 32768, 128, 64, 2), (3, 32768, 100, 32, 4), (2, 32768, 64, 8, 8),
                                            (2, 32768, 200, 16, 16), (3, 32771, 2048, 2048, 1), (3, 32770, 128, 64, 2),
@@ -220,17 +220,16 @@ def test_column_split_plans(dtype):
         assert (n * es) % 128 == 0
         plan = atk.plan_describe(m, n, k, b, k_b, dt)
         split += " colblocks=1 " not in plan and " direct=0" in plan
-        rows = [0, 1, 63, 64, 127] if m == 128 else None
-        run_case(workloads.normal_rows(m, n, seed=700 + i, dtype=dtype), k, b, k_b, rows=rows, tag="colsplit")
+        run_case(workloads.normal_rows(m, n, seed=700 + i, dtype=dtype), k, b, k_b, tag="colsplit")
     assert split >= 4  # the plans this test is about are the ones the library picks
     run_case(workloads.few_levels(6, 65536, levels=3, seed=720, dtype=dtype), 64, 64, 1, tag="colsplit ties")
     run_case(workloads.special_values(6, 65536, seed=721, dtype=dtype), 128, 128, 1, tag="colsplit specials")
 
 
 @pytest.mark.parametrize("plan", ["P=8", "P=16,T=256", "P=32,T=512,S=3", "P=64,T=512", "P=64,T=256,S=2"])
-def test_forced_column_blocks(plan, monkeypatch):
+def test_forced_column_blocks(plan, plan_override):
     """Narrow column blocks forced on shapes with and without Stage 2, several slots per bucket, ragged rows."""
-    monkeypatch.setenv("ATK_PLAN", plan)
+    plan_override(plan)
     for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (3, 32768, 128, 64, 2),
                                            (2, 32768, 256, 128, 4), (3, 32771, 64, 64, 1), (2, 32776, 128, 128, 1)]):
         for dtype in ["f32", "bf16"]:
@@ -238,9 +237,9 @@ def test_forced_column_blocks(plan, monkeypatch):
 
 
 @pytest.mark.parametrize("lanes", ["V=1", "V=2", "V=4", "V=8"])
-def test_forced_lane_widths(lanes, monkeypatch):
+def test_forced_lane_widths(lanes, plan_override):
     """Every compiled (type, columns per lane, slots) instance gives the same results."""
-    monkeypatch.setenv("ATK_PLAN", lanes)
+    plan_override(lanes)
     for i, (m, n, k, b, k_b) in enumerate([(3, 16384, 2048, 2048, 1), (3, 16384, 64, 64, 1), (3, 16384, 100, 256, 1),
                                            (3, 16384, 2048, 1024, 2), (3, 16384, 128, 64, 2), (3, 16384, 2048, 512, 4),
                                            (3, 16384, 96, 32, 4), (3, 16384, 2048, 256, 8), (2, 16384, 64, 8, 8),
@@ -391,8 +390,8 @@ def test_contiguous_assignment(dtype):
 
 
 @pytest.mark.parametrize("plan", ["T=64", "T=128,S=3", "T=256,S=16", "T=1024,S=2", "V=1"])
-def test_contiguous_forced_plans(plan, monkeypatch):
-    monkeypatch.setenv("ATK_PLAN", plan)
+def test_contiguous_forced_plans(plan, plan_override):
+    plan_override(plan)
     for i, (m, n, k, b, k_b) in enumerate([(3, 32768, 64, 64, 1), (3, 32768, 64, 256, 1), (2, 1 << 17, 16, 4, 4),
                                            (2, 1 << 17, 10, 2, 8), (3, 32768, 2048, 2048, 1)]):
         for dtype in ["f32", "bf16"]:
@@ -430,12 +429,12 @@ def test_interleaved_flag_is_approx_topk():
 
 
 @pytest.mark.parametrize("plan", ["", "PK=0", "T=64,S=1"])
-def test_bf16_packed_queues(plan, monkeypatch):
+def test_bf16_packed_queues(plan, plan_override):
     """bf16 with k_b >= 3 keeps (key, row) in one 32-bit word per slot when a lane's share of the row
     is short enough; the results are the same with that path switched off, and on rows whose
     single split is too long for it."""
     if plan:
-        monkeypatch.setenv("ATK_PLAN", plan)
+        plan_override(plan)
     cases = [(3, 16384, 2048, 1024, 2), (3, 16384, 96, 32, 4), (2, 16384, 64, 8, 8), (2, 16392, 64, 64, 3),
              (4, 65536, 16384, 1024, 16), (2, 300000, 16, 4, 4), (2, 300001, 10, 2, 5), (1, 1 << 20, 64, 16, 4)]
     for i, (m, n, k, b, k_b) in enumerate(cases):
@@ -478,6 +477,87 @@ def test_repeatable():
         assert np.array_equal(cur[0], ref[0]) and np.array_equal(cur[1], ref[1])
 
 
+def _repeat_against_oracle(x_cpu, call, oracle_result, runs, tag, between):
+    """`runs` calls of call(xg) -> (vals, idx), other launches in between, each run compared with the oracle
+    on every row; stops at the first mismatch."""
+    ov, oi = oracle_result
+    ovb = ov.view(np.uint32) if ov.dtype == np.float32 else ov
+    xg = x_cpu.cuda()
+    for run in range(runs):
+        vals, idx = call(xg)
+        between(run)
+        torch.cuda.synchronize()
+        gi, gv = idx.cpu().numpy(), as_bits(vals)
+        if not (np.array_equal(gi, oi) and np.array_equal(gv, ovb)):
+            bad = np.argwhere(gi != oi)
+            raise AssertionError("%s: run %d of %d differs from the oracle in %d places (rows %s)" % (
+                tag, run, runs, len(bad), np.unique(bad[:, 0])[:16].tolist()))
+    del xg
+
+
+HAND_OVER_CASES = [
+    # (tag, input, (k, b, k_b), plan override, what the plan must say)
+    ("cfg4 b=1024 Stage 2", ("cfg4",), (64, 1024, 1), None, "scratch=1"),
+    ("cfg4 b=128 k_b=8 Stage 2", ("cfg4",), (64, 128, 8), None, "scratch=1"),
+    ("8 x 2^20 b=64", (8, 1 << 20, 51, "f32"), (64, 64, 1), None, "scratch=1"),
+    ("3 x 2^18 b=256 S=64", (3, 1 << 18, 52, "f32"), (64, 256, 1), "S=64", "S=64 "),
+    ("5 x 2^18 bf16 b=64 k_b=4 S=16 P=4", (5, 1 << 18, 53, "bf16"), (100, 64, 4), "S=16,P=4", "S=16 "),
+    ("cfg2 b=512 two workgroups per row", ("cfg2",), (64, 512, 1), "S=2", "scratch=1"),
+]
+
+
+@pytest.mark.parametrize("case", HAND_OVER_CASES, ids=[c[0] for c in HAND_OVER_CASES])
+def test_repeat_runs_on_hand_over_plans(case, plan_override):
+    """Plans whose workgroups hand partial lists over through global scratch and a ticket (Appendix A:
+    the per-thread queues are merged once, here also across workgroups): 20 runs each with other
+    launches in between, every run compared with the oracle on every row."""
+    tag, inp, (k, b, k_b), plan, must = case
+    x = workloads.config_input(inp[0]) if len(inp) == 1 else workloads.normal_rows(inp[0], inp[1], seed=inp[2], dtype=inp[3])
+    dt = atk.ATK_F32 if x.dtype == torch.float32 else atk.ATK_BF16
+    other = workloads.normal_rows(16, 32768, seed=54).cuda()
+    expect = oracle.approx_topk(workloads.as_numpy_bits(x), k, b, k_b, threads=THREADS)
+
+    def between(run):  # other shapes on the same scratch pool and tickets; the override is for the case alone
+        plan_override(None)
+        atk.approx_topk(other, 64, 64 << (run % 3), 1)
+        atk.exact_topk(other, 64)
+        plan_override(plan)
+
+    plan_override(plan)
+    described = atk.plan_describe(x.shape[0], x.shape[1], k, b, k_b, dt)
+    print("repeat %s plan=[%s]" % (tag, described), flush=True)
+    assert must in described + " ", described
+    _repeat_against_oracle(x, lambda xg: atk.approx_topk(xg, k, b, k_b), expect, 20, tag, between)
+
+
+@pytest.mark.parametrize("shape", [(128, 65536, 64), (1, 1 << 20, 1000), (128, 65536, 16384)])
+def test_repeat_runs_of_exact_topk(shape):
+    """exact_topk's sweeps whose last workgroup per row decides the digit (a ticket after the counts are
+    acknowledged): 20 runs with other launches in between, every run compared with the oracle."""
+    m, n, k = shape
+    x = workloads.normal_rows(m, n, seed=55)
+    other = workloads.normal_rows(16, 32768, seed=56).cuda()
+    expect = oracle.exact_topk(workloads.as_numpy_bits(x), k, threads=THREADS)
+
+    def between(run):
+        atk.approx_topk(other, 64, 64 << (run % 3), 1)
+
+    _repeat_against_oracle(x, lambda xg: atk.exact_topk(xg, k), expect, 20, "exact %s" % (shape,), between)
+
+
+def test_cfg2_cfg3_bf16_and_small_batches():
+    """The bf16 versions of the two 128 x 65536 sweeps (Appendix B.1's bfloat16 figure), Stage 2 included, and
+    the same parameters on batches of 1, 8 and 32 rows (Section 5 leaves the batch size open)."""
+    xb = workloads.normal_rows(128, 65536, seed=0, dtype="bf16")
+    for k, b, k_b in workloads.CONFIGS["cfg2"]["cases"] + workloads.CONFIGS["cfg3"]["cases"]:
+        run_case(xb, k, b, k_b, tag="bf16 cfg2/cfg3")
+    for m in (1, 8, 32):
+        for dtype in ("f32", "bf16"):
+            x = workloads.normal_rows(m, 65536, seed=60 + m, dtype=dtype)
+            for k, b, k_b in workloads.CONFIGS["cfg2"]["cases"] + workloads.CONFIGS["cfg3"]["cases"]:
+                run_case(x, k, b, k_b, tag="m=%d" % m)
+
+
 # ------------------------------------------------------------------------------- exact_topk
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_exact_small_rows(dtype):
@@ -490,13 +570,13 @@ def test_exact_small_rows(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_exact_sampled_threshold(dtype, monkeypatch):
+def test_exact_sampled_threshold(dtype, plan_override):
     """Very small k on big inputs: the threshold is first guessed from a sample of the row (every 16th
     run of 4096 elements) and everything that reaches it is copied out in one sweep.  Rows where too
     much reaches it (ties, few levels, an ascending row whose sample misses the large values) start
     over digit by digit; finished and restarted rows share one call.  XS=1 takes that path on inputs
     below the size from which the library would choose it."""
-    monkeypatch.setenv("ATK_PLAN", "XS=1")
+    plan_override("XS=1")
     n = (1 << 19) + 333
     for k in (1, 64, 128):
         run_exact(workloads.normal_rows(3, n, seed=600 + k, dtype=dtype), k)
@@ -549,11 +629,11 @@ def test_input_off_a_vector_boundary(dtype):
 
 
 @pytest.mark.parametrize("chunk", [1024, 4096, 8192, 16384])
-def test_exact_sweep_chunks(chunk, monkeypatch):
+def test_exact_sweep_chunks(chunk, plan_override):
     """The sweeps of the long-row path take 4096 to 16384 elements of a row per workgroup, by the size of
     the input; XC=<elements> fixes it.  Every size gives the same results: rows with a ragged last chunk,
     the copy-out path, the digit descent, and many survivors per chunk (the second sweep of the collect step)."""
-    monkeypatch.setenv("ATK_PLAN", "XC=%d" % chunk)
+    plan_override("XC=%d" % chunk)
     for dtype in ("f32", "bf16"):
         run_exact(workloads.normal_rows(3, 70001, seed=700 + chunk % 7, dtype=dtype), 64)
         run_exact(workloads.normal_rows(2, 50000, seed=701, dtype=dtype), 3000)
@@ -601,23 +681,25 @@ def test_exact_long_rows(dtype):
 
 
 def test_exact_many_long_rows():
-    """More long rows than a grid dimension holds: they go through in blocks of rows."""
+    """More long rows than a grid dimension holds: they go through in blocks of rows.  The last block (465 rows)
+    is planned on its own and takes the copy-out buffer, which the scratch of the call has to cover."""
     x = workloads.normal_rows(66000, 9000, seed=41)  # 9000 f32 per row do not fit 64 KB of LDS
-    run_exact(x, 10, rows=[0, 1, 65534, 65535, 65536, 65999])
+    assert atk.load_library().atk_exact_workspace_bytes(66000, 9000, 10, atk.ATK_F32) >= \
+        atk.load_library().atk_exact_workspace_bytes(465, 9000, 10, atk.ATK_F32)
+    run_exact(x, 10, rows=list(range(0, 65535, 4099)) + [65534] + list(range(65535, 66000)))
 
 
 def test_exact_copy_out_more_rows_than_cus():
     """k up to 4096 with more rows than CUs: the copy-out path is taken when the input is big enough to pay
     for the rounds of one-row-per-CU selections (here 300 rows of 2^18: two rounds)."""
     x = workloads.normal_rows(300, 1 << 18, seed=43)
-    run_exact(x, 3000, rows=[0, 1, 255, 256, 257, 299])
+    run_exact(x, 3000)
 
 
 def test_exact_cfg4():
     x = workloads.config_input("cfg4")
-    rows = [0, 1, 64, 127]
-    run_exact(x, 64, rows=rows)
-    run_exact(x, 1 << 18, rows=rows)
+    run_exact(x, 64)
+    run_exact(x, 1 << 18)
 
 
 def test_b1_equals_exact():

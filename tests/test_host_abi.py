@@ -191,20 +191,20 @@ def test_assign_argument_checks(lib):
     assert lib.atk_plan_describe_assign(4, 4096, 64, 64, 1, 0, 0, buf, 256) == OK and buf.value.startswith(b"V=")
 
 
-def test_plan_override_env(lib, monkeypatch):
-    monkeypatch.setenv("ATK_PLAN", "T=64,S=3")
+def test_plan_override(lib, plan_override):
+    plan_override("T=64,S=3")
     p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
     assert p["T"] == 64 and p["S"] == 3
-    monkeypatch.setenv("ATK_PLAN", "T=1024")
+    plan_override("T=1024")
     p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
     assert p["T"] == 1024
-    monkeypatch.setenv("ATK_PLAN", "V=1")
+    plan_override("V=1")
     p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
     assert p["V"] == 1
-    monkeypatch.setenv("ATK_PLAN", "V=4")
+    plan_override("V=4")
     p = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 4))
     assert p["V"] == 4
-    monkeypatch.delenv("ATK_PLAN")
+    plan_override(None)
     q = parse_plan(atk.plan_describe(4, 1 << 16, 64, 64, 1))
     assert q["T"] in (256, 512)
 
@@ -225,6 +225,60 @@ def test_workspace_bytes(lib):
     assert lib.atk_workspace_bytes_assign(1, 1 << 20, 64, 8, 8, 0, 1) == pc["scratch_bytes"] > 0
     assert lib.atk_workspace_bytes_assign(128, 65536, 16384, 16384, 1, 0, 1) == 0
     assert lib.atk_workspace_bytes_assign(128, 65536, 64, 64, 1, 0, 5) == PARAMS
+
+
+def test_scratch_covers_every_block_of_rows(lib):
+    """More long rows than a grid dimension holds go through in blocks of 65535 rows, and the last, smaller block
+    is planned on its own: with fewer rows it may switch on buffers the full blocks do not use (the copy-out
+    buffer of small k).  The scratch of the whole call must cover every block's plan."""
+    block = 65535
+
+    def parts(m, n, k, dt):
+        st, da = ctypes.c_int64(0), ctypes.c_int64(0)
+        assert lib.atk_exact_workspace_parts(m, n, k, dt, ctypes.byref(st), ctypes.byref(da)) == OK
+        assert st.value + da.value == lib.atk_exact_workspace_bytes(m, n, k, dt)
+        return st.value, da.value
+
+    for dt in (0, 1):
+        for (n, k) in [(9000, 10), (9000, 700), (20000, 64), (20000, 3000), (9000, 4096), (40000, 1), (9000, 9000)]:
+            full = parts(block, n, k, dt)
+            assert full[0] > 0 and full[1] > 0
+            for rem in (1, 255, 256, 257, 465, 4000, 30000, 65534):
+                last = parts(rem, n, k, dt)
+                for blocks in (1, 2):
+                    total = parts(blocks * block + rem, n, k, dt)
+                    for pool in (0, 1):  # state and data live in separate pools: each must cover every block
+                        assert total[pool] >= full[pool] and total[pool] >= last[pool], (dt, n, k, rem, blocks, total, full, last)
+    # the case that showed it: 66000 x 9000 f32, k = 10 - the data of the 465-row last block (with the copy-out
+    # buffer) is twice the first block's
+    assert parts(465, 9000, 10, 0)[1] > parts(block, 9000, 10, 0)[1]
+    assert parts(66000, 9000, 10, 0)[1] >= parts(465, 9000, 10, 0)[1]
+    # Stage 2 over more candidates than one workgroup holds runs the same selection over the candidates
+    for (m, n, k, b, k_b) in [(block + 465, 20000, 10, 9000, 1), (block + 300, 30000, 100, 5000, 2)]:
+        ws = lib.atk_workspace_bytes(m, n, k, b, k_b, 0)
+        assert ws >= lib.atk_exact_workspace_bytes(m - block, b * k_b, k, 0) + m * b * k_b * 8
+        assert ws >= lib.atk_exact_workspace_bytes(block, b * k_b, k, 0) + m * b * k_b * 8
+
+
+def test_plan_override_is_read_from_the_environment_once():
+    """ATK_PLAN is parsed when the library is loaded, not on every call: a fresh process sees it,
+    a change of the variable afterwards does nothing, atk_set_plan_override() replaces it."""
+    import subprocess
+    import sys
+
+    code = ("import os, paper_2412_04358_amd as atk\n"
+            "a = atk.plan_describe(4, 65536, 64, 64, 1)\n"
+            "os.environ['ATK_PLAN'] = 'T=1024'\n"
+            "b = atk.plan_describe(4, 65536, 64, 64, 1)\n"
+            "atk.set_plan_override('T=128')\n"
+            "c = atk.plan_describe(4, 65536, 64, 64, 1)\n"
+            "atk.set_plan_override(None)\n"
+            "d = atk.plan_describe(4, 65536, 64, 64, 1)\n"
+            "print(' T=64 ' in a, a == b, ' T=128 ' in c, ' T=64 ' in d or ' T=128 ' in d)\n")
+    env = dict(os.environ, ATK_PLAN="T=64,S=2", PYTHONPATH=ROOT)
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, cwd=ROOT)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.split() == ["True", "True", "True", "False"], out.stdout
 
 
 # ----------------------------------------------------------------------------- choosing (b, k_b)
