@@ -55,7 +55,8 @@ enum {
     ATK_ERR_UNSUPPORTED = -4, /* legal for the method, not implemented here (see each function) */
     ATK_ERR_DTYPE = -5,       /* dtype is neither ATK_F32 nor ATK_BF16 */
     ATK_ERR_HIP = -6,         /* a HIP runtime call failed; see atk_last_hip_error() */
-    ATK_ERR_ALIGN = -7        /* a pointer is not aligned to its element size */
+    ATK_ERR_ALIGN = -7,       /* a pointer is not aligned to its element size */
+    ATK_ERR_WORKSPACE = -8    /* approx_topk_noalloc: the call needs more scratch than its fixed array holds */
 };
 
 /* Largest supported k_b (per-lane insertion buffers live in registers). */
@@ -93,6 +94,25 @@ int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64
  */
 int approx_topk_assign(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
                        int assignment, void *out_vals, int32_t *out_idx, void *stream);
+
+/*
+ * approx_topk for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as approx_topk, but the
+ * scratch of plans whose workgroups hand partial lists over (few rows of long rows; Stage 2 over rows split
+ * between workgroups) is a fixed array of ATK_NOALLOC_SCRATCH_BYTES inside the library's code object, one
+ * per device, held until the process ends: the call allocates and frees nothing, and never synchronises.
+ *   - ATK_ERR_WORKSPACE when the plan needs more than the array holds (atk_workspace_bytes() tells:
+ *     at most ATK_NOALLOC_STATE_BYTES of tickets and the rest of the array in lists), ATK_ERR_UNSUPPORTED
+ *     when Stage 2 would run over more than atk_stage2_max_candidates() candidates.  Nothing is launched then.
+ *   - The array keeps the last call's contents; the call clears the tickets it uses with a small fill
+ *     kernel before its own launch (one more launch when the plan uses scratch, none otherwise).
+ *   - Every call on a device shares that device's array: calls that may overlap on one device (different
+ *     streams) race, and must be serialised by the caller.  approx_topk uses other memory and may overlap.
+ */
+#define ATK_NOALLOC_STATE_BYTES (256 * 1024)
+#define ATK_NOALLOC_SCRATCH_BYTES (16 * 1024 * 1024 + ATK_NOALLOC_STATE_BYTES)
+int approx_topk_noalloc(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
+                        void *out_vals, int32_t *out_idx, void *stream);
 
 /*
  * Exact top-k of every row, the comparison point (Section 1; the radix-select listing of

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     advise,
     approx_topk,
     approx_topk_assign_raw,
+    approx_topk_noalloc_raw,
     approx_topk_raw,
     estimate_us,
     exact_topk,

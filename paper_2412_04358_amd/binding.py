@@ -44,6 +44,8 @@ def load_library():
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.approx_topk.argtypes = [vp, i64, i64, i64, i64, i64, ci, vp, vp, vp]
     lib.approx_topk.restype = ci
+    lib.approx_topk_noalloc.argtypes = [vp, i64, i64, i64, i64, i64, ci, vp, vp, vp]
+    lib.approx_topk_noalloc.restype = ci
     lib.approx_topk_assign.argtypes = [vp, i64, i64, i64, i64, i64, ci, ci, vp, vp, vp]
     lib.approx_topk_assign.restype = ci
     lib.atk_plan_describe_assign.argtypes = [i64, i64, i64, i64, i64, ci, ci, ctypes.c_char_p, i64]
@@ -106,6 +108,11 @@ def _check(code: int):
 def approx_topk_raw(x_ptr, m, n, k, b, k_b, dtype, out_vals_ptr, out_idx_ptr, stream_ptr=0) -> int:
     """The C call itself on raw device addresses; returns the library's status code."""
     return load_library().approx_topk(x_ptr, m, n, k, b, k_b, dtype, out_vals_ptr, out_idx_ptr, stream_ptr)
+
+
+def approx_topk_noalloc_raw(x_ptr, m, n, k, b, k_b, dtype, out_vals_ptr, out_idx_ptr, stream_ptr=0) -> int:
+    """approx_topk_noalloc on raw device addresses: the caller brings the outputs, the library allocates nothing."""
+    return load_library().approx_topk_noalloc(x_ptr, m, n, k, b, k_b, dtype, out_vals_ptr, out_idx_ptr, stream_ptr)
 
 
 def approx_topk_assign_raw(x_ptr, m, n, k, b, k_b, dtype, assignment, out_vals_ptr, out_idx_ptr, stream_ptr=0) -> int:

@@ -475,6 +475,38 @@ static hipError_t get_pool(int which, size_t bytes, void **out) {
     return hipSuccess;
 }
 
+// ------------------------------------------------------------------------------------ fixed scratch
+// Scratch of the allocation-free entry point: one array per device that the library runs on, part of the
+// code object, so it is there (zero-filled) when the module is loaded and stays until the process ends.
+// The first ATK_NOALLOC_STATE_BYTES hold the tickets, the rest the partial lists.
+static __device__ __align__(256) unsigned char scratch[ATK_NOALLOC_SCRATCH_BYTES];
+// The array's name is a host-side stand-in, not a device address: the address on each device comes from
+// hipGetSymbolAddress, once per device, with that device current, and only that pointer is used afterwards.
+static void *g_fixed_scratch[64];
+static hipError_t fixed_scratch(void **out) {
+    *out = nullptr;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_pool_mu);
+    if (!g_fixed_scratch[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_fixed_scratch[dev] = p;
+    }
+    *out = g_fixed_scratch[dev];
+    return hipSuccess;
+}
+
+// zero fill (a kernel, not a memset: a caller may be capturing the stream into a graph)
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint4 *p, int64_t n_vec) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_vec) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 // ------------------------------------------------------------------------------------ utilities
 __global__ void __launch_bounds__(256) read_ceiling_kernel(const uint4 *x, int64_t n_vec, int64_t slab, u64 *sink) {
     // every workgroup streams one contiguous slab, eight 16-byte loads per lane in flight
@@ -530,6 +562,7 @@ const char *atk_strerror(int code) {
         case ATK_ERR_DTYPE: return "dtype must be ATK_F32 (0) or ATK_BF16 (1)";
         case ATK_ERR_HIP: return "a HIP runtime call failed";
         case ATK_ERR_ALIGN: return "a pointer is not aligned to its element size";
+        case ATK_ERR_WORKSPACE: return "the call needs more scratch than the allocation-free entry point holds (ATK_NOALLOC_SCRATCH_BYTES)";
     }
     return "unknown error code";
 }
@@ -756,6 +789,39 @@ int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *
                void *stream) {
     if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
     int rc = check_common(m, n, k, dtype);
+int approx_topk_noalloc(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
+                        void *out_vals, int32_t *out_idx, void *stream) {
+    if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    const int es = (dtype == ATK_F32) ? 4 : 2;
+    if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
+    if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
+    FullPlan fp;
+    rc = make_full_plan(m, n, k, b, k_b, dtype, ATK_INTERLEAVED, ((uintptr_t)x & 15u) == 0, &fp);
+    if (rc != ATK_OK) return rc;
+    if (fp.two_step) return ATK_ERR_UNSUPPORTED;  // Stage 2 over more candidates than one workgroup holds: approx_topk only
+    if (fp.state_bytes > ATK_NOALLOC_STATE_BYTES || fp.data_bytes > ATK_NOALLOC_SCRATCH_BYTES - ATK_NOALLOC_STATE_BYTES)
+        return ATK_ERR_WORKSPACE;
+    unsigned char *base = nullptr;
+    if (fp.s1.use_scratch) {
+        void *p = nullptr;
+        const hipError_t e = fixed_scratch(&p);
+        if (e != hipSuccess) return hip_fail(e);
+        base = (unsigned char *)p;
+        // The array keeps what the last call left.  Every launch leaves its tickets at zero, but a launch
+        // that was cut short would not have: the tickets of this call are cleared first.
+        const int64_t n_vec = (fp.state_bytes + 15) / 16;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)ceil_div(n_vec, 256)), dim3(256), 0, (hipStream_t)stream,
+                           (uint4 *)base, n_vec);
+        const hipError_t ez = hipGetLastError();
+        if (ez != hipSuccess) return hip_fail(ez);
+    }
+    const hipError_t e = launch_approx(fp.s1, x, out_vals, out_idx, base, base ? base + ATK_NOALLOC_STATE_BYTES : nullptr,
+                                       (hipStream_t)stream);
+    return e == hipSuccess ? ATK_OK : hip_fail(e);
+}
+
     if (rc != ATK_OK) return rc;
     const int es = (dtype == ATK_F32) ? 4 : 2;
     if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;

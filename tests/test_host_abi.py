@@ -81,13 +81,30 @@ def test_calls_reject_before_hip(lib):
     assert lib.atk_sleep(-1, None) == SHAPE
 
 
+def test_noalloc_rejects_what_does_not_fit(lib):
+    """Checked on the host before anything is launched: the pointers are never touched."""
+    fake = 0x1000
+    # 128 rows of 2^22 elements, 1024 buckets of 16 slots, rows split over workgroups: 67 MB of partial lists
+    m, n, k, b, k_b = 128, 1 << 22, 16384, 1024, 16
+    need = lib.atk_workspace_bytes(m, n, k, b, k_b, 0)
+    assert need > (16 << 20), need
+    assert lib.approx_topk_noalloc(fake, m, n, k, b, k_b, 0, fake, fake, None) == -8
+    assert b"scratch" in lib.atk_strerror(-8)
+    # Stage 2 over more candidates than one workgroup holds takes further launches and their buffers
+    assert lib.approx_topk_noalloc(fake, 4, 1 << 16, 64, 1 << 13, 1, 0, fake, fake, None) == UNSUP
+    # the argument checks of approx_topk
+    assert lib.approx_topk_noalloc(None, 4, 4096, 64, 64, 1, 0, fake, fake, None) == -1
+    assert lib.approx_topk_noalloc(fake, 4, 4096, 64, 32, 1, 0, fake, fake, None) == -3
+    assert lib.approx_topk_noalloc(fake + 2, 4, 4096, 64, 64, 1, 0, fake, fake, None) == -7
+
+
 def test_strerror(lib):
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = atk.strerror(code)
         assert s and s != "unknown error code"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 9
     assert atk.strerror(-99) == "unknown error code"
 
 
