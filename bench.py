@@ -47,6 +47,10 @@ def main():
     ap.add_argument("--probe-exact", action="store_true",
                     help="profiler run of exact_topk: 10 calls each on 128 x 65536 f32 (k=64, k=16384) and on "
                          "128 x 2^20 f32 (k=64, k=2^18); no timing")
+    ap.add_argument("--timeline", action="store_true",
+                    help="phase timeline of the fused kernel on the headline workload: per b, 30 launches of the "
+                         "measurement build (atk_trace_approx) on HBM-cold inputs, each right behind an ordinary launch; "
+                         "prints when the first, the median and the last wavefront passed every phase boundary")
     ap.add_argument("--probe", action="store_true",
                     help="short run for hardware-counter passes: 20 copy launches, 20 read-only launches and 20 "
                          "approx_topk launches per b, nothing else")
@@ -135,6 +139,10 @@ def main():
                 launch(ring[i % RING], b)
         torch.cuda.synchronize()
         print(json.dumps({"probe": "done", "copy_bytes": M * N * 4, "launches_each": 20, "b": SWEEP_B}))
+        return
+
+    if args.timeline:
+        print(json.dumps(timeline(atk, lib, torch, dev, ring, out_v, out_i, stream)))
         return
 
     for i in range(args.warmup):
@@ -266,6 +274,52 @@ def main():
     if args.detail:
         out["detail"] = detail(atk, workloads, torch, dev)
     print(json.dumps(out))
+
+
+PHASES = [(0, "start"), (1, "own share of the row read"), (2, "own lists merged / handed on"),
+          (10, "last ticket drawn"), (11, "other workgroups' lists merged"), (3, "Stage 2 begins"),
+          (4, "key range known"), (5, "histogram"), (6, "prefix sums"), (7, "winners filed"), (8, "outputs written"),
+          (9, "end")]
+
+
+def timeline(atk, lib, torch, dev, ring, out_v, out_i, stream, reps=30):
+    """Microseconds after the first wavefront's start at which the first / median / last wavefront passed
+    each phase boundary, averaged over `reps` traced launches per b (100 MHz device wall clock)."""
+    import numpy as np
+
+    res = {}
+    for b in SWEEP_B:
+        nbytes = lib.atk_trace_bytes(M, N, K, b, 1, atk.ATK_F32)
+        assert nbytes > 0, nbytes
+        tr = torch.zeros(nbytes // 8, dtype=torch.int64, device=dev)
+        acc = {}
+        for rep in range(reps):
+            tr.zero_()
+            rc = atk.approx_topk_raw(ring[(2 * rep) % RING].data_ptr(), M, N, K, b, 1, atk.ATK_F32, out_v.data_ptr(),
+                                     out_i.data_ptr(), stream)
+            assert rc == 0, atk.strerror(rc)
+            rc = lib.atk_trace_approx(ring[(2 * rep + 1) % RING].data_ptr(), M, N, K, b, 1, atk.ATK_F32, out_v.data_ptr(),
+                                      out_i.data_ptr(), tr.data_ptr(), nbytes, stream)
+            assert rc == 0, atk.strerror(rc)
+            torch.cuda.synchronize()
+            t = tr.cpu().numpy().reshape(-1, 16).astype(np.int64)
+            t = t[t[:, 0] != 0]  # wavefronts that ran
+            t0 = t[:, 0].min()
+            for ph, _ in PHASES:
+                v = t[:, ph]
+                v = v[v != 0]
+                if v.size:
+                    us = (v - t0) / 100.0
+                    acc.setdefault(ph, []).append((float(us.min()), float(np.median(us)), float(us.max()), int(v.size)))
+        rows = {}
+        for ph, name in PHASES:
+            if ph in acc:
+                a = np.array(acc[ph])
+                rows[name] = {"first_us": round(a[:, 0].mean(), 2), "median_us": round(a[:, 1].mean(), 2),
+                              "last_us": round(a[:, 2].mean(), 2), "wavefronts": int(a[:, 3].mean())}
+        res["b=%d" % b] = {"plan": atk.plan_describe(M, N, K, b, 1), "phases": rows}
+    return {"timeline": res, "reps": reps, "clock": "100 MHz device wall clock, 10 ns steps",
+            "workload": "cfg2: m=128 n=65536 f32 k=64 k_b=1, inputs from a 403 MB ring (HBM-cold)"}
 
 
 def _time_us(torch, launch, reps, warm=5):

@@ -202,8 +202,24 @@ int atk_advise(int64_t m, int64_t n, int64_t k, int dtype, double min_recall, in
  *   which is what hardware traffic counters are scaled against.
  * atk_sleep: a kernel that spins for about `microseconds` (one wave), used to queue work
  *   behind it so that host launch latency stays out of event timings.
+ * atk_trace_approx: approx_topk (same arguments and results) run by a measurement build of the fused kernel in
+ *   which lane 0 of every wavefront stores the device's 100 MHz wall clock at the phase boundaries of the
+ *   call: trace[(workgroup * ATK_TRACE_WAVES + wavefront) * ATK_TRACE_PHASES + phase], 64-bit words, 0 where a
+ *   wavefront never passed.  Phases: 0 start, 1 own share of the row read, 2 own lists merged and handed on,
+ *   10 last ticket drawn, 11 other workgroups' lists merged, 3 Stage 2 begins, 4 key range known, 5 histogram,
+ *   6 prefix sums, 7 possible winners filed by bin, 8 outputs written, 9 end; words 12 and 13 hold the
+ *   wavefront's HW_ID and XCC_ID hardware registers (which CU of which XCD it ran on).  The caller zero-fills `trace`
+ *   (device, atk_trace_bytes() bytes for these arguments).  Only the k_b = 1 kernels with 16-byte loads
+ *   (b a multiple of 4 in f32, of 8 in bf16) and a fused Stage 2 have this build: ATK_ERR_UNSUPPORTED /
+ *   ATK_ERR_HIP otherwise.  The timestamps cost a few stores per wavefront; timings of approx_topk itself
+ *   are taken without them.
  */
 #define ATK_CEILING_SINK_BYTES 65536
+#define ATK_TRACE_WAVES 16
+#define ATK_TRACE_PHASES 16
+int64_t atk_trace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
+int atk_trace_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, void *out_vals,
+                     int32_t *out_idx, void *trace, int64_t trace_bytes, void *stream);
 int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream);
 int atk_copy(void *dst, const void *src, int64_t bytes, void *stream);
 int atk_sleep(int64_t microseconds, void *stream);

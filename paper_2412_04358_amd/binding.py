@@ -82,6 +82,10 @@ def load_library():
     lib.atk_advise.argtypes = [i64, i64, i64, ci, dbl, ctypes.POINTER(i64), ctypes.POINTER(i64),
                                ctypes.POINTER(dbl), ctypes.POINTER(dbl)]
     lib.atk_advise.restype = ci
+    lib.atk_trace_bytes.argtypes = [i64, i64, i64, i64, i64, ci]
+    lib.atk_trace_bytes.restype = i64
+    lib.atk_trace_approx.argtypes = [vp, i64, i64, i64, i64, i64, ci, vp, vp, vp, i64, vp]
+    lib.atk_trace_approx.restype = ci
     lib.atk_read_ceiling.argtypes = [vp, i64, vp, vp]
     lib.atk_read_ceiling.restype = ci
     lib.atk_copy.argtypes = [vp, vp, i64, vp]

@@ -75,12 +75,16 @@ static PlanOverride parse_plan_override(const char *e) {
         if (v >= 1 && v <= 64 && (v & (v - 1)) == 0) o.P = v;
     }
     if (const char *q = field("PK")) o.pk_off = atoi(q) == 0;
+    if (const char *q = field("LM")) o.lm_off = atoi(q) == 0;
+    if (const char *q = field("LN")) o.ln_off = atoi(q) == 0;
     if (const char *q = field("XS")) o.xs = atoi(q) == 0 ? -1 : 1;
     if (const char *q = field("XC")) {
         const int v = atoi(q);
         if (v >= 1024 && v <= 16384 && (v & (v - 1)) == 0) o.xc = v;
     }
     if (const char *q = field("HF")) o.hf = atoi(q) == 0 ? -1 : 1;
+    if (const char *q = field("HT")) o.ht = atoi(q);
+    if (const char *q = field("SL")) o.sl = atoi(q);
     if (const char *q = field("HQ")) {
         const int v = atoi(q);
         if (v >= 1 && v <= 63) o.hq = v;
@@ -92,7 +96,7 @@ const PlanOverride &plan_override() { return g_plan_override; }
 
 // ------------------------------------------------------------------------------------ approx plan
 static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, bool ptr16,
-                             Plan *pl) {
+                             Plan *pl, bool allow_pair = true) {
     const int es = (dtype == ATK_F32) ? 4 : 2;
     Plan p;
     memset(&p, 0, sizeof p);
@@ -311,11 +315,57 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         p.lds_bytes = (int)(16 + (lds_xch > lds_s2 ? lds_xch : lds_s2));
     }
 
+    // One slot per bucket and no hand-over through memory: the lanes meet in LDS by atomic maximum, in the
+    // candidate array itself (no exchange area); Stage 2's tables sit behind it.
+    p.lds_max = p.KB == 1 && !p.use_scratch && !p.direct && !ov.lm_off;
+    if (p.lds_max) {
+        const int64_t wcols = std::min<int64_t>(b, (int64_t)p.Gw * p.V);
+        p.lds_cand_off = 16;
+        p.lds_xch_off = 16;
+        p.lds_bytes = (int)(16 + (p.stage2 ? select_lds_bytes(b, (int)pow2_ceil(k)) : ceil_div(wcols * 8, 16) * 16));
+    }
     // one ticket per row with Stage 2, else one per (row, column block)
     p.scratch_ticket_bytes = p.use_scratch ? m * (p.stage2 ? 1 : p.colblocks) * kTicketStride * 4 : 0;
     p.scratch_lists_bytes = p.use_scratch ? m * p.S * b * k_b * 8 : 0;
     p.grid = m * p.S * p.colblocks;
     if (p.grid >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
+    // Stage 2's short form takes its bins' lower end from the merge: tight when some wavefront covers every column
+    // (its minimum bounds the smallest candidate), else only as tight as the smallest value any lane holds -
+    // good enough once every lane has seen a few dozen rows
+    p.bound_ok = p.lds_max && p.stage2 && (p.Gw <= kWave || p.L / p.P >= 24);
+    // Rows of whole, aligned 16-byte vectors with one slot per bucket and one workgroup per row or column
+    // block: the lean kernels (same mapping, nothing else in the kernel).
+    p.lean = p.lds_max && ptr16 && p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && p.S == 1 && p.T <= 512 && !ov.ln_off;
+    p.pair_rows = 0;
+    if (p.lean && p.stage2 && ov.sl && ov.sl >= p.Gw && ov.sl <= p.T) p.P = ov.sl / p.Gw;  // SL=<lanes that stream> (sweeps)
+    if (p.lean && p.stage2 && p.colblocks == 1 && allow_pair && ov.hf >= 0 &&
+        (ov.hf > 0 || (2 * m <= (int64_t)kNumCU && n * es >= (128 << 10) && b <= 512))) {
+        // Two workgroups per row (helper + finisher, see atk_lean.hip) while that still leaves every workgroup a CU of
+        // its own, on rows long enough to be worth a second CU.  What the memory system likes is four streaming
+        // wavefronts per CU on all CUs (128 x 65536 f32: 256 workgroups of 256 lanes have their rows in 1.1 us before
+        // 128 of 512 do, and 256 of 512 are slower than either), so the pair streams with 256 lanes per workgroup: up to
+        // 256 buckets in workgroups of 256 lanes with the rows split in half (b = 128: 9.9 -> 9.1 us, b = 256: 10.0 ->
+        // 9.4 us), up to 512 buckets in workgroups of 512 lanes (Stage 2 wants a lane per candidate) of which 256 stream,
+        // the helper taking 30/64 (10.2 -> 9.9 us); beyond that Stage 2 outweighs what the second CU saves.
+        int t_pair = b <= 256 ? 256 : 512, lanes = 256, share = b <= 256 ? 32 : 30;
+        if (ov.ht && ov.ht % kWave == 0 && ov.ht <= 512) t_pair = ov.ht;
+        if (ov.sl) lanes = ov.sl;
+        if (ov.hq) share = ov.hq;
+        if (lanes > t_pair) lanes = t_pair;
+        if (t_pair >= p.Gw && lanes >= p.Gw) {
+            const int P = lanes / p.Gw;
+            const int64_t unit = P;
+            const int64_t lh = p.L * share / 64 / unit * unit;
+            if (lh > 0 && p.L - lh >= unit && b <= (int64_t)kBkSlots * t_pair && 2 * m < (1ll << 31)) {
+                p.T = t_pair;
+                p.P = P;
+                p.pair_rows = (int)lh;
+                p.grid = 2 * m;
+                p.scratch_ticket_bytes = m * b * 8;  // the mailbox: one composite per bucket, zero between calls
+                p.bound_ok = true;                   // (the mailbox is the bound)
+            }
+        }
+    }
     *pl = p;
     return ATK_OK;
 }
@@ -606,14 +656,14 @@ static int make_exact_plans(int64_t m, int64_t n, int64_t k, int dtype, ExactPla
 }
 
 static int make_full_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
-                          bool ptr16, FullPlan *fp) {
+                          bool ptr16, FullPlan *fp, bool allow_pair = true) {
     if (assignment != ATK_INTERLEAVED && assignment != ATK_CONTIGUOUS) return ATK_ERR_BAD_PARAMS;
     const int es = (dtype == ATK_F32) ? 4 : 2;
     const int64_t nc = b * k_b;
     fp->two_step = nc > k && nc > kStage2MaxCand;
     const int64_t k1 = fp->two_step ? nc : k;  // two steps: Stage 1 writes all its candidates, bucket by bucket
     int rc = (assignment == ATK_CONTIGUOUS) ? make_contig_plan(m, n, k1, b, k_b, dtype, ptr16, &fp->s1)
-                                            : make_plan_aligned(m, n, k1, b, k_b, dtype, ptr16, &fp->s1);
+                                            : make_plan_aligned(m, n, k1, b, k_b, dtype, ptr16, &fp->s1, allow_pair);
     if (rc != ATK_OK) return rc;
     fp->state_bytes = fp->s1.scratch_ticket_bytes;
     fp->data_bytes = fp->s1.scratch_lists_bytes;
@@ -657,7 +707,7 @@ static int run_exact(const ExactPlan &first, const void *x, const int32_t *xi, i
 }
 
 static int run_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, int assignment,
-                      void *out_vals, int32_t *out_idx, void *stream) {
+                      void *out_vals, int32_t *out_idx, void *stream, void *trace = nullptr, int64_t trace_bytes = 0) {
     if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
     int rc = check_approx(m, n, k, b, k_b, dtype);
     if (rc != ATK_OK) return rc;
@@ -668,6 +718,10 @@ static int run_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b,
     FullPlan fp;
     rc = make_full_plan(m, n, k, b, k_b, dtype, assignment, ((uintptr_t)x & 15u) == 0, &fp);
     if (rc != ATK_OK) return rc;
+    if (trace) {  // measurement build: the lean kernels alone, and room for every wavefront's timestamps
+        if (fp.two_step || assignment != ATK_INTERLEAVED || !fp.s1.lean) return ATK_ERR_UNSUPPORTED;
+        if (trace_bytes < fp.s1.grid * kTraceWaves * kTracePhases * 8 || fp.s1.T > kTraceWaves * kWave) return ATK_ERR_BAD_SHAPE;
+    }
     void *state = nullptr, *data = nullptr;
     hipError_t e = get_pool(kPoolState, (size_t)fp.state_bytes, &state);
     if (e != hipSuccess) return hip_fail(e);
@@ -681,6 +735,8 @@ static int run_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b,
     }
     if (assignment == ATK_CONTIGUOUS)
         e = launch_approx_contig(fp.s1, x, s1_vals, s1_idx, state, data, (hipStream_t)stream);
+    else if (fp.s1.lean)
+        e = launch_approx_lean(fp.s1, x, s1_vals, s1_idx, state, (hipStream_t)stream, trace);
     else
         e = launch_approx(fp.s1, x, s1_vals, s1_idx, state, data, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
@@ -763,10 +819,10 @@ int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     else
         snprintf(buf, (size_t)buflen,
                  "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
-                 "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d",
+                 "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d lean=%d pair_rows=%d",
                  pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid, stage2,
                  (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
-                 (long long)(fp.state_bytes + fp.data_bytes), (int)pl.packed);
+                 (long long)(fp.state_bytes + fp.data_bytes), (int)pl.packed, (int)pl.lean, pl.pair_rows);
     return ATK_OK;
 }
 
@@ -785,10 +841,6 @@ int approx_topk(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64
     return run_approx(x, m, n, k, b, k_b, dtype, ATK_INTERLEAVED, out_vals, out_idx, stream);
 }
 
-int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *out_vals, int32_t *out_idx,
-               void *stream) {
-    if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
-    int rc = check_common(m, n, k, dtype);
 int approx_topk_noalloc(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype,
                         void *out_vals, int32_t *out_idx, void *stream) {
     if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
@@ -798,7 +850,8 @@ int approx_topk_noalloc(const void *x, int64_t m, int64_t n, int64_t k, int64_t 
     if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
     if ((uintptr_t)out_idx & 3u) return ATK_ERR_ALIGN;
     FullPlan fp;
-    rc = make_full_plan(m, n, k, b, k_b, dtype, ATK_INTERLEAVED, ((uintptr_t)x & 15u) == 0, &fp);
+    // (no pair plans here: their mailbox has to be zero between calls, and this entry point shares its array)
+    rc = make_full_plan(m, n, k, b, k_b, dtype, ATK_INTERLEAVED, ((uintptr_t)x & 15u) == 0, &fp, false);
     if (rc != ATK_OK) return rc;
     if (fp.two_step) return ATK_ERR_UNSUPPORTED;  // Stage 2 over more candidates than one workgroup holds: approx_topk only
     if (fp.state_bytes > ATK_NOALLOC_STATE_BYTES || fp.data_bytes > ATK_NOALLOC_SCRATCH_BYTES - ATK_NOALLOC_STATE_BYTES)
@@ -817,11 +870,16 @@ int approx_topk_noalloc(const void *x, int64_t m, int64_t n, int64_t k, int64_t 
         const hipError_t ez = hipGetLastError();
         if (ez != hipSuccess) return hip_fail(ez);
     }
-    const hipError_t e = launch_approx(fp.s1, x, out_vals, out_idx, base, base ? base + ATK_NOALLOC_STATE_BYTES : nullptr,
-                                       (hipStream_t)stream);
+    const hipError_t e = fp.s1.lean ? launch_approx_lean(fp.s1, x, out_vals, out_idx, nullptr, (hipStream_t)stream)
+                                    : launch_approx(fp.s1, x, out_vals, out_idx, base,
+                                                    base ? base + ATK_NOALLOC_STATE_BYTES : nullptr, (hipStream_t)stream);
     return e == hipSuccess ? ATK_OK : hip_fail(e);
 }
 
+int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *out_vals, int32_t *out_idx,
+               void *stream) {
+    if (!x || !out_vals || !out_idx) return ATK_ERR_NULL_PTR;
+    int rc = check_common(m, n, k, dtype);
     if (rc != ATK_OK) return rc;
     const int es = (dtype == ATK_F32) ? 4 : 2;
     if (((uintptr_t)x | (uintptr_t)out_vals) & (uintptr_t)(es - 1)) return ATK_ERR_ALIGN;
@@ -837,6 +895,22 @@ int approx_topk_noalloc(const void *x, int64_t m, int64_t n, int64_t k, int64_t 
     if (e != hipSuccess) return hip_fail(e);
     return run_exact(pl, x, nullptr, m, n, k, dtype, out_vals, out_idx, state, state_bytes, data, data_bytes,
                      (hipStream_t)stream);
+}
+
+int64_t atk_trace_bytes(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
+    int rc = check_approx(m, n, k, b, k_b, dtype);
+    if (rc != ATK_OK) return rc;
+    FullPlan fp;
+    rc = make_full_plan(m, n, k, b, k_b, dtype, ATK_INTERLEAVED, true, &fp);
+    if (rc != ATK_OK) return rc;
+    return fp.s1.grid * kTraceWaves * kTracePhases * 8;
+}
+
+int atk_trace_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, void *out_vals,
+                     int32_t *out_idx, void *trace, int64_t trace_bytes, void *stream) {
+    if (!trace) return ATK_ERR_NULL_PTR;
+    if ((uintptr_t)trace & 7u) return ATK_ERR_ALIGN;
+    return run_approx(x, m, n, k, b, k_b, dtype, ATK_INTERLEAVED, out_vals, out_idx, stream, trace, trace_bytes);
 }
 
 int atk_read_ceiling(const void *x, int64_t bytes, void *sink, void *stream) {

@@ -74,10 +74,14 @@ constexpr int kEmptyT = 0x7fffffff;       // "no element yet" row marker of a re
 struct PlanOverride {
     int T, S, V, P;   // threads per workgroup, row splits, columns per lane, lanes sharing a column group
     bool pk_off;      // PK=0: no packed bf16 queue words
+    bool lm_off;      // LM=0: lanes that share a column merge through the LDS exchange, not by LDS atomic maximum
     int xs;           // exact_topk sampled threshold: 0 not set, 1 forced on (XS=1), -1 off (XS=0)
     int xc;           // exact_topk sweep chunk in elements
-    int hf;           // helper/finisher hand-over: 0 not set, 1 forced on where legal (HF=1), -1 off (HF=0)
-    int hq;           // helper's share of the matrix rows in 64ths (HQ=..), 0 not set
+    int hf;           // two workgroups per row (helper + finisher): 0 not set, 1 forced on where legal (HF=1), -1 off (HF=0)
+    int hq;           // the helper's share of the matrix rows in 64ths (HQ=..), 0 not set
+    int ht;           // HT=<lanes>: workgroup size of the two-workgroups-per-row plans, 0 not set
+    int sl;           // SL=<lanes>: lanes of a workgroup that stream (the rest only join Stage 2), 0 not set
+    bool ln_off;      // LN=0: never the lean kernels
 };
 const PlanOverride &plan_override();
 
@@ -105,6 +109,10 @@ struct Plan {
     bool direct;      // every lane owns whole buckets: write results straight from registers
     bool use_scratch; // partial lists go through global scratch + a per-row ticket
     bool packed;      // bf16, k_b >= 3: 32-bit (key, row) queue words; needs rows_per_split + 2 < 32768
+    bool lds_max;     // k_b = 1, no scratch, lanes share columns: they meet in LDS by atomic maximum
+    bool bound_ok;    // lds_max with Stage 2: the merge yields a tight lower bound on the smallest candidate (see select_binned())
+    bool lean;        // k_b = 1 on rows of whole aligned 16-byte vectors, one workgroup (or a pair) per row: the lean kernels
+    int pair_rows;    // lean, Stage 2: > 0 = two workgroups per row, the helper takes this many matrix rows
     bool wave_merge;  // Gw < 64 and a power of two: lanes of a wavefront share columns, merged by shuffles
     int nparts;       // partial lists per column left for the LDS exchange
     int lds_xch_off, lds_cand_off;
@@ -126,11 +134,18 @@ int make_contig_plan(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, in
 
 // Enqueue the fused Stage 1 (+ merge, + Stage 2) kernel for `plan`.
 // state: zeroed words (tickets); data: partial lists.
+// trace: NULL, or (measurement build of the k_b = 1 kernels with 16-byte loads) a device buffer of
+// grid * kTraceWaves * kTracePhases words that receives every wavefront's phase timestamps.
 hipError_t launch_approx(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state, void *data,
-                         hipStream_t stream);
+                         hipStream_t stream, void *trace = nullptr);
 // The same for a plan of make_contig_plan().
 hipError_t launch_approx_contig(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state,
                                 void *data, hipStream_t stream);
+
+// The same for a plan with `lean` set (atk_lean.hip).  state: the helper-to-finisher mailbox of a pair plan
+// (plan.scratch_ticket_bytes, zero between calls), else unused.  trace: as for launch_approx.
+hipError_t launch_approx_lean(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state,
+                              hipStream_t stream, void *trace = nullptr);
 
 // ------------------------------------------------------------------------------------
 // exact_topk plan

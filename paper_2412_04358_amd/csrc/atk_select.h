@@ -38,6 +38,24 @@ __host__ __device__ constexpr int64_t select_lds_bytes(int64_t count, int kp) {
     return count * 8 + (radix > bucket ? radix : bucket);
 }
 
+// Phase timestamps of the measurement build of the fused kernel (atk_trace_approx): lane 0 of every wavefront
+// stores the 100 MHz wall clock into its own row of `tr`.  TR = false (every product launch) compiles to nothing.
+constexpr int kTracePhases = 16;   // words per wavefront: 12 phase stamps, [12] HW_ID, [13] XCC_ID of the wavefront
+constexpr int kTraceWaves = 16;    // wavefronts per workgroup the buffer has rows for
+template <bool TR>
+__device__ __forceinline__ void trace_mark(u64 *tr, int phase) {
+    if constexpr (TR) {
+        if ((threadIdx.x & (kWave - 1)) == 0) {
+            u64 *row = tr + ((int64_t)blockIdx.x * kTraceWaves + (threadIdx.x >> 6)) * kTracePhases;
+            row[phase] = wall_clock64();
+            if (phase == 0) {  // where the wavefront runs: hardware registers HW_ID (4) and XCC_ID (20), all 32 bits
+                row[12] = (u64)__builtin_amdgcn_s_getreg((31 << 11) | 4);
+                row[13] = (u64)__builtin_amdgcn_s_getreg((31 << 11) | 20);
+            }
+        }
+    }
+}
+
 // Decode a composite and store it as output element `pos` (absolute element offset).
 template <int ELT>
 __device__ __forceinline__ void write_composite(u64 c, void *out_vals, int32_t *out_idx, int64_t pos) {
@@ -338,13 +356,13 @@ __device__ __forceinline__ void select_radix_write(u64 *cand, int count, int k, 
 //
 // idx_bits: the candidates' column indices are below 2^idx_bits (1..31); it tells which index
 // bits vary, so that equal values can be spread over bins by index.
-template <int ELT, int NS>
+template <int ELT, int NS, bool TR>
 __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, int idx_bits, void *out_vals,
-                                                   int32_t *out_idx, int64_t row_out);
+                                                   int32_t *out_idx, int64_t row_out, u64 *tr);
 
-template <int ELT>
+template <int ELT, bool TR = false>
 __device__ __forceinline__ void select_write(u64 *cand, int count, int k, int idx_bits, void *out_vals, int32_t *out_idx,
-                             int64_t row_out) {
+                             int64_t row_out, u64 *tr = nullptr) {
     const int T = blockDim.x;
     if (count > kBkSlots * T || T > kBkBins) {
         select_radix_write<ELT>(cand, count, k, out_vals, out_idx, row_out);
@@ -353,17 +371,17 @@ __device__ __forceinline__ void select_write(u64 *cand, int count, int k, int id
     // the tail is a chain of dependent instructions in one workgroup: code for as many register
     // slots as the candidates need, not for the maximum
     if (count <= T)
-        select_bucket_rank<ELT, 1>(cand, count, k, idx_bits, out_vals, out_idx, row_out);
+        select_bucket_rank<ELT, 1, TR>(cand, count, k, idx_bits, out_vals, out_idx, row_out, tr);
     else if (count <= 2 * T)
-        select_bucket_rank<ELT, 2>(cand, count, k, idx_bits, out_vals, out_idx, row_out);
+        select_bucket_rank<ELT, 2, TR>(cand, count, k, idx_bits, out_vals, out_idx, row_out, tr);
     else
-        select_bucket_rank<ELT, kBkSlots>(cand, count, k, idx_bits, out_vals, out_idx, row_out);
+        select_bucket_rank<ELT, kBkSlots, TR>(cand, count, k, idx_bits, out_vals, out_idx, row_out, tr);
 }
 
 // The fast path of select_write with NS candidates per lane in registers (count <= NS * blockDim.x).
-template <int ELT, int NS>
+template <int ELT, int NS, bool TR>
 __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, int idx_bits, void *out_vals,
-                                                   int32_t *out_idx, int64_t row_out) {
+                                                   int32_t *out_idx, int64_t row_out, u64 *tr) {
     const int tid = threadIdx.x, T = blockDim.x;
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     // as many bins as it takes for about one candidate in four bins, 256 at least: clearing and
@@ -418,6 +436,7 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
         atomicOr(&misc[3], k_or);
     }
     __syncthreads();
+    trace_mark<TR>(tr, 4);  // key range known
     k_min = misc[1];
     k_max = misc[2];
     k_or = misc[3];
@@ -438,6 +457,7 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
         if (c[e]) atomicAdd(&cnt[bin[e]], 1u);
     }
     __syncthreads();
+    trace_mark<TR>(tr, 5);  // histogram done
 
     // ---- descending exclusive prefix over the bins: thread t owns the q bins below 2048 - t*q
     const int q = n_bins / T;  // T is a multiple of 64 and at most n_bins; q*T may fall short of n_bins
@@ -478,6 +498,7 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
         }
     }
     __syncthreads();
+    trace_mark<TR>(tr, 6);  // prefix done
     if (misc[0] != 0u) {
         // A bin is too full: cand still holds the candidates, take the radix descent.  Every
         // lane reads the same flag; the barrier keeps the descent from reusing this area
@@ -495,6 +516,7 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
         if (start[e] < (uint32_t)k) cand[start[e] + atomicSub(&cnt[bin[e]], 1u) - 1u] = c[e];
     }
     __syncthreads();
+    trace_mark<TR>(tr, 7);  // filed
 #pragma unroll
     for (int e = 0; e < NS; ++e)
         if (start[e] < (uint32_t)k) {
@@ -505,6 +527,175 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
         }
 }
 
+// ---- Stage 2 for callers that know the candidates' key range before the workgroup's barrier -------------
+// select_bucket_rank() spends two barriers on the range of the keys and two on a prefix sum that every
+// wavefront takes part in.  A kernel that touches every candidate anyway before its barrier (the fused
+// Stage 1 merging its lanes' running maxima) folds the range into that step, and then this shorter form
+// does: one histogram (the atomic's return value is the candidate's place among its bin's arrivals), a
+// prefix sum by the first wavefront alone (it is a chain of dependent steps either way; with one
+// wavefront there is no second level and one barrier less), filing by bin, exact rank inside the bin.
+//
+// LDS behind cand (count rounded up to even, 16-byte aligned): cnt[kBkBins], abv[kBkBins + 8], misc[32].
+// Before the barrier that precedes the call, the caller has: zeroed cnt[0 .. 1 << binned_lg_bins(count)) and
+// misc[0]; set misc[2] / misc[3] to an upper bound and the OR (or a superset of its bits) of the candidates'
+// value keys, and misc[1] and misc[4] each to a lower bound (the larger is used; a bound far below the
+// candidates costs bin resolution, and with it the short form: crowded bins send the row to the digit-by-digit
+// selection); put the candidates at cand[0 .. count), zeros for none.
+__device__ __forceinline__ int binned_lg_bins(int count) {
+    int lg = 8;
+    while (lg < 11 && (2 << lg) < count) ++lg;
+    return lg;
+}
+__device__ __forceinline__ uint32_t *binned_cnt(u64 *cand, int count) { return (uint32_t *)(cand + ((count + 1) & ~1)); }
+__device__ __forceinline__ uint32_t *binned_misc(u64 *cand, int count) { return binned_cnt(cand, count) + 2 * kBkBins + 8; }
+
+// The prefix sum of select_binned(): run by the first wavefront; lane l owns the Q bins below n_bins - l*Q, so lane
+// order is descending bin order.  All of a lane's counts are loaded before any is used.
+template <int Q>
+__device__ __forceinline__ void binned_scan(const uint32_t *cnt, uint32_t *abv, uint32_t *misc, int n_bins, int k, int lane) {
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const int hi = n_bins - 1 - lane * Q;
+    v4u v[Q / 4];
+#pragma unroll
+    for (int j = 0; j < Q / 4; ++j) v[j] = *(const v4u *)&cnt[hi - 4 * j - 3];
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < Q / 4; ++j) s += v[j].x + v[j].y + v[j].z + v[j].w;
+    uint32_t run = wave_incl_scan_u32(s) - s;
+    bool crowded = false;
+#pragma unroll
+    for (int j = 0; j < Q / 4; ++j) {
+        v4u a;
+        a.w = run;
+        a.z = run + v[j].w;
+        a.y = a.z + v[j].z;
+        a.x = a.y + v[j].y;
+        // a bin that may hold winners and is too full for the in-bin count to stay cheap
+        crowded = crowded || (a.w < (uint32_t)k && v[j].w > (uint32_t)kBkBinMax) || (a.z < (uint32_t)k && v[j].z > (uint32_t)kBkBinMax) ||
+                  (a.y < (uint32_t)k && v[j].y > (uint32_t)kBkBinMax) || (a.x < (uint32_t)k && v[j].x > (uint32_t)kBkBinMax);
+        *(v4u *)&abv[hi - 4 * j - 3 + 4] = a;
+        run = a.x + v[j].x;
+    }
+    if (lane == kWave - 1) abv[3] = run;  // "bin -1" starts behind everything
+    if (__ballot(crowded) != 0ull && lane == 0) misc[0] = 1u;
+}
+
+template <int ELT, int NS, bool TR>
+__device__ __forceinline__ void select_binned_ns(u64 *cand, int count, int k, int idx_bits, void *out_vals,
+                                                 int32_t *out_idx, int64_t row_out, u64 *tr) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int lg_bins = binned_lg_bins(count), n_bins = 1 << lg_bins;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t *cnt = binned_cnt(cand, count);
+    uint32_t *abv = cnt + kBkBins;       // abv[b + 4] = candidates in bins above b, for b = -1 .. n_bins - 1
+    uint32_t *misc = abv + kBkBins + 8;  // [0] overflow flag, [1] and [4] lower bounds, [2] largest key
+    // (the bounds and the candidates are loaded together)
+    const uint32_t lb1 = misc[1], k_max = misc[2], lb4 = misc[4];
+    u64 c[NS];
+#pragma unroll
+    for (int e = 0; e < NS; ++e) {
+        const int i = tid + e * T;
+        c[e] = (i < count) ? cand[i] : 0ull;
+    }
+    const uint32_t k_min = lb4 > lb1 ? lb4 : lb1;
+    // Bin key as in select_bucket_rank(): the value key relative to the lower bound (below it: 0), without the
+    // low bits that are zero in every key of the element type, the varying index bits appended; n_bins bins,
+    // linear over that range.
+    constexpr int tz = (ELT == ATK_BF16) ? 16 : 0;
+    const uint32_t imask = (idx_bits >= 31) ? 0x7fffffffu : ((1u << idx_bits) - 1u);
+    const u64 span = ((u64)((k_max - k_min) >> tz) + 1ull) << idx_bits;
+    const int rbits = 64 - __clzll((long long)span);
+    const int bshift = rbits > lg_bins ? rbits - lg_bins : 0;
+    uint32_t bin[NS], pos[NS];
+#pragma unroll
+    for (int e = 0; e < NS; ++e) {
+        const uint32_t key = (uint32_t)(c[e] >> 32);
+        const uint32_t rel = key > k_min ? key - k_min : 0u;
+        const u64 bk = ((u64)(rel >> tz) << idx_bits) | (((uint32_t)c[e] >> 1) & imask);
+        bin[e] = (uint32_t)(bk >> bshift);
+    }
+#pragma unroll
+    for (int e = 0; e < NS; ++e) pos[e] = c[e] ? atomicAdd(&cnt[bin[e]], 1u) : 0u;  // its place among its bin's arrivals
+    __syncthreads();
+    trace_mark<TR>(tr, 5);  // histogram done
+    if (wave == 0) {
+        const int q = n_bins >> 6;
+        if (q == 4)
+            binned_scan<4>(cnt, abv, misc, n_bins, k, lane);
+        else if (q == 8)
+            binned_scan<8>(cnt, abv, misc, n_bins, k, lane);
+        else if (q == 16)
+            binned_scan<16>(cnt, abv, misc, n_bins, k, lane);
+        else
+            binned_scan<32>(cnt, abv, misc, n_bins, k, lane);
+    }
+    __syncthreads();
+    trace_mark<TR>(tr, 6);  // prefix done
+    // where the candidate's bin starts and ends (= where the next lower bin starts), loaded together with the flag
+    uint32_t start[NS], end[NS];
+#pragma unroll
+    for (int e = 0; e < NS; ++e) {
+        start[e] = abv[bin[e] + 4];
+        end[e] = abv[bin[e] + 3];
+    }
+    if (misc[0] != 0u) {
+        // cand still holds the candidates: the digit-by-digit selection takes over (every lane has read the flag
+        // before the descent reuses this area)
+        __syncthreads();
+        select_radix_write<ELT>(cand, count, k, out_vals, out_idx, row_out);
+        return;
+    }
+    // ---- file the possible winners by bin, in place of cand (every lane has its own in registers)
+#pragma unroll
+    for (int e = 0; e < NS; ++e) {
+        if (!c[e]) start[e] = 0xffffffffu;
+        if (start[e] < (uint32_t)k) cand[start[e] + pos[e]] = c[e];
+    }
+    __syncthreads();
+    trace_mark<TR>(tr, 7);  // filed
+    // ---- exact rank = start of the bin + larger elements of the bin.  The first four of the bin are read in one go,
+    // wanted or not (a bin seldom holds more; past its end lies another bin or stale data, masked out).
+    u64 peer[NS][4];
+#pragma unroll
+    for (int e = 0; e < NS; ++e)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = start[e] + (uint32_t)u;
+            peer[e][u] = cand[(start[e] < (uint32_t)k && j < end[e]) ? j : 0u];
+        }
+#pragma unroll
+    for (int e = 0; e < NS; ++e)
+        if (start[e] < (uint32_t)k) {
+            uint32_t r = start[e];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) r += (start[e] + (uint32_t)u < end[e] && peer[e][u] > c[e]) ? 1u : 0u;
+            for (uint32_t j = start[e] + 4u; j < end[e]; ++j) r += (cand[j] > c[e]) ? 1u : 0u;
+            if (r < (uint32_t)k) write_composite<ELT>(c[e], out_vals, out_idx, row_out * k + r);
+        }
+}
+
+// true when select_binned() takes the short form for this many candidates (else the caller need not
+// prepare the range and the counts: the digit-by-digit selection runs)
+__device__ __forceinline__ bool binned_fits(int count) { return count <= kBkSlots * (int)blockDim.x; }
+
+template <int ELT, bool TR = false>
+__device__ __forceinline__ void select_binned(u64 *cand, int count, int k, int idx_bits, void *out_vals,
+                                              int32_t *out_idx, int64_t row_out, u64 *tr = nullptr) {
+    const int T = blockDim.x;
+    if (!binned_fits(count)) {
+        select_radix_write<ELT>(cand, count, k, out_vals, out_idx, row_out);
+        return;
+    }
+    if (count <= T)
+        select_binned_ns<ELT, 1, TR>(cand, count, k, idx_bits, out_vals, out_idx, row_out, tr);
+    else if (count <= 2 * T)
+        select_binned_ns<ELT, 2, TR>(cand, count, k, idx_bits, out_vals, out_idx, row_out, tr);
+    else
+        select_binned_ns<ELT, kBkSlots, TR>(cand, count, k, idx_bits, out_vals, out_idx, row_out, tr);
+}
+
 #endif  // __HIPCC__
+
 
 }  // namespace atk

@@ -19,6 +19,7 @@
 
 #include "atk_common.h"
 #include "atk_select.h"
+#include "atk_stream.h"
 
 namespace atk {
 
@@ -45,62 +46,10 @@ struct S1Params {
     int bblocks;         // workgroups side by side across the b buckets
     int chunks_per_split;
     int NB;              // short buckets: buckets a lane group takes in turn (0: one bucket per group)
+    int lds_max;         // k_b = 1, no scratch: the lanes' running maxima meet in LDS by atomic maximum (see the kernel)
+    int bound_ok;        // ... and the lower bound on the smallest candidate that comes with that merge is tight enough for select_binned()
+    u64 *trace;          // measurement build only: phase timestamps, [workgroup][wavefront][phase]
 };
-
-template <int ELT, int V>
-struct RowVec {
-    static constexpr int kBytes = V * ((ELT == ATK_F32) ? 4 : 2);
-    static constexpr int kWords = (kBytes + 3) / 4;
-    uint32_t w[kWords];
-};
-
-// One load of V adjacent elements (16, 8, 4 or 2 bytes).  The data is read exactly once,
-// so the loads are marked non-temporal.
-template <int ELT, int V>
-__device__ __forceinline__ RowVec<ELT, V> load_vec(const unsigned char *p) {
-    RowVec<ELT, V> r;
-    constexpr int B = RowVec<ELT, V>::kBytes;
-    if constexpr (B == 16) {
-        typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-        v4u q = __builtin_nontemporal_load((const v4u *)p);
-        r.w[0] = q.x;
-        r.w[1] = q.y;
-        r.w[2] = q.z;
-        r.w[3] = q.w;
-    } else if constexpr (B == 8) {
-        typedef uint32_t v2u __attribute__((ext_vector_type(2)));
-        v2u q = __builtin_nontemporal_load((const v2u *)p);
-        r.w[0] = q.x;
-        r.w[1] = q.y;
-    } else if constexpr (B == 4) {
-        r.w[0] = __builtin_nontemporal_load((const uint32_t *)p);
-    } else {
-        r.w[0] = (uint32_t)__builtin_nontemporal_load((const uint16_t *)p);
-    }
-    return r;
-}
-
-// element e of the vector as float bits (bf16 widened exactly)
-template <int ELT, int V>
-__device__ __forceinline__ uint32_t elem_bits(const RowVec<ELT, V> &r, int e) {
-    if constexpr (ELT == ATK_F32) {
-        return r.w[e];
-    } else {
-        uint32_t w = r.w[e >> 1];
-        return (e & 1) ? (w & 0xffff0000u) : (w << 16);
-    }
-}
-
-// q = x / d, rem = x % d; shift = log2(d) when d is a power of two, else -1
-__device__ __forceinline__ void divmod(int x, int d, int shift, int &q, int &rem) {
-    if (shift >= 0) {
-        q = x >> shift;
-        rem = x & (d - 1);
-    } else {
-        q = x / d;
-        rem = x - q * d;
-    }
-}
 
 // Insert (v, t) into the descending list (val, tt); later elements never displace equal
 // earlier ones ("!(v <= slot)" is "v > slot" for numbers and true for the NaN that marks
@@ -215,7 +164,7 @@ __device__ __forceinline__ void emit_list(const S1Params &p, int r, int sp, int 
 // without it every block of columns [c_lo, c_hi) has its own (ticket number `tk`), and whoever
 // draws the last one merges the row splits of just those columns.  Column c of the block is
 // bucket c - rot (mod b).
-template <int ELT, int KB>
+template <int ELT, int KB, bool TR = false>
 __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, int c_lo, int c_hi, int rot,
                                          unsigned char *smem) {
     const int tid = threadIdx.x, T = blockDim.x;
@@ -243,6 +192,7 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
         }
         __syncthreads();
         if (flag[0] == 0) return;
+        trace_mark<TR>(p.trace, 10);  // drew the last ticket
         if (tid == 0)  // ready for the next call
             __hip_atomic_store(ticket_word, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
@@ -331,17 +281,21 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
             }
             if (ok && part == 0) put(col, acc);
         }
+        trace_mark<TR>(p.trace, 11);  // the other workgroups' lists are merged
         if (!p.stage2) return;
         __syncthreads();
     }
 
     // ---------------------------------------------------------------- Stage 2 in LDS
-    select_write<ELT>(cand, p.b * p.k_b, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r);
+    trace_mark<TR>(p.trace, 3);  // all candidates of the row are in LDS
+    select_write<ELT, TR>(cand, p.b * p.k_b, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
+    trace_mark<TR>(p.trace, 8);  // outputs written
 }
 
-template <int ELT, int V, int KB, int U, int MAXT, bool PKF>
+template <int ELT, int V, int KB, int U, int MAXT, bool PKF, bool TR = false>
 __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     extern __shared__ __align__(16) unsigned char smem[];
+    trace_mark<TR>(p.trace, 0);  // the wavefront has started
     constexpr int ES = (ELT == ATK_F32) ? 4 : 2;
     constexpr bool PK = PKF && ELT == ATK_BF16 && KB >= 4;  // packed 32-bit queues (host: rows per split < 32766)
     const int tid = threadIdx.x, T = blockDim.x;
@@ -366,6 +320,24 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     const int t0 = sp * p.rows_per_split;
     const int t1 = (sp == p.S - 1) ? Lr : min(Lr, t0 + p.rows_per_split);
     auto bucket_of = [&](int c) { return c - rot + (c < rot ? p.b : 0); };
+
+    // One slot per bucket, no hand-over through memory: the lanes that share a column meet in LDS by
+    // atomic maximum on the composite (the merge of Appendix A's per-thread queues, for queues of one
+    // slot), straight into the candidate array that Stage 2 selects from.  The array - and the counts
+    // of Stage 2's histogram - are cleared here, while nothing else is going on.
+    if constexpr (KB == 1) {
+        if (p.lds_max) {
+            u64 *cand = (u64 *)(smem + p.lds_cand_off);
+            const int wcols = min(p.Gw * V, p.b - cb * p.Gw * V);
+            for (int i = tid; i < wcols; i += T) cand[i] = 0ull;
+            if (p.stage2 && binned_fits(wcols) && p.bound_ok) {
+                uint32_t *cnt = binned_cnt(cand, wcols), *misc = binned_misc(cand, wcols);
+                for (int i = tid; i < (1 << binned_lg_bins(wcols)); i += T) cnt[i] = 0u;
+                if (tid < 8) misc[tid] = (tid == 1) ? 0xffffffffu : 0u;  // (see select_binned: flag, range, lower bounds)
+            }
+            __syncthreads();
+        }
+    }
 
     float val[V][KB];
     int tt[V][KB];
@@ -512,6 +484,7 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 
 #undef ATK_FEED_VEC
 #undef ATK_FEED_ELEM
+    trace_mark<TR>(p.trace, 1);  // its share of the row is in
     if constexpr (PK) {
 #pragma unroll
         for (int e = 0; e < V; ++e)
@@ -572,6 +545,65 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
                     }
         }
         return;
+    }
+
+    // ---------------------------------------------------------------- one slot, one workgroup per row or column block
+    if constexpr (KB == 1) {
+        if (p.lds_max) {
+            u64 *cand = (u64 *)(smem + p.lds_cand_off);
+            const int colbase = cb * p.Gw * V;
+            const int wcols = min(p.Gw * V, p.b - colbase);
+            const bool binned = p.stage2 && binned_fits(wcols) && p.bound_ok;
+            uint32_t k_min = 0xffffffffu, k_max = 0u;
+            bool whole = active;  // this lane holds an element of every one of its V columns
+            if (active) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) whole = whole && tt[e][0] != kEmptyT;
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    if (tt[e][0] != kEmptyT) {
+                        const u64 c = make_composite(__float_as_uint(val[e][0]), tt[e][0] * p.b + col0 + e - rot);
+                        // column e of column group cgl sits at e*Gw + cgl: side-by-side lanes, side-by-side words
+                        __hip_atomic_fetch_max(&cand[e * p.Gw + cgl], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        const uint32_t key = (uint32_t)(c >> 32);
+                        k_min = key < k_min ? key : k_min;
+                        k_max = key > k_max ? key : k_max;
+                    }
+            }
+            if (binned) {
+                // the range of the value keys that Stage 2 spreads its bins over: the lanes' maxima span at least
+                // the range of the columns' maxima.  Folded here, before the barrier, it costs the wavefronts that
+                // finish reading early nothing.
+                uint32_t *misc = binned_misc(cand, wcols);
+                k_min = wave_min_u32(k_min);
+                k_max = wave_max_u32(k_max);
+                // a wavefront whose 64 lanes between them hold an element of every column of the row: its minimum is
+                // a lower bound on the smallest candidate, usually far tighter than the minimum over all lanes
+                const bool cover = p.Gw <= kWave && __ballot(whole) == ~0ull;
+                if ((tid & (kWave - 1)) == 0) {
+                    atomicMin(&misc[1], k_min);
+                    atomicMax(&misc[2], k_max);
+                    if (cover) atomicMax(&misc[4], k_min);
+                }
+            }
+            trace_mark<TR>(p.trace, 2);  // this wavefront's maxima are in
+            __syncthreads();
+            if (!p.stage2) {
+                for (int lc = tid; lc < wcols; lc += T)
+                    write_composite<ELT>(cand[(lc % V) * p.Gw + lc / V], p.out_vals, p.out_idx,
+                                         (int64_t)r * p.k + bucket_of(colbase + lc));
+                trace_mark<TR>(p.trace, 9);
+                return;
+            }
+            trace_mark<TR>(p.trace, 3);  // all candidates of the row are in LDS, their key range is known
+            if (binned)
+                select_binned<ELT, TR>(cand, wcols, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
+            else
+                select_write<ELT, TR>(cand, wcols, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
+            trace_mark<TR>(p.trace, 8);
+            trace_mark<TR>(p.trace, 9);
+            return;
+        }
     }
 
     // ---------------------------------------------------------------- to composites
@@ -637,9 +669,11 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
         for (int e = 0; e < V; ++e) emit(bucket_of(col0 + e), comp[e]);
     }
 
+    trace_mark<TR>(p.trace, 2);  // this workgroup's lists are merged and handed on
     const bool whole = p.stage2 != 0;
-    row_tail<ELT, KB>(p, r, whole ? (int64_t)r : (int64_t)r * p.colblocks + cb, whole ? 0 : cb * p.Gw * V,
-                      whole ? p.b : min(p.b, (cb + 1) * p.Gw * V), whole ? 0 : rot, smem);
+    row_tail<ELT, KB, TR>(p, r, whole ? (int64_t)r : (int64_t)r * p.colblocks + cb, whole ? 0 : cb * p.Gw * V,
+                          whole ? p.b : min(p.b, (cb + 1) * p.Gw * V), whole ? 0 : rot, smem);
+    trace_mark<TR>(p.trace, 9);  // done
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -850,6 +884,7 @@ static hipError_t launch_one(const Plan &pl, const S1Params &prm, hipStream_t st
             return hipGetLastError();
         }
     }
+    if (prm.trace) return hipErrorNotSupported;  // the measurement build exists for the lean kernels only
     hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U, MAXT, false>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T),
                        (size_t)pl.lds_bytes, stream, prm);
     return hipGetLastError();
@@ -863,9 +898,10 @@ static int log2_exact(int v) {
 }
 
 hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state, void *data,
-                         hipStream_t stream) {
+                         hipStream_t stream, void *trace) {
     S1Params prm;
     memset(&prm, 0, sizeof prm);
+    prm.trace = (u64 *)trace;
     prm.x = x;
     prm.out_vals = out_vals;
     prm.out_idx = out_idx;
@@ -893,6 +929,8 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.nparts = pl.nparts;
     prm.lds_xch_off = pl.lds_xch_off;
     prm.lds_cand_off = pl.lds_cand_off;
+    prm.lds_max = pl.lds_max;
+    prm.bound_ok = pl.bound_ok;
     prm.wgs_per_ticket = pl.stage2 ? pl.S * pl.colblocks : pl.S;
     prm.tail_tpc_shift = log2_exact(pl.tail_tpc);
     prm.cb_shift = log2_exact(pl.colblocks);
