@@ -211,7 +211,7 @@ def main():
     achieved = min_bytes(M, N, K) / avg_launch_s / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "kernel": "stage1_kernel<f32,V=4,KB=1>", "avg_launch_us": round(avg_launch_s * 1e6, 3),
+                "kernel": "lean_kernel<f32> (k_b = 1 streaming scan + fused Stage 2)", "avg_launch_us": round(avg_launch_s * 1e6, 3),
                 "read_only_ceiling_GBps": {"cold": round(ceil_cold, 1), "warm": round(ceil_warm, 1)}}
     # HBM bytes per launch come from separate rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE scaled by a
     # copy kernel of known size); the summary of those passes records the figure.
@@ -271,6 +271,9 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    del ring
+    torch.cuda.empty_cache()
+    out["secondary"] = secondary(atk, workloads, torch, dev)
     if args.detail:
         out["detail"] = detail(atk, workloads, torch, dev)
     print(json.dumps(out))
@@ -355,6 +358,40 @@ def _approx_entry(atk, torch, dev, ring, m, n, k, b, k_b, dt, es, reps, assignme
     return {"us": round(us, 2), "est_us": round(atk.estimate_us(m, n, k, b, k_b, dt), 2) if assignment is None else None,
             "GBps": round(nbytes / us / 1e3, 1), "frac_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
             "plan": atk.plan_describe(m, n, k, b, k_b, dt, assignment if assignment is not None else atk.ATK_INTERLEAVED)}
+
+
+def secondary(atk, workloads, torch, dev):
+    """The other configurations, in every default run: microseconds per launch (inputs cold where a ring
+    fits), total bandwidth and its fraction of the HBM peak.  Figure 1 right (k = n/4, k_b = 1 and 8), the long
+    rows of 2^20 elements at k = 64 (one bucket per output, and 16 per output with Stage 2), the attention-score
+    shape in bf16, and the row-length sweep at the headline setting (k = 64, k_b = 1, b = 64)."""
+    res = {}
+
+    def run(tag, ring, m, n, k, b, k_b, dt, es, reps):
+        e = _approx_entry(atk, torch, dev, ring, m, n, k, b, k_b, dt, es, reps)
+        res[tag] = {"us": e["us"], "GBps": e["GBps"], "frac_hbm_peak": e["frac_hbm_peak"], "plan": e["plan"]}
+
+    ring = [workloads.normal_rows(M, N, seed=s).to(dev) for s in range(RING)]
+    run("cfg3 k=16384 b=16384 k_b=1", ring, M, N, 16384, 16384, 1, atk.ATK_F32, 4, 200)
+    run("cfg3 k=16384 b=2048 k_b=8", ring, M, N, 16384, 2048, 8, atk.ATK_F32, 4, 200)
+    run("n=2^16 m=128 k=64 b=64 k_b=1", ring, M, N, 64, 64, 1, atk.ATK_F32, 4, 200)
+    del ring
+    torch.cuda.empty_cache()
+    ring = [workloads.attention_scores(seed=s).to(dev) for s in range(RING)]
+    run("cfg5 bf16 2048x8192 k=512 b=512 k_b=1", ring, 2048, 8192, 512, 512, 1, atk.ATK_BF16, 2, 200)
+    del ring
+    torch.cuda.empty_cache()
+    for lg in (17, 18, 19, 20):
+        n = 1 << lg
+        nring = max(1, min(12, (420 << 20) // (M * n * 4)))
+        ring = [workloads.normal_rows(M, n, seed=s).to(dev) for s in range(nring)]
+        run("n=2^%d m=128 k=64 b=64 k_b=1" % lg, ring, M, n, 64, 64, 1, atk.ATK_F32, 4, 100)
+        if lg == 20:  # = cfg4, k = 64
+            res["cfg4 k=64 b=64 k_b=1"] = res["n=2^20 m=128 k=64 b=64 k_b=1"]
+            run("cfg4 k=64 b=1024 k_b=1", ring, M, n, 64, 1024, 1, atk.ATK_F32, 4, 100)
+        del ring
+        torch.cuda.empty_cache()
+    return res
 
 
 def detail(atk, workloads, torch, dev):

@@ -151,6 +151,19 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
     }
     trace_mark<TR>(p.trace, 1);  // this wavefront's share of the row is in
 
+    // the finisher's look at the helper's mailbox
+    u64 cm[kBkSlots];  // slots tid, tid + T, ... (the host sends at most kBkSlots * T buckets this way)
+    auto look = [&]() {
+        const u64 *mail = p.mail + (int64_t)r * p.b;
+#pragma unroll
+        for (int q = 0; q < kBkSlots; ++q) {  // all loads in flight together
+            const int i = tid + q * T;
+            cm[q] = 1ull;
+            if (q * T < wcols)  // (the same for every lane)
+                cm[q] = __hip_atomic_load(&mail[i < wcols ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+
     // ---------------------------------------------------------------- the lanes of a column meet in LDS
     uint32_t k_own_min = 0xffffffffu, k_mail_min = 0xffffffffu, k_max = 0u;
     if (active) {
@@ -186,16 +199,11 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
     bool gave_up = false;
     if (MODE == kLeanPair) {
         // the finisher: the helper's maxima, slot for slot (every slot holds a composite, and a composite is never 0)
+        // (A first look issued before this wavefront's own maxima go to LDS, to hide its latency, measured slower:
+        // it comes back empty more often than not, and the second look then starts later than a single late one.)
         u64 *mail = p.mail + (int64_t)r * p.b;
-        u64 cm[kBkSlots];  // slots tid, tid + T, ... (the host sends at most kBkSlots * T buckets this way)
+        look();
         for (int spins = 0;;) {
-#pragma unroll
-            for (int q = 0; q < kBkSlots; ++q) {  // all loads in flight together
-                const int i = tid + q * T;
-                cm[q] = 1ull;
-                if (q * T < wcols)  // (the same for every lane)
-                    cm[q] = __hip_atomic_load(&mail[i < wcols ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
             bool missing = false;
 #pragma unroll
             for (int q = 0; q < kBkSlots; ++q) missing = missing || (tid + q * T < wcols && cm[q] == 0ull);
@@ -204,7 +212,8 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
                 gave_up = true;
                 break;
             }
-            __builtin_amdgcn_s_sleep(8);
+            __builtin_amdgcn_s_sleep(2);
+            look();
         }
 #pragma unroll
         for (int q = 0; q < kBkSlots; ++q) {
