@@ -51,6 +51,9 @@ def main():
                     help="phase timeline of the fused kernel on the headline workload: per b, 30 launches of the "
                          "measurement build (atk_trace_approx) on HBM-cold inputs, each right behind an ordinary launch; "
                          "prints when the first, the median and the last wavefront passed every phase boundary")
+    ap.add_argument("--probe-queues", action="store_true",
+                    help="profiler run of the kernels with register queues: 5 plain copies, then 20 approx_topk calls each on "
+                         "cfg3 (128 x 65536 f32, k=16384) at k_b = 1, 4, 8, 16 and on cfg5 (2048 x 8192 bf16, k=b=512); no timing")
     ap.add_argument("--probe", action="store_true",
                     help="short run for hardware-counter passes: 20 copy launches, 20 read-only launches and 20 "
                          "approx_topk launches per b, nothing else")
@@ -88,6 +91,34 @@ def main():
             torch.cuda.synchronize()
             del xe, ov, oi
         print(json.dumps({"probe": "done", "calls_each": 10, "cases": [[M, n_row, k] for n_row, k in cases]}))
+        return
+
+    if args.probe_queues:
+        st = torch.cuda.current_stream().cuda_stream
+        ring = [workloads.normal_rows(M, N, seed=s).to(dev) for s in range(RING)]
+        dst = torch.empty_like(ring[0])
+        for i in range(5):
+            lib.atk_copy(dst.data_ptr(), ring[i % RING].data_ptr(), M * N * 4, st)
+        ov = torch.empty((M, 16384), dtype=torch.float32, device=dev)
+        oi = torch.empty((M, 16384), dtype=torch.int32, device=dev)
+        for k_b in (1, 4, 8, 16):
+            for i in range(20):
+                rc = lib.approx_topk(ring[i % RING].data_ptr(), M, N, 16384, 16384 // k_b, k_b, atk.ATK_F32, ov.data_ptr(),
+                                     oi.data_ptr(), st)
+                if rc != 0:
+                    raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
+        torch.cuda.synchronize()
+        del ring, dst
+        ring5 = [workloads.attention_scores(seed=s).to(dev) for s in range(RING)]
+        ov5 = torch.empty((2048, 512), dtype=torch.bfloat16, device=dev)
+        oi5 = torch.empty((2048, 512), dtype=torch.int32, device=dev)
+        for i in range(20):
+            rc = lib.approx_topk(ring5[i % RING].data_ptr(), 2048, 8192, 512, 512, 1, atk.ATK_BF16, ov5.data_ptr(),
+                                 oi5.data_ptr(), st)
+            if rc != 0:
+                raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "done", "copy_bytes": M * N * 4, "launches_each": 20, "cfg3_k_b": [1, 4, 8, 16], "cfg5": True}))
         return
 
     if args.probe_long:
@@ -215,7 +246,7 @@ def main():
                 "read_only_ceiling_GBps": {"cold": round(ceil_cold, 1), "warm": round(ceil_warm, 1)}}
     # HBM bytes per launch come from separate rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE scaled by a
     # copy kernel of known size); the summary of those passes records the figure.
-    traffic_file = os.path.join(ROOT, "profiles", "stage1_kernel_cfg2_hbm_traffic.md")
+    traffic_file = os.path.join(ROOT, "profiles", "lean_kernel_cfg2_hbm_traffic.md")
     if os.path.exists(traffic_file):
         import re
 
