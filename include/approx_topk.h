@@ -174,6 +174,10 @@ int atk_set_plan_override(const char *spec);
  *   method returns when top-k positions fall into buckets uniformly (a lower bound on the
  *   recall once k_b is not small against n/b, as the remark after Eq. 1 says).  -1 for
  *   arguments outside 1 <= k_b <= k <= b*k_b.
+ * atk_worst_case_recall: Eq. 2 of Appendix C, the recall when the true top-k sit in as few buckets as they can
+ *   (floor(b*k/n) buckets full of them and one more with the rest): the lower end of what any input can give, which
+ *   the paper calls too pessimistic for real data and leaves out of its discussion.  Stated for b dividing n; -1 for
+ *   other arguments or ones Section 2 does not allow.
  * atk_estimate_us: microseconds one approx_topk call with these arguments is expected to take on
  *   an MI355X, in the shape of Appendix D's cost composition (Stage 1 + Stage 2 if b*k_b > k) with
  *   terms fitted to this library's measured timings.  -1 if the arguments are not accepted.
@@ -185,6 +189,7 @@ int atk_set_plan_override(const char *spec);
  */
 #define ATK_ADVISE_BELOW_TARGET 1
 double atk_expected_recall(int64_t k, int64_t b, int64_t k_b);
+double atk_worst_case_recall(int64_t n, int64_t k, int64_t b, int64_t k_b);
 double atk_estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype);
 int atk_advise(int64_t m, int64_t n, int64_t k, int dtype, double min_recall, int64_t *b, int64_t *k_b,
                double *recall, double *us);

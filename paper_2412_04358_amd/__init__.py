@@ -23,4 +23,5 @@ from .binding import (  # noqa: F401
     plan_describe,
     set_plan_override,
     strerror,
+    worst_case_recall,
 )

@@ -77,6 +77,8 @@ def load_library():
     dbl = ctypes.c_double
     lib.atk_expected_recall.argtypes = [i64, i64, i64]
     lib.atk_expected_recall.restype = dbl
+    lib.atk_worst_case_recall.argtypes = [i64, i64, i64, i64]
+    lib.atk_worst_case_recall.restype = dbl
     lib.atk_estimate_us.argtypes = [i64, i64, i64, i64, i64, ci]
     lib.atk_estimate_us.restype = dbl
     lib.atk_advise.argtypes = [i64, i64, i64, ci, dbl, ctypes.POINTER(i64), ctypes.POINTER(i64),
@@ -199,6 +201,11 @@ def set_plan_override(spec=None) -> None:
 def expected_recall(k, b, k_b) -> float:
     """Eq. 1 of Appendix C as the library computes it (host only)."""
     return load_library().atk_expected_recall(k, b, k_b)
+
+
+def worst_case_recall(n, k, b, k_b) -> float:
+    """Eq. 2 of Appendix C as the library computes it (host only); -1 for arguments it is not stated for."""
+    return load_library().atk_worst_case_recall(n, k, b, k_b)
 
 
 def estimate_us(m, n, k, b, k_b, dtype=ATK_F32) -> float:

@@ -87,6 +87,16 @@ double atk_expected_recall(int64_t k, int64_t b, int64_t k_b) {
     return eq1_recall(k, b, k_b);
 }
 
+double atk_worst_case_recall(int64_t n, int64_t k, int64_t b, int64_t k_b) {
+    // Eq. 2 of Appendix C: the true top-k packed into as few buckets as possible - floor(b*k/n) buckets filled
+    // with top-k elements, of which k_b each come back, and k mod (n/b) of them in one more bucket
+    if (n < 1 || k < 1 || k > n || b < 1 || b > n || n % b != 0 || k_b < 1 || k_b > k || k_b > n / b || b * k_b < k) return -1.0;
+    const int64_t len = n / b;
+    const int64_t full = k / len, rest = k % len;  // floor(b*k/n) = floor(k / (n/b))
+    const double r = (double)(full * k_b + std::min<int64_t>(k_b, rest)) / (double)k;
+    return r > 1.0 ? 1.0 : r;
+}
+
 double atk_estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype) {
     if (atk_check_approx(m, n, k, b, k_b, dtype) != ATK_OK) return -1.0;
     return estimate_us(m, n, k, b, k_b, dtype);

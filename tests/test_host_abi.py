@@ -311,6 +311,36 @@ def test_expected_recall_is_eq1(lib):
     assert atk.expected_recall(64, 32, 1) == -1.0 and atk.expected_recall(4, 64, 8) == -1.0
 
 
+def test_worst_case_recall_is_eq2(lib):
+    """The library's Eq. 2 against the oracle's writing of it, on every legal (k, b, k_b) of small rows and on the
+    benchmark configurations; and against a row built to be the worst case, run through the oracle itself."""
+    import numpy as np
+
+    import oracle
+    from oracle import recall
+
+    for n in (12, 16, 60, 64):
+        for b in [d for d in range(1, n + 1) if n % d == 0]:
+            for k_b in range(1, n // b + 1):
+                for k in range(k_b, b * k_b + 1):
+                    assert abs(atk.worst_case_recall(n, k, b, k_b) - min(1.0, recall.worst_case_recall(n, k, b, k_b))) < 1e-12
+    for (n, k, b, k_b) in [(65536, 64, 64, 1), (65536, 64, 1024, 1), (65536, 16384, 2048, 8), (1 << 20, 1 << 18, 1 << 15, 8),
+                           (8192, 512, 512, 1)]:
+        assert abs(atk.worst_case_recall(n, k, b, k_b) - recall.worst_case_recall(n, k, b, k_b)) < 1e-12
+    # the adversarial row: the k largest values at the indices of as few (interleaved) buckets as possible
+    n, b, k_b, k = 64, 8, 2, 12
+    x = np.zeros((1, n), dtype=np.float32)
+    order = [j + t * b for j in range(b) for t in range(n // b)]  # bucket 0's indices, then bucket 1's, ...
+    for rank, i in enumerate(order[:k]):
+        x[0, i] = 100.0 - rank
+    got = set(oracle.approx_topk(x, k, b, k_b)[1][0].tolist())
+    true = set(oracle.exact_topk(x, k)[1][0].tolist())
+    assert abs(len(got & true) / k - atk.worst_case_recall(n, k, b, k_b)) < 1e-12
+    # not stated for b that does not divide n, nor for arguments the method does not allow
+    assert atk.worst_case_recall(65, 8, 8, 1) == -1.0 and atk.worst_case_recall(64, 8, 4, 1) == -1.0
+    assert atk.worst_case_recall(64, 8, 8, 9) == -1.0 and atk.worst_case_recall(64, 0, 8, 1) == -1.0
+
+
 def test_advise(lib):
     for (m, n, k, dt) in [(128, 65536, 64, atk.ATK_F32), (128, 65536, 16384, atk.ATK_F32), (64, 128256, 256, atk.ATK_BF16),
                           (128, 2653751, 100, atk.ATK_BF16), (1, 40000, 5000, atk.ATK_BF16), (4, 4096, 64, atk.ATK_F32)]:
