@@ -33,8 +33,7 @@ constexpr int kExChunk = 16384;          // elements per workgroup of the sweeps
 constexpr int kExChunkMin = 4096;        // ... down to this on smaller inputs, while a sweep stays within kExFusedMaxWgs workgroups
 constexpr int kExFusedMaxWgs = 1024;     // largest sweep whose last workgroup per row also decides the digit (see ex_hist_kernel)
 constexpr int kExRow = kExBins + kTicketStride;  // words per row of the global histograms: the bins, then the row's ticket
-constexpr int kSortTile = 2048;          // elements per workgroup of the global sort
-constexpr int kSortScanInScatter = 32;    // rows of up to this many tiles: the scatter step of the global sort scans the tile counts itself
+constexpr int kSortTile = 2048;          // granule of the sort buffers' sizes
 constexpr int kSortLdsMaxK = 4096;       // survivors ordered in LDS by one workgroup
 constexpr int kPartTile = 4096;          // survivors per workgroup of the partition sort's sweeps
 constexpr int kPartMaxBins = 2048;
@@ -476,6 +475,100 @@ __global__ void __launch_bounds__(kMaxThreads) ex_collect_kernel(const void *x, 
     }, chunk_elems);
 }
 
+// Small k on rows of moderate length, after the first digit and the copy-out path: the rows that are still open
+// (more elements in play than the copy-out buffer holds: ties, values on few levels) are rare, and a launch cannot
+// be skipped without asking the device.  So instead of one launch per remaining digit plus two to collect and order,
+// all of which usually find nothing to do, this is one launch whose workgroups return at once unless their row is
+// open; a workgroup that stays takes its row through the remaining digits alone (LDS histogram over the whole row
+// per digit), collects the k survivors in LDS and writes them in order.
+constexpr int64_t kRestMaxRow = 1 << 18;  // longest row handled this way (one workgroup re-reads it once per digit)
+template <int ELT>
+__global__ void __launch_bounds__(kMaxThreads) ex_rest_kernel(const void *x, const int32_t *xi, int64_t n, ExRowState *st, int k,
+                                                              int sq_bits, int n_passes, int chunk_elems, Squeeze sq,
+                                                              void *out_vals, int32_t *out_idx) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t lh[kExBins];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ u64 s_prefix;
+    __shared__ uint32_t s_need, s_done, s_cursor;
+    const int r = blockIdx.x, tid = threadIdx.x;
+    if (st[r].mode == 2u) return;  // finished by the copy-out path (uniform over the workgroup)
+    u64 prefix = st[r].prefix;
+    uint32_t need = st[r].need;
+    bool done = st[r].done != 0u;
+    const int chunks = (int)((n + chunk_elems - 1) / chunk_elems);
+    for (int p = 1; p < n_passes && !done; ++p) {
+        const int shift = p == n_passes - 1 ? 0 : sq_bits - kExDigit * (p + 1);
+        const int width = p == n_passes - 1 ? sq_bits - kExDigit * (n_passes - 1) : kExDigit;
+        const u64 hi_mask = (shift + width >= 64) ? 0ull : (~0ull << (shift + width));
+        const uint32_t dmask = (1u << width) - 1u;
+        for (int i = tid; i < kExBins; i += blockDim.x) lh[i] = 0u;
+        __syncthreads();
+        for (int c = 0; c < chunks; ++c)
+            for_chunk<ELT>(
+                x, xi, n, r, c,
+                [&](u64 cc, bool ok) {
+                    const u64 q = sq(cc);
+                    if (ok && (q & hi_mask) == prefix) atomicAdd(&lh[(uint32_t)(q >> shift) & dmask], 1u);
+                },
+                chunk_elems);
+        __syncthreads();
+        // the digit bucket that holds the need-th largest: lane t owns bins 2047-8t-7 .. 2047-8t (descending)
+        uint32_t hb[8], sum = 0;
+        const int base = kExBins - 8 - 8 * tid;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            hb[q] = lh[base + q];
+            sum += hb[q];
+        }
+        const uint32_t incl = wave_incl_scan_u32(sum);
+        if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+        __syncthreads();
+        uint32_t above = incl - sum;
+        for (int w = 0; w < (tid >> 6); ++w) above += wave_tot[w];
+#pragma unroll
+        for (int q = 7; q >= 0; --q) {
+            const uint32_t with = above + hb[q];
+            if (above < need && with >= need) {
+                s_prefix = prefix | ((u64)(uint32_t)(base + q) << shift);
+                s_need = need - above;
+                s_done = (hb[q] == need - above || p == n_passes - 1) ? 1u : 0u;
+            }
+            above = with;
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        need = s_need;
+        done = s_done != 0u;
+        __syncthreads();
+    }
+    // every element at or above the threshold: exactly k of them, into LDS
+    u64 *sel = (u64 *)smem;
+    uint32_t *rk = (uint32_t *)(sel + pow2_ceil_dev(k));
+    if (tid == 0) s_cursor = 0u;
+    for (int i = tid; i < kRankMax; i += blockDim.x) rk[i] = 0u;
+    __syncthreads();
+    const u64 thr = sq.expand(prefix);
+    const int lane = tid & (kWave - 1);
+    for (int c = 0; c < chunks; ++c)
+        for_chunk<ELT>(
+            x, xi, n, r, c,
+            [&](u64 cc, bool ok) {
+                const bool keep = ok && cc >= thr;
+                const u64 mask = __ballot(keep);
+                if (mask) {  // uniform over the wavefront
+                    uint32_t at = 0;
+                    if (lane == 0) at = atomicAdd(&s_cursor, (uint32_t)__popcll(mask));
+                    at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at) +
+                         __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                    if (keep && at < (uint32_t)k) sel[at] = cc;
+                }
+            },
+            chunk_elems);
+    __syncthreads();
+    order_write<ELT>(sel, k, rk, out_vals, out_idx, (int64_t)r);
+}
+
 // k <= kSortLdsMaxK: one workgroup per row orders the survivors in LDS and writes the outputs.
 template <int ELT>
 __global__ void __launch_bounds__(kMaxThreads) ex_order_lds_kernel(const u64 *sel, const ExRowState *st, int k,
@@ -795,125 +888,76 @@ __global__ void __launch_bounds__(256) part_sort_big_kernel(const u64 *src, cons
     }
 }
 
-// ---- global least-significant-digit radix sort of the survivors, descending, 8-bit digits ----
-// bin = 255 - digit, so that ascending bins are descending digits.
-// (all three kernels skip rows that the partition sort has taken, i.e. whose mode is not 3)
-__global__ void __launch_bounds__(256) sort_hist_kernel(const u64 *src, const ExRowState *st, int64_t k, int tiles,
-                                                        uint32_t *tile_hist, int shift) {
-    __shared__ uint32_t lh[256];
-    const int r = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
-    if (st[r].mode != 3u) return;
-    lh[tid] = 0;
-    __syncthreads();
-    const int64_t e0 = (int64_t)tile * kSortTile;
-    const u64 *row = src + (int64_t)r * k;
-    for (int j = 0; j < kSortTile / 256; ++j) {
-        const int64_t i = e0 + j * 256 + tid;
-        if (i < k) atomicAdd(&lh[255u - ((uint32_t)(row[i] >> shift) & 255u)], 1u);
-    }
-    __syncthreads();
-    tile_hist[((int64_t)r * tiles + tile) * 256 + tid] = lh[tid];
-}
-
-// one workgroup per row: tile_hist[tile][bin] <- number of elements of the row that sort before
-// the first element of (tile, bin): all smaller bins, and the same bin in earlier tiles
-__global__ void __launch_bounds__(256) sort_scan_kernel(uint32_t *tile_hist, const ExRowState *st, int tiles) {
-    __shared__ uint32_t wave_tot[4];
-    const int r = blockIdx.x, tid = threadIdx.x;  // tid = bin
-    if (st[r].mode != 3u) return;
-    uint32_t *th = tile_hist + (int64_t)r * tiles * 256;
-    uint32_t total = 0;
-    for (int t = 0; t < tiles; ++t) total += th[t * 256 + tid];
-    const uint32_t incl = wave_incl_scan_u32(total);
-    if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
-    __syncthreads();
-    uint32_t run = incl - total;
-    for (int w = 0; w < (tid >> 6); ++w) run += wave_tot[w];
-    for (int t = 0; t < tiles; ++t) {
-        const uint32_t c = th[t * 256 + tid];
-        th[t * 256 + tid] = run;
-        run += c;
-    }
-}
-
-// stable scatter of one tile: the tile is walked in rounds of 256 consecutive elements; inside a
-// round an element's rank among equal bins is its rank among the lanes of its wavefront with
-// that bin (eight ballots) plus the counts of the lower wavefronts.
-// SCAN (rows of few tiles): tile_hist holds the counts as sort_hist_kernel left them, and every
-// workgroup works out its own starting places from them - what sort_scan_kernel does for all tiles
-// at once, without its launch.
-template <bool SCAN>
-__global__ void __launch_bounds__(256) sort_scatter_kernel(const u64 *src, u64 *dst, const ExRowState *st, int64_t k,
-                                                           int tiles, const uint32_t *tile_hist, int shift) {
+// ---- least-significant-digit radix sort of the survivors of one row, descending, 8-bit digits ----
+// For the rows the partition sort could not take (mode 3: values piled on a few levels).  Such rows are rare,
+// and a launch cannot be skipped without asking the device: so this is one launch whose workgroups return at
+// once unless their row is in that mode, and a workgroup that stays sorts its row alone, digit by digit,
+// ping-pong between the row's two buffers - no hand-over between workgroups, no launch per digit.
+// bin = 255 - digit, so that ascending bins are descending digits.  shifts: bit s set = the digit at bit 8*s
+// differs between elements (the high bytes of the index field are the same in all of them).
+template <int ELT>
+__global__ void __launch_bounds__(256) sort_rows_kernel(u64 *buf0, u64 *buf1, const ExRowState *st, int64_t k, uint32_t shifts,
+                                                        void *out_vals, int32_t *out_idx) {
     __shared__ uint32_t running[256];
     __shared__ uint32_t wcnt[4][256];
     __shared__ uint32_t wave_tot[4];
-    const int r = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
-    if (st[r].mode != 3u) return;
+    const int r = blockIdx.x, tid = threadIdx.x;
+    if (st[r].mode != 3u) return;  // uniform over the workgroup
     const int lane = tid & 63, wave = tid >> 6;
-    if (SCAN) {
-        const uint32_t *th = tile_hist + (int64_t)r * tiles * 256;
-        uint32_t total = 0, before = 0;  // of bin tid: in the whole row, in the tiles before this one
-        for (int t = 0; t < tiles; ++t) {
-            const uint32_t c = th[t * 256 + tid];
-            total += c;
-            if (t < tile) before += c;
-        }
+    u64 *src = buf0 + (int64_t)r * k, *dst = buf1 + (int64_t)r * k;
+    for (int d = 0; d < 8; ++d) {
+        if (!((shifts >> d) & 1u)) continue;
+        const int shift = 8 * d;
+        // count the digits
+        running[tid] = 0u;
+        __syncthreads();
+        for (int64_t i = tid; i < k; i += 256) atomicAdd(&running[255u - ((uint32_t)(src[i] >> shift) & 255u)], 1u);
+        __syncthreads();
+        // running[bin] <- elements in lower bins
+        const uint32_t total = running[tid];
         const uint32_t incl = wave_incl_scan_u32(total);
         if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
-        uint32_t start = incl - total + before;
+        uint32_t start = incl - total;
         for (int w = 0; w < wave; ++w) start += wave_tot[w];
         running[tid] = start;
-    } else {
-        running[tid] = tile_hist[((int64_t)r * tiles + tile) * 256 + tid];
-    }
 #pragma unroll
-    for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
-    __syncthreads();
-    const int64_t e0 = (int64_t)tile * kSortTile;
-    const u64 *row = src + (int64_t)r * k;
-    u64 *orow = dst + (int64_t)r * k;
-    for (int j = 0; j < kSortTile / 256; ++j) {
-        const int64_t i = e0 + j * 256 + tid;
-        const bool ok = i < k;
-        const u64 c = ok ? row[i] : 0ull;
-        const uint32_t bin = 255u - ((uint32_t)(c >> shift) & 255u);
-        // lanes of this wavefront with the same bin (and a valid element)
-        u64 peers = __ballot(ok);
+        for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0u;
+        __syncthreads();
+        // Stable scatter in rounds of 256 consecutive elements: an element's rank among equal bins of its round is
+        // its rank among the lanes of its wavefront with that bin (eight ballots) plus the counts of the lower wavefronts.
+        for (int64_t base = 0; base < k; base += 256) {
+            const int64_t i = base + tid;
+            const bool ok = i < k;
+            const u64 c = ok ? src[i] : 0ull;
+            const uint32_t bin = 255u - ((uint32_t)(c >> shift) & 255u);
+            u64 peers = __ballot(ok);
 #pragma unroll
-        for (int bit = 0; bit < 8; ++bit) {
-            const u64 vote = __ballot((bin >> bit) & 1u);
-            peers &= ((bin >> bit) & 1u) ? vote : ~vote;
+            for (int bit = 0; bit < 8; ++bit) {
+                const u64 vote = __ballot((bin >> bit) & 1u);
+                peers &= ((bin >> bit) & 1u) ? vote : ~vote;
+            }
+            const uint32_t rank_in_wave =
+                __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
+            if (ok && rank_in_wave == 0) wcnt[wave][bin] = (uint32_t)__popcll(peers);
+            __syncthreads();
+            if (ok) {
+                uint32_t pos = running[bin] + rank_in_wave;
+                for (int w = 0; w < wave; ++w) pos += wcnt[w][bin];
+                dst[pos] = c;
+            }
+            __syncthreads();
+            running[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0u;
+            __syncthreads();
         }
-        const uint32_t rank_in_wave =
-            __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
-        if (ok && rank_in_wave == 0) wcnt[wave][bin] = (uint32_t)__popcll(peers);
-        __syncthreads();
-        if (ok) {
-            uint32_t pos = running[bin] + rank_in_wave;
-            for (int w = 0; w < wave; ++w) pos += wcnt[w][bin];
-            orow[pos] = c;
-        }
-        __syncthreads();
-        running[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
-        __syncthreads();
+        u64 *t = src;
+        src = dst;
+        dst = t;
+        __syncthreads();  // this workgroup's writes to the new source are visible to its own reads (same CU)
     }
-}
-
-template <int ELT>
-__global__ void __launch_bounds__(256) ex_decode_kernel(const u64 *sorted, const ExRowState *st, int64_t k, int64_t total,
-                                                        void *out_vals, int32_t *out_idx) {
-    const int r = blockIdx.y;
-    if (st[r].mode != 3u) return;
-    // a few workgroups per row stride over it: for the usual launch, in which no row is in this mode,
-    // thousands of workgroups that exit at once would cost ten times a small grid's launch
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < k; j += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t i = (int64_t)r * k + j;
-        if (i < total) write_composite<ELT>(sorted[i], out_vals, out_idx, i);
-    }
+    for (int64_t i = tid; i < k; i += 256) write_composite<ELT>(src[i], out_vals, out_idx, (int64_t)r * k + i);
 }
 
 // A kernel that is about to be launched with more dynamic LDS than a launch may ask for by default is
@@ -1015,6 +1059,15 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         pass(1, false, kSampledLast, kSampleChunk, sample_stride(k), true);
         copy_out();
     }
+    if (pl.filter && !sample && k <= kSortLdsMaxK && n <= kRestMaxRow) {
+        // first digit, copy-out path, and one launch for whatever rows are left
+        pass(0, true, (uint32_t)pl.filter_cap, pl.chunk_elems, 1, false);
+        copy_out();
+        const size_t lds = (size_t)pow2_ceil64(k) * 8 + kRankMax * 4;
+        hipLaunchKernelGGL(ex_rest_kernel<ELT>, dim3((unsigned)m), dim3(kMaxThreads), lds, stream, x, xi, n, st, (int)k, sq_bits,
+                           n_passes, pl.chunk_elems, sq, out_vals, out_idx);
+        return hipGetLastError();
+    }
     for (int p = 0; p < n_passes; ++p) {
         const bool filter_now = p == 0 && pl.filter && !sample;
         pass(p, p == 0 && !sample, filter_now ? (uint32_t)pl.filter_cap : 0u, pl.chunk_elems, 1, sample);
@@ -1035,7 +1088,7 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
     }
     u64 *bufs[2] = {sel, sel + m * k};
     uint32_t *tile_hist = (uint32_t *)(bufs[1] + m * k);
-    const int tiles = (int)ceil_div64(k, kSortTile);
+    const int tiles = (int)ceil_div64(k, kSortTile);  // (the area behind the buffers, sized in tiles, holds the partition sort's tables)
     // partition sort: about 128 survivors per bin
     {
         int nb = 16;
@@ -1061,27 +1114,14 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    // rows the partition sort could not take (mode 3): stable least-significant-digit sort; digits that are
-    // the same for every element (high bits of the index field) are skipped
+    // rows the partition sort could not take (mode 3): one launch, a workgroup per such row; digits that are the same
+    // for every element (high bytes of the index field) are skipped
     // (the index field holds 0x7fffffff - idx in bits [31:1]; bit 0 is the zero-sign flag)
-    int cur = 0;
-    for (int shift = 0; shift < 64; shift += 8) {
-        if (shift < 32 && shift >= idx_bits + 1) continue;
-        const dim3 grid((unsigned)tiles, (unsigned)m);
-        hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(256), 0, stream, bufs[cur], st, k, tiles, tile_hist, shift);
-        if (tiles <= kSortScanInScatter) {
-            hipLaunchKernelGGL(sort_scatter_kernel<true>, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], st, k, tiles,
-                               tile_hist, shift);
-        } else {
-            hipLaunchKernelGGL(sort_scan_kernel, dim3((unsigned)m), dim3(256), 0, stream, tile_hist, st, tiles);
-            hipLaunchKernelGGL(sort_scatter_kernel<false>, grid, dim3(256), 0, stream, bufs[cur], bufs[cur ^ 1], st, k, tiles,
-                               tile_hist, shift);
-        }
-        cur ^= 1;
-    }
-    const int64_t total = m * k;
-    hipLaunchKernelGGL(ex_decode_kernel<ELT>, dim3((unsigned)std::min<int64_t>(ceil_div64(k, 256), 32), (unsigned)m), dim3(256), 0, stream, bufs[cur],
-                       st, k, total, out_vals, out_idx);
+    uint32_t shifts = 0;
+    for (int shift = 0; shift < 64; shift += 8)
+        if (!(shift < 32 && shift >= idx_bits + 1)) shifts |= 1u << (shift / 8);
+    hipLaunchKernelGGL(sort_rows_kernel<ELT>, dim3((unsigned)m), dim3(256), 0, stream, bufs[0], bufs[1], st, k, shifts, out_vals,
+                       out_idx);
     return hipGetLastError();
 }
 
