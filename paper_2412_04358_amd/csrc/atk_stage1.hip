@@ -68,6 +68,42 @@ __device__ __forceinline__ void insert(float (&val)[KB], int (&tt)[KB], float v,
     tt[0] = c[0] ? t : tt[0];
 }
 
+// ---- batch scan for long queues (k_b > 8) -------------------------------------------------------------------------
+// Inserting element by element costs about five lane operations per slot and element.  Where most elements enter
+// the queue (short buckets: the top quarter of every bucket is kept when b*k_b = k = n/4) it is cheaper to take
+// k_b matrix rows at a time, sort them with a network, and fold the sorted batch into the queue with the
+// bitonic merge that also joins the lanes' queues: about 3.3 lane operations per slot and element.  A network has no
+// notion of "earlier element wins ties", so the queues hold words that are distinct: [63:32] the value's order
+// key, [31:1] 0x7fffffff - matrix row, [0] "was -0" (the composite word with the row in place of the column index).
+__device__ __forceinline__ u64 row_word(uint32_t bits, int t) {
+    return ((u64)ukey_of_bits(bits) << 32) | ((0x7fffffffu - (uint32_t)t) << 1) | (bits == 0x80000000u ? 1u : 0u);
+}
+// Batcher's odd-even merge sort of N words, largest first (N a power of two; 19 compare-exchanges for 8, 63 for 16).
+template <int N>
+__device__ __forceinline__ void sort_desc(u64 (&a)[N]) {
+#pragma unroll
+    for (int p = 1; p < N; p *= 2)
+#pragma unroll
+        for (int k = p; k >= 1; k /= 2)
+#pragma unroll
+            for (int j = k % p; j + k < N; j += 2 * k)
+#pragma unroll
+                for (int i = 0; i < k; ++i)
+                    if (i + j + k < N && (i + j) / (2 * p) == (i + j + k) / (2 * p)) {
+                        const u64 x = a[i + j], y = a[i + j + k];
+                        const bool sw = y > x;
+                        a[i + j] = sw ? y : x;
+                        a[i + j + k] = sw ? x : y;
+                    }
+}
+// one word into a queue sorted largest first
+template <int KB>
+__device__ __forceinline__ void insert_word(u64 (&q)[KB], u64 c) {
+#pragma unroll
+    for (int j = KB - 1; j >= 1; --j) q[j] = (c > q[j - 1]) ? q[j - 1] : (c > q[j] ? c : q[j]);
+    q[0] = c > q[0] ? c : q[0];
+}
+
 // Feed the V elements of one load into the lane's V queues.  With k_b > 1 the insertion costs
 // about 5*k_b lane operations per element, so it is skipped whenever no lane of the wavefront
 // holds an element that beats the last slot of its queue (one compare per element and a
@@ -298,6 +334,10 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     trace_mark<TR>(p.trace, 0);  // the wavefront has started
     constexpr int ES = (ELT == ATK_F32) ? 4 : 2;
     constexpr bool PK = PKF && ELT == ATK_BF16 && KB >= 4;  // packed 32-bit queues (host: rows per split < 32766)
+    // queues of distinct 64-bit words, fed k_b matrix rows at a time: pays from sixteen slots on (128 x 65536 f32,
+    // k = 16384, k_b = 16: 44.8 -> 36.0 us; with eight slots the 64-bit compares cost more than the shorter
+    // network saves: 19.2 -> 21.8 us, and 164 -> 185 us on 128 x 2^20, b = 8)
+    constexpr bool BATCH = KB >= 16 && !PK;
     const int tid = threadIdx.x, T = blockDim.x;
     int wg = blockIdx.x, cb, sp, r, cgl, ph;
     divmod(wg, p.colblocks, p.cb_shift, wg, cb);
@@ -342,6 +382,8 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     float val[V][KB];
     int tt[V][KB];
     uint32_t pk[PK ? V : 1][PK ? KB : 1];
+    u64 qw[BATCH ? V : 1][BATCH ? KB : 1];  // BATCH: the queues, as row words
+    float last_f[BATCH ? V : 1];            // ... and the value of each queue's last slot (NaN while it is empty)
 #pragma unroll
     for (int e = 0; e < V; ++e)
 #pragma unroll
@@ -349,20 +391,28 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
             val[e][j] = __uint_as_float(0x7fc00000u);
             tt[e][j] = kEmptyT;
             if constexpr (PK) pk[e][j] = 0u;
+            if constexpr (BATCH) {
+                qw[e][j] = 0ull;
+                last_f[e] = __uint_as_float(0x7fc00000u);
+            }
         }
-#define ATK_FEED_VEC(vec, row)                                  \
-    do {                                                        \
-        if constexpr (PK)                                       \
-            scan_vec_pk<ELT, V, KB>(pk, vec, (row) - t0);       \
-        else                                                    \
-            scan_vec<ELT, V, KB>(val, tt, vec, (row));          \
-    } while (0)
 #define ATK_FEED_ELEM(e, xb, row)                                                                    \
     do {                                                                                             \
         if constexpr (PK)                                                                            \
             insert_pk<KB>(pk[e], pack_bf16(xb, (uint32_t)(0x7fff - ((row) - t0)) << 1));             \
+        else if constexpr (BATCH)                                                                    \
+            insert_word<KB>(qw[e], row_word(xb, (row)));                                             \
         else                                                                                         \
             insert<KB>(val[e], tt[e], __uint_as_float(xb), (row));                                   \
+    } while (0)
+#define ATK_FEED_VEC(vec, row)                                                                       \
+    do {                                                                                             \
+        if constexpr (PK)                                                                            \
+            scan_vec_pk<ELT, V, KB>(pk, vec, (row) - t0);                                            \
+        else if constexpr (BATCH) {                                                                  \
+            _Pragma("unroll") for (int e_ = 0; e_ < V; ++e_) ATK_FEED_ELEM(e_, (elem_bits<ELT, V>(vec, e_)), (row)); \
+        } else                                                                                       \
+            scan_vec<ELT, V, KB>(val, tt, vec, (row));                                               \
     } while (0)
 
     // ---------------------------------------------------------------- streaming scan
@@ -379,7 +429,57 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
                 if (e >= rot) ATK_FEED_ELEM(e, (elem_bits<ELT, V>(v, e)), 0);
             t += step;
         }
-        if (KB == 8) {
+        if constexpr (BATCH) {
+            // k_b matrix rows at a time; the next batch's loads are issued before this one is worked on.  Rows past
+            // the end re-read row t and are dropped.
+            RowVec<ELT, V> v[KB], w[KB];
+            bool have = t < t1;
+            if (have) {
+#pragma unroll
+                for (int u = 0; u < KB; ++u) {
+                    const int tu = t + u * step;
+                    v[u] = load_vec<ELT, V>(base + (int64_t)(tu < t1 ? tu : t) * row_bytes);
+                }
+            }
+            while (have) {
+                const int tn = t + KB * step;
+                const bool more = tn < t1;
+                if (more) {
+#pragma unroll
+                    for (int u = 0; u < KB; ++u) {
+                        const int tu = tn + u * step;
+                        w[u] = load_vec<ELT, V>(base + (int64_t)(tu < t1 ? tu : tn) * row_bytes);
+                    }
+                }
+                // one compare per element, and a wavefront-uniform skip, keep long buckets cheap: an element enters
+                // only if it beats the queue's last slot (equal values never displace earlier ones)
+                bool any = false;
+#pragma unroll
+                for (int u = 0; u < KB; ++u)
+#pragma unroll
+                    for (int e = 0; e < V; ++e)
+                        any = any || (t + u * step < t1 && !(__uint_as_float(elem_bits<ELT, V>(v[u], e)) <= last_f[e]));
+                if (__ballot(any) != 0ull) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        u64 bt[KB];
+#pragma unroll
+                        for (int u = 0; u < KB; ++u) {
+                            const int tu = t + u * step;
+                            bt[u] = tu < t1 ? row_word(elem_bits<ELT, V>(v[u], e), tu) : 0ull;
+                        }
+                        sort_desc<KB>(bt);
+                        merge_topk<KB>(qw[e], bt);
+                        const uint32_t lk = (uint32_t)(qw[e][KB - 1] >> 32);
+                        last_f[e] = __uint_as_float(qw[e][KB - 1] ? bits_of_ukey(lk) : 0x7fc00000u);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < KB; ++u) v[u] = w[u];
+                t = tn;
+                have = more;
+            }
+        } else if (KB == 8) {
             // The next batch's loads are issued before the current one is worked on (measured:
             // 4-7 % at eight slots, nothing or a loss at other queue lengths).
             RowVec<ELT, V> v[U], w[U];
@@ -485,6 +585,18 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
 #undef ATK_FEED_VEC
 #undef ATK_FEED_ELEM
     trace_mark<TR>(p.trace, 1);  // its share of the row is in
+    if constexpr (BATCH) {
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+#pragma unroll
+            for (int j = 0; j < KB; ++j) {
+                const u64 c = qw[e][j];
+                if (c != 0ull) {
+                    val[e][j] = __uint_as_float(((uint32_t)c & 1u) ? 0x80000000u : bits_of_ukey((uint32_t)(c >> 32)));
+                    tt[e][j] = (int)(0x7fffffffu - ((uint32_t)c >> 1));
+                }
+            }
+    }
     if constexpr (PK) {
 #pragma unroll
         for (int e = 0; e < V; ++e)
