@@ -121,6 +121,11 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (!v_want && dtype == ATK_BF16 && p.KB >= 8 && b >= 1024 && m * b >= 256 * (int64_t)kNumCU &&
         m * b <= (p.KB >= 16 ? 512 : 1024) * (int64_t)kNumCU)
         v_want = 1;
+    // f32 queues of 16 slots (fed sixteen matrix rows at a time, a long chain of dependent compare-exchanges) the same
+    // way while two columns per lane would leave one wavefront per SIMD: 128 x 65536, b = 1024: 36.1 -> 27.0 us
+    // (with more lanes than that two columns win: 128 x 2^20, b = 16384: 297 against 325 us)
+    if (!v_want && dtype == ATK_F32 && p.KB >= 16 && b >= 1024 && m * b >= 256 * (int64_t)kNumCU && m * b <= 512 * (int64_t)kNumCU)
+        v_want = 1;
     p.V = stage1_pick_v(dtype, p.KB, v_want, b);
     p.G = b / p.V;
     p.L = n / b;

@@ -226,6 +226,13 @@ def test_plan_override(lib, plan_override):
     assert q["T"] in (256, 512)
 
 
+def test_long_queue_lane_widths(lib):
+    """f32 queues of 16 slots take one column per lane while two would leave one wavefront per SIMD, two beyond."""
+    assert atk.plan_describe(128, 65536, 16384, 1024, 16).startswith("V=1 KB=16 ")
+    assert atk.plan_describe(128, 1 << 20, 1 << 18, 1 << 14, 16).startswith("V=2 KB=16 ")
+    assert atk.plan_describe(128, 65536, 16384, 2048, 8).startswith("V=2 KB=8 ")
+
+
 def test_workspace_bytes(lib):
     assert lib.atk_workspace_bytes(128, 65536, 16384, 16384, 1, 0) == 0
     assert lib.atk_workspace_bytes(128, 65536, 64, 64, 1, 0) == 0  # whole buckets per workgroup: no hand-over
