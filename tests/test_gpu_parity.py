@@ -503,6 +503,8 @@ HAND_OVER_CASES = [
     ("3 x 2^18 b=256 S=64", (3, 1 << 18, 52, "f32"), (64, 256, 1), "S=64", "S=64 "),
     ("5 x 2^18 bf16 b=64 k_b=4 S=16 P=4", (5, 1 << 18, 53, "bf16"), (100, 64, 4), "S=16,P=4", "S=16 "),
     ("cfg2 b=512 two workgroups per row", ("cfg2",), (64, 512, 1), "S=2", "scratch=1"),
+    ("cfg2 b=256 helper + finisher", ("cfg2",), (64, 256, 1), None, "pair_rows=128"),
+    ("cfg2 b=512 helper + finisher", ("cfg2",), (64, 512, 1), None, "pair_rows=60"),
 ]
 
 
@@ -543,6 +545,97 @@ def test_repeat_runs_of_exact_topk(shape):
         atk.approx_topk(other, 64, 64 << (run % 3), 1)
 
     _repeat_against_oracle(x, lambda xg: atk.exact_topk(xg, k), expect, 20, "exact %s" % (shape,), between)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_helper_finisher_pairs(dtype, plan_override):
+    """Stage 2 with two workgroups per row (the helper leaves its maxima in a mailbox in memory, the finisher
+    picks them up): the plans the library chooses on its own, ties and special values included, and forced on
+    shapes it would not choose them for - every split of the matrix rows, workgroup sizes, streaming lane counts."""
+    dt = atk.ATK_F32 if dtype == "f32" else atk.ATK_BF16
+    for (m, n) in [(6, 65536), (128, 65536), (40, 1 << 17)]:
+        for (k, b) in [(64, 128), (100, 256), (64, 512), (17, 64 * 5)]:
+            plan = atk.plan_describe(m, n if n % b == 0 else n // b * b, k, b, 1, dt)
+            nn = n if n % b == 0 else n // b * b
+            if m == 128 and nn == n:  # (fewer rows are split over more than two workgroups, with tickets)
+                assert " lean=1 " in plan and " pair_rows=0" not in plan, plan
+            run_case(workloads.normal_rows(m, nn, seed=950 + b, dtype=dtype), k, b, 1, tag="pair")
+        run_case(workloads.few_levels(m, n, levels=3, seed=960, dtype=dtype), 64, 256, 1, tag="pair ties")
+        run_case(workloads.few_levels(m, n, levels=1, seed=961, dtype=dtype), 64, 128, 1, tag="pair constant")
+        run_case(workloads.special_values(m, n, seed=962, dtype=dtype), 100, 512, 1, tag="pair specials")
+    for spec in ["HF=1", "HF=1,HQ=1", "HF=1,HQ=63", "HF=1,HT=64", "HF=1,HT=128,HQ=40", "HF=1,HT=512,SL=512", "HF=1,HT=512,SL=128,HQ=9"]:
+        plan_override(spec)
+        for (m, n, k, b) in [(3, 8192, 64, 128), (300, 4096, 16, 64), (5, 36864, 100, 256), (2, 65536, 64, 1024),
+                             (2, 1 << 16, 1000, 2048)]:
+            x = workloads.normal_rows(m, n, seed=970 + b, dtype=dtype)
+            print(spec, atk.plan_describe(m, n, k, b, 1, dt), flush=True)
+            run_case(x, k, b, 1, tag=spec)
+        run_case(workloads.few_levels(4, 16384, levels=2, seed=980, dtype=dtype), 30, 128, 1, tag=spec + " ties")
+        run_case(workloads.special_values(4, 16384, seed=981, dtype=dtype), 64, 256, 1, tag=spec + " specials")
+    plan_override(None)
+
+
+@pytest.mark.parametrize("spec", ["LN=0", "LN=0,LM=0", "HF=0", "HF=0,SL=64"])
+def test_headline_shapes_on_every_kernel(spec, plan_override):
+    """The configurations of the headline sweep and of the attention-score shape through the general kernel (LN=0:
+    no lean kernels; LM=0: lanes merge through the LDS exchange instead of LDS atomics) and without pairs."""
+    plan_override(spec)
+    x = workloads.config_input("cfg2")
+    for k, b, k_b in workloads.CONFIGS["cfg2"]["cases"]:
+        run_case(x, k, b, k_b, tag=spec)
+    xb = workloads.normal_rows(64, 65536, seed=77, dtype="bf16")
+    for k, b, k_b in workloads.CONFIGS["cfg2"]["cases"]:
+        run_case(xb, k, b, k_b, tag=spec + " bf16")
+    run_case(workloads.few_levels(6, 65536, levels=3, seed=78), 64, 256, 1, tag=spec + " ties")
+    run_case(workloads.special_values(6, 65536, seed=79), 64, 1024, 1, tag=spec + " specials")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stage2_with_few_rows_per_lane(dtype):
+    """Stage 2 whose bins cannot take their lower end from the merge (lanes that saw only a few rows may hold values
+    far below the candidates): the selection then finds the range itself.  Also rows of small and negative values, on
+    which a loose bound would crowd the bins, and buckets that beat every bound (all-negative columns)."""
+    for (m, n, k, b) in [(8, 16384, 64, 1024), (8, 8192, 100, 2048), (128, 16384, 64, 512), (16, 32768, 64, 1024),
+                         (128, 8192, 30, 256)]:
+        run_case(workloads.normal_rows(m, n, seed=990 + b, dtype=dtype), k, b, 1, tag="few rows per lane")
+    x = workloads.normal_rows(16, 65536, seed=995) * 1e-3 - 5.0
+    x[:, ::7] = 3.0
+    run_case(x if dtype == "f32" else x.to(torch.bfloat16), 64, 256, 1, tag="negative bulk")
+    x = -torch.abs(workloads.normal_rows(16, 65536, seed=996)) - 1.0
+    run_case(x if dtype == "f32" else x.to(torch.bfloat16), 64, 512, 1, tag="all negative")
+    x = workloads.normal_rows(16, 65536, seed=997)
+    x[:, 5::64] = -1e30  # one column whose maximum lies far below every other candidate
+    run_case(x if dtype == "f32" else x.to(torch.bfloat16), 64, 64 * 4, 1, tag="one tiny column")
+    run_case(x if dtype == "f32" else x.to(torch.bfloat16), 250, 64 * 4, 1, tag="one tiny column, k near b")
+
+
+def test_trace_build_matches_and_stamps():
+    """atk_trace_approx (the measurement build of the lean kernels) returns what approx_topk returns and leaves a
+    start and an end stamp for every wavefront; shapes without that build are refused before anything is launched."""
+    lib = atk.load_library()
+    x = workloads.normal_rows(128, 65536, seed=71).cuda()
+    st = torch.cuda.current_stream().cuda_stream
+    for (k, b) in [(64, 64), (64, 256), (64, 1024)]:
+        ref_v, ref_i = atk.approx_topk(x, k, b, 1)
+        nbytes = lib.atk_trace_bytes(128, 65536, k, b, 1, atk.ATK_F32)
+        assert nbytes > 0
+        tr = torch.zeros(nbytes // 8, dtype=torch.int64, device="cuda")
+        v = torch.empty_like(ref_v)
+        i = torch.empty_like(ref_i)
+        rc = lib.atk_trace_approx(x.data_ptr(), 128, 65536, k, b, 1, atk.ATK_F32, v.data_ptr(), i.data_ptr(), tr.data_ptr(), nbytes, st)
+        assert rc == 0, atk.strerror(rc)
+        torch.cuda.synchronize()
+        assert torch.equal(i, ref_i) and torch.equal(v, ref_v)
+        t = tr.cpu().numpy().reshape(-1, 16)
+        ran = t[t[:, 0] != 0]
+        assert len(ran) > 0 and (ran[:, 9] >= ran[:, 0]).all() and (ran[:, 1] >= ran[:, 0]).all()
+        assert lib.atk_trace_approx(x.data_ptr(), 128, 65536, k, b, 1, atk.ATK_F32, v.data_ptr(), i.data_ptr(), tr.data_ptr(), 64, st) == -2
+    assert lib.atk_trace_bytes(128, 65536, 128, 64, 2, atk.ATK_F32) > 0
+    tr = torch.zeros(1 << 20, dtype=torch.int64, device="cuda")
+    v = torch.empty((128, 128), dtype=torch.float32, device="cuda")
+    i = torch.empty((128, 128), dtype=torch.int32, device="cuda")
+    assert lib.atk_trace_approx(x.data_ptr(), 128, 65536, 128, 64, 2, atk.ATK_F32, v.data_ptr(), i.data_ptr(), tr.data_ptr(), 8 << 20, st) == -4
+    assert lib.atk_trace_approx(x.data_ptr(), 128, 65536, 128, 64, 2, atk.ATK_F32, v.data_ptr(), i.data_ptr(), None, 8 << 20, st) == -1
 
 
 def test_cfg2_cfg3_bf16_and_small_batches():
