@@ -43,7 +43,8 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     const bool lean = KB == 1 && dtype == ATK_F32;
     double rate = (lean ? 7.2e6 : 6.5e6) * bytes / (bytes + (lean ? 8.0e6 : 6.0e6));  // bytes per microsecond
     if (rate < 0.5e6) rate = 0.5e6;
-    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.07 : KB == 4 ? 1.3 : KB == 8 ? 2.3 : 6.0;
+    // (sixteen slots: f32 rows go through the sorting-network scan, bf16 rows hold twice the elements per byte)
+    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.07 : KB == 4 ? 1.3 : KB == 8 ? 2.7 : (dtype == ATK_F32 ? 3.9 : 6.9);
     double us = 1.5 + (rd * queue + wr) / rate;
     const bool stage2 = b * k_b > k;
     const double cand = (double)(b * k_b);
@@ -65,11 +66,14 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     if (splits > 128.0) splits = 128.0;
     const bool split = splits >= 2.0;
     if (split || stage2) us += 2.0;
-    if (stage2) us += 2.5 + 0.0015 * cand;
+    if (stage2) us += 0.3 + 0.001 * cand;
+    // more rows than CUs: the selections of the rows that share a CU queue up behind each other (measured 2 us
+    // a row at 1024 candidates, k = 256; 7 us at k = 512, where wide key ranges send rows to the digit-by-digit form)
+    if (stage2 && m > 256) us += (double)m / 256.0 * (0.001 * cand + (k > 256 ? 0.012 : 0.004) * (double)k);
     double floor_us = 4.0;
     // lanes share column groups and merge inside the workgroup when the rows alone cannot fill the chip
     if ((double)m * groups < 16384.0) floor_us = 6.0 + bytes / 16.0e6;
-    if (split && !(stage2 && m >= 128)) floor_us = 6.5 + bytes / 12.0e6 + (stage2 ? 3.0 + 0.0015 * cand : 0.0);
+    if (split && !(stage2 && m >= 128)) floor_us = 6.5 + bytes / 12.0e6 + (stage2 ? 1.5 + 0.001 * cand : 0.0);
     if (us < floor_us) us = floor_us;
     // few rows: many splits per row, merged by the workgroup that finishes the row
     if (split && splits > 2.0) us += 0.04 * splits * (stage2 ? std::max(1.0, cand / 256.0) : 1.0);

@@ -866,3 +866,64 @@ def test_hip_graph_replay_matches_eager():
         # eager work between the replays, on the same pool
         v, i = atk.approx_topk(x2, 64, 256, 1)
         assert torch.equal(i, atk.approx_topk(x2, 64, 256, 1)[1])
+
+
+# ------------------------------------------------------------------------------- choosing (b, k_b): estimate against the clock
+def _time_call_us(x, k, b, k_b, reps=60):
+    dt = atk.ATK_F32 if x[0].dtype == torch.float32 else atk.ATK_BF16
+    m, n = x[0].shape
+    ov = torch.empty((m, k), dtype=x[0].dtype, device="cuda")
+    oi = torch.empty((m, k), dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+
+    def go(i):
+        rc = atk.approx_topk_raw(x[i % len(x)].data_ptr(), m, n, k, b, k_b, dt, ov.data_ptr(), oi.data_ptr(), st)
+        assert rc == 0, atk.strerror(rc)
+
+    for i in range(8):
+        go(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        go(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def test_runtime_estimate_and_advice_against_the_clock():
+    """atk_estimate_us (Appendix D's composition, Stage 1 + [b*k_b > k] Stage 2, with this library's measured terms)
+    within a factor 1.6 of event timings on ten shapes, and atk_advise's choice for a recall target not slower, by
+    more than that band, than the other ways of reaching the target (Appendix E: more buckets or more slots)."""
+    band = 1.6
+    shapes = [("f32", 128, 65536, [(64, 64, 1), (64, 256, 1), (64, 1024, 1), (16384, 16384, 1), (16384, 4096, 4), (16384, 1024, 16)]),
+              ("bf16", 2048, 8192, [(512, 512, 1), (512, 1024, 1)]),
+              ("f32", 8, 1 << 20, [(64, 64, 1)]),
+              ("f32", 128, 1 << 18, [(64, 512, 1)])]
+    for dtype, m, n, cases in shapes:
+        cnt = max(2, min(12, (420 << 20) // (m * n * (4 if dtype == "f32" else 2))))
+        xs = [workloads.normal_rows(m, n, seed=40 + s, dtype=dtype).cuda() for s in range(cnt)]
+        dt = atk.ATK_F32 if dtype == "f32" else atk.ATK_BF16
+        for (k, b, k_b) in cases:
+            us, est = _time_call_us(xs, k, b, k_b), atk.estimate_us(m, n, k, b, k_b, dt)
+            print("estimate %s %dx%d k=%d b=%d k_b=%d: measured %.2f us, estimated %.2f us" % (dtype, m, n, k, b, k_b, us, est), flush=True)
+            assert us / band <= est <= us * band, (dtype, m, n, k, b, k_b, us, est)
+        if (dtype, m, n) == ("f32", 128, 65536):
+            for k, target in [(64, 0.9), (16384, 0.8)]:
+                b, k_b, rec, est, reached = atk.advise(m, n, k, dt, target)
+                assert reached and rec >= target
+                t_pick = _time_call_us(xs, k, b, k_b)
+                others = []
+                for kb2 in (1, 2, 4, 8, 16):  # the cheapest b that reaches the target with kb2 slots
+                    for ratio in (1, 2, 4, 8, 16, 32, 64):
+                        b2 = -(-ratio * k // kb2)
+                        b2 += (-b2) % 4
+                        if (b2, kb2) != (b, k_b) and atk.load_library().atk_check_approx(m, n, k, b2, kb2, dt) == 0 and \
+                                atk.expected_recall(k, b2, kb2) >= target:
+                            others.append((_time_call_us(xs, k, b2, kb2), b2, kb2))
+                            break
+                print("advice k=%d target %.2f: picked b=%d k_b=%d %.2f us; others %s" % (k, target, b, k_b, t_pick, others), flush=True)
+                assert others and t_pick <= band * min(o[0] for o in others)
+        del xs
+        torch.cuda.empty_cache()
