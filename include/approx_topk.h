@@ -155,8 +155,12 @@ int atk_exact_workspace_parts(int64_t m, int64_t n, int64_t k, int dtype, int64_
  * V=<columns per lane: 1, 2, 4, 8>, P=<lanes of a workgroup sharing a column group: a power of two up to 64>,
  * PK=0 (bf16: no packed queue words), XS=0 / XS=1 (exact_topk with k <= 512: never / also on small
  * inputs guess the threshold from a sample of the row first), XC=<elements of a row per workgroup of
- * exact_topk's sweeps: a power of two from 1024 to 16384>.  Values the kernels cannot take are
- * ignored or clamped; results never depend on the plan.
+ * exact_topk's sweeps: a power of two from 1024 to 16384>, LN=0 (k_b = 1: the general kernel instead of the
+ * one specialised for running maxima), LM=0 (k_b = 1: the lanes of a column merge through per-part lists and
+ * a pass over them instead of atomic maxima in LDS), HF=0 / HF=1 (never / whenever the shape allows, two
+ * workgroups - a helper and a finisher - share a row of a Stage-2 plan), HQ=<sixty-fourths of the matrix rows
+ * that the helper takes: 1..63>, HT=<threads of such a workgroup>, SL=<lanes of a workgroup that stream>.
+ * Values the kernels cannot take are ignored or clamped; results never depend on the plan.
  */
 int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
                       int64_t buflen);

@@ -150,6 +150,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (p.KB == 1) want_threads = 512 * (int64_t)kNumCU;
     // rows short enough that a Stage 2 plan is better off in one workgroup per row than in two (below)
     const bool one_piece = n * (dtype == ATK_BF16 ? 4 : 1) <= 512 * 512;
+    // Shapes on which two workgroups share a row as helper and finisher (atk_lean.hip) instead of one workgroup, or
+    // two halves meeting through scratch and a ticket: rows of whole aligned vectors with one slot per bucket, few
+    // enough that every workgroup still has a CU of its own, long enough to be worth a second CU; past 512 buckets
+    // Stage 2 outweighs what the second CU saves unless the row has 2^17 elements or more.
+    const bool pair_rule = p.KB == 1 && p.stage2 && allow_pair && ov.hf >= 0 && !ov.lm_off && !ov.ln_off && ptr16 &&
+                           p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && 2 * m <= (int64_t)kNumCU &&
+                           n * es >= (128 << 10) && b <= 1024 && (b <= 512 || n >= (1 << 17));
     int T = 256;
     int64_t lanes_per_wg = 0;  // what a workgroup counts as when the splits are chosen (0: its size)
     if (p.G <= 256) {
@@ -249,7 +256,9 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // Long rows are the other way round: there the second workgroup per row shortens the streaming
     // part by more than the trip costs (128 x 2^20 f32, b = 1024: 90.5 us in one piece, 84.2 in two;
     // the two are level at 2^18 elements in f32 and at 2^16 in bf16).
-    if (S == 2 && p.stage2 && p.colblocks == 1 && base * T >= 256 * (int64_t)kNumCU && one_piece) S = 1;
+    // (Rows that a helper + finisher pair takes stay in one piece here: 128 x 2^20 f32, b = 1024: 83.6 us in two
+    // halves, 76.9 as a pair; 2^19: 45.7 -> 41.1; bf16 2^18, b = 256: 19.3 -> 15.9.)
+    if (S == 2 && p.stage2 && p.colblocks == 1 && ((base * T >= 256 * (int64_t)kNumCU && one_piece) || pair_rule)) S = 1;
     {
         // The workgroup that draws the last ticket merges S lists per column, SU splits per batch
         // of loads, tpc lanes per column: keep that serial tail to about four batches.
@@ -343,16 +352,19 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.lean = p.lds_max && ptr16 && p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && p.S == 1 && p.T <= 512 && !ov.ln_off;
     p.pair_rows = 0;
     if (p.lean && p.stage2 && ov.sl && ov.sl >= p.Gw && ov.sl <= p.T) p.P = ov.sl / p.Gw;  // SL=<lanes that stream> (sweeps)
-    if (p.lean && p.stage2 && p.colblocks == 1 && allow_pair && ov.hf >= 0 &&
-        (ov.hf > 0 || (2 * m <= (int64_t)kNumCU && n * es >= (128 << 10) && b <= 512))) {
+    if (p.lean && p.stage2 && p.colblocks == 1 && allow_pair && ov.hf >= 0 && (ov.hf > 0 || pair_rule)) {
         // Two workgroups per row (helper + finisher, see atk_lean.hip) while that still leaves every workgroup a CU of
         // its own, on rows long enough to be worth a second CU.  What the memory system likes is four streaming
         // wavefronts per CU on all CUs (128 x 65536 f32: 256 workgroups of 256 lanes have their rows in 1.1 us before
         // 128 of 512 do, and 256 of 512 are slower than either), so the pair streams with 256 lanes per workgroup: up to
         // 256 buckets in workgroups of 256 lanes with the rows split in half (b = 128: 9.9 -> 9.1 us, b = 256: 10.0 ->
         // 9.4 us), up to 512 buckets in workgroups of 512 lanes (Stage 2 wants a lane per candidate) of which 256 stream,
-        // the helper taking 30/64 (10.2 -> 9.9 us); beyond that Stage 2 outweighs what the second CU saves.
-        int t_pair = b <= 256 ? 256 : 512, lanes = 256, share = b <= 256 ? 32 : 30;
+        // the helper taking 30/64 (10.2 -> 9.9 us) - half on rows of 2^17 elements and more, where Stage 2 is small
+        // against the streaming (f32 2^18, b = 1024: 24.7 us at 30/64, 24.1 at half).  bf16 lanes do twice the work
+        // per load, and on rows from 2^18 elements all 512 stream (2^20, b = 256: 48.4 us with 256, 42.6 with 512;
+        // 2^17: 10.4 against 10.9).
+        int t_pair = b <= 256 ? 256 : 512, lanes = 256, share = (b <= 256 || n >= (1 << 17)) ? 32 : 30;
+        if (dtype == ATK_BF16 && n >= (1 << 18)) t_pair = lanes = 512;
         if (ov.ht && ov.ht % kWave == 0 && ov.ht <= 512) t_pair = ov.ht;
         if (ov.sl) lanes = ov.sl;
         if (ov.hq) share = ov.hq;

@@ -497,7 +497,8 @@ def _repeat_against_oracle(x_cpu, call, oracle_result, runs, tag, between):
 
 HAND_OVER_CASES = [
     # (tag, input, (k, b, k_b), plan override, what the plan must say)
-    ("cfg4 b=1024 Stage 2", ("cfg4",), (64, 1024, 1), None, "scratch=1"),
+    ("cfg4 b=1024 Stage 2", ("cfg4",), (64, 1024, 1), None, "pair_rows=512 "),
+    ("cfg4 b=1024 Stage 2 in two halves", ("cfg4",), (64, 1024, 1), "HF=0", "scratch=1"),
     ("cfg4 b=128 k_b=8 Stage 2", ("cfg4",), (64, 128, 8), None, "scratch=1"),
     ("8 x 2^20 b=64", (8, 1 << 20, 51, "f32"), (64, 64, 1), None, "scratch=1"),
     ("3 x 2^18 b=256 S=64", (3, 1 << 18, 52, "f32"), (64, 256, 1), "S=64", "S=64 "),
@@ -563,6 +564,13 @@ def test_helper_finisher_pairs(dtype, plan_override):
         run_case(workloads.few_levels(m, n, levels=3, seed=960, dtype=dtype), 64, 256, 1, tag="pair ties")
         run_case(workloads.few_levels(m, n, levels=1, seed=961, dtype=dtype), 64, 128, 1, tag="pair constant")
         run_case(workloads.special_values(m, n, seed=962, dtype=dtype), 100, 512, 1, tag="pair specials")
+    # long rows: pairs also at 1024 buckets, half the matrix rows each, all 512 lanes streaming in bf16
+    for (m, n, k, b) in [(128, 1 << 18, 64, 1024), (100, 1 << 19, 50, 256), (128, 1 << 17, 200, 1024)]:
+        plan = atk.plan_describe(m, n, k, b, 1, dt)
+        assert " lean=1 " in plan and " pair_rows=%d" % (n // b // 2) in plan and " S=1 " in plan, plan
+        if dtype == "bf16" and n >= 1 << 18:
+            assert " T=512 " in plan, plan
+        run_case(workloads.normal_rows(m, n, seed=990 + b, dtype=dtype), k, b, 1, tag="pair long")
     for spec in ["HF=1", "HF=1,HQ=1", "HF=1,HQ=63", "HF=1,HT=64", "HF=1,HT=128,HQ=40", "HF=1,HT=512,SL=512", "HF=1,HT=512,SL=128,HQ=9"]:
         plan_override(spec)
         for (m, n, k, b) in [(3, 8192, 64, 128), (300, 4096, 16, 64), (5, 36864, 100, 256), (2, 65536, 64, 1024),
