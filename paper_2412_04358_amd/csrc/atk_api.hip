@@ -359,11 +359,11 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         // 128 of 512 do, and 256 of 512 are slower than either), so the pair streams with 256 lanes per workgroup: up to
         // 256 buckets in workgroups of 256 lanes with the rows split in half (b = 128: 9.9 -> 9.1 us, b = 256: 10.0 ->
         // 9.4 us), up to 512 buckets in workgroups of 512 lanes (Stage 2 wants a lane per candidate) of which 256 stream,
-        // the helper taking 30/64 (10.2 -> 9.9 us) - half on rows of 2^17 elements and more, where Stage 2 is small
-        // against the streaming (f32 2^18, b = 1024: 24.7 us at 30/64, 24.1 at half).  bf16 lanes do twice the work
-        // per load, and on rows from 2^18 elements all 512 stream (2^20, b = 256: 48.4 us with 256, 42.6 with 512;
-        // 2^17: 10.4 against 10.9).
-        int t_pair = b <= 256 ? 256 : 512, lanes = 256, share = (b <= 256 || n >= (1 << 17)) ? 32 : 30;
+        // (10.2 -> 9.6 us).  The two take half the matrix rows each: the finisher has Stage 2 to run, but a helper
+        // with less than half measured slower all the same (b = 512: 9.97 us at 30/64 or 34/64, 9.62 at half; bf16
+        // 8.87 against 8.00).  bf16 lanes do twice the work per load, and on rows from 2^18 elements all 512 stream
+        // (2^20, b = 256: 48.4 us with 256, 42.6 with 512; 2^17: 10.4 against 10.9).
+        int t_pair = b <= 256 ? 256 : 512, lanes = 256, share = 32;
         if (dtype == ATK_BF16 && n >= (1 << 18)) t_pair = lanes = 512;
         if (ov.ht && ov.ht % kWave == 0 && ov.ht <= 512) t_pair = ov.ht;
         if (ov.sl) lanes = ov.sl;

@@ -505,7 +505,7 @@ HAND_OVER_CASES = [
     ("5 x 2^18 bf16 b=64 k_b=4 S=16 P=4", (5, 1 << 18, 53, "bf16"), (100, 64, 4), "S=16,P=4", "S=16 "),
     ("cfg2 b=512 two workgroups per row", ("cfg2",), (64, 512, 1), "S=2", "scratch=1"),
     ("cfg2 b=256 helper + finisher", ("cfg2",), (64, 256, 1), None, "pair_rows=128"),
-    ("cfg2 b=512 helper + finisher", ("cfg2",), (64, 512, 1), None, "pair_rows=60"),
+    ("cfg2 b=512 helper + finisher", ("cfg2",), (64, 512, 1), None, "pair_rows=64"),
 ]
 
 
