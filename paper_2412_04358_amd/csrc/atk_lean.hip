@@ -51,7 +51,12 @@ struct LeanParams {
 enum { kLeanOut = 0, kLeanSelect = 1, kLeanPair = 2 };
 constexpr int kLeanU = 8;  // loads in flight per lane
 
-template <int ELT, int MODE, bool TR>
+// NS, BINNED: the form of Stage 2, fixed by the host so that a kernel holds the code of one form only (all of them
+// in one kernel make 60 KB of code, of which a call runs a few KB, and the tail after the last load - a chain of
+// dependent steps through code that no wavefront has run yet in this launch - is as fast as its instructions arrive):
+// NS candidates per lane in registers (1, 2 or 4; b <= NS * blockDim.x), selected by bins with the key range that
+// comes out of the merge (BINNED) or with a range found from the merged candidates; NS = 0: digit by digit.
+template <int ELT, int MODE, int NS, bool BINNED, bool TR>
 __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int ES = (ELT == ATK_F32) ? 4 : 2;
@@ -77,7 +82,7 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
     const int t_hi = (MODE == kLeanPair && helper) ? p.Lh : p.L;
 
     u64 *cand = (u64 *)(smem + 16);
-    const bool binned = MODE != kLeanOut && binned_fits(wcols) && p.bound_ok;
+    constexpr bool binned = MODE != kLeanOut && BINNED;
     // the candidate array and the counts of Stage 2's histogram start from zero
     for (int i = tid; i < wcols; i += T) cand[i] = 0ull;
     if (tid == 0) *(uint32_t *)(smem + 4) = 0u;
@@ -252,10 +257,12 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
     }
     __syncthreads();
     trace_mark<TR>(p.trace, 3);  // all candidates of the row are in LDS, their key range is known
-    if (binned)
-        select_binned<ELT, TR>(cand, wcols, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
+    if constexpr (NS == 0)
+        select_radix_write<ELT>(cand, wcols, p.k, p.out_vals, p.out_idx, (int64_t)r);
+    else if constexpr (binned)
+        select_binned_ns<ELT, NS, TR>(cand, wcols, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
     else
-        select_write<ELT, TR>(cand, wcols, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
+        select_bucket_rank<ELT, NS, TR>(cand, wcols, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
     trace_mark<TR>(p.trace, 8);
     if (MODE == kLeanPair) {
         if (*(volatile uint32_t *)(smem + 4) != 0u) {
@@ -273,14 +280,31 @@ static int log2_exact_lean(int v) {
     return s;
 }
 
-template <int ELT, int MODE>
-static hipError_t launch_lean_mode(const Plan &pl, const LeanParams &prm, hipStream_t stream) {
+template <int ELT, int MODE, int NS, bool BINNED>
+static hipError_t launch_lean_form(const Plan &pl, const LeanParams &prm, hipStream_t stream) {
     const unsigned grid = (unsigned)pl.grid;
     if (prm.trace)
-        hipLaunchKernelGGL((lean_kernel<ELT, MODE, true>), dim3(grid), dim3((unsigned)pl.T), (size_t)pl.lds_bytes, stream, prm);
+        hipLaunchKernelGGL((lean_kernel<ELT, MODE, NS, BINNED, true>), dim3(grid), dim3((unsigned)pl.T), (size_t)pl.lds_bytes, stream, prm);
     else
-        hipLaunchKernelGGL((lean_kernel<ELT, MODE, false>), dim3(grid), dim3((unsigned)pl.T), (size_t)pl.lds_bytes, stream, prm);
+        hipLaunchKernelGGL((lean_kernel<ELT, MODE, NS, BINNED, false>), dim3(grid), dim3((unsigned)pl.T), (size_t)pl.lds_bytes, stream, prm);
     return hipGetLastError();
+}
+
+template <int ELT, int MODE>
+static hipError_t launch_lean_mode(const Plan &pl, const LeanParams &prm, hipStream_t stream) {
+    if constexpr (MODE == kLeanOut) {
+        return launch_lean_form<ELT, MODE, 0, false>(pl, prm, stream);
+    } else {
+        // Stage 2 over the b candidates of the row (one column block): candidates per lane, and whether the merge's
+        // key range serves the bins
+        const int64_t per_lane = (pl.b + pl.T - 1) / pl.T;
+        if (per_lane > kBkSlots) return launch_lean_form<ELT, MODE, 0, false>(pl, prm, stream);
+        const bool binned = pl.bound_ok != 0;
+        if (per_lane <= 1) return binned ? launch_lean_form<ELT, MODE, 1, true>(pl, prm, stream) : launch_lean_form<ELT, MODE, 1, false>(pl, prm, stream);
+        if (per_lane <= 2) return binned ? launch_lean_form<ELT, MODE, 2, true>(pl, prm, stream) : launch_lean_form<ELT, MODE, 2, false>(pl, prm, stream);
+        return binned ? launch_lean_form<ELT, MODE, kBkSlots, true>(pl, prm, stream)
+                      : launch_lean_form<ELT, MODE, kBkSlots, false>(pl, prm, stream);
+    }
 }
 
 hipError_t launch_approx_lean(const Plan &pl, const void *x, void *out_vals, int32_t *out_idx, void *state, hipStream_t stream,
