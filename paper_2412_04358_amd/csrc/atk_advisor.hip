@@ -68,8 +68,8 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     if (split || stage2) us += 2.0;
     if (stage2) us += 0.3 + 0.001 * cand;
     // more rows than CUs: the selections of the rows that share a CU queue up behind each other (measured 2 us
-    // a row at 1024 candidates, k = 256; 7 us at k = 512, where wide key ranges send rows to the digit-by-digit form)
-    if (stage2 && m > 256) us += (double)m / 256.0 * (0.001 * cand + (k > 256 ? 0.012 : 0.004) * (double)k);
+    // a row at 1024 candidates, k = 256; 3 us at k = 512)
+    if (stage2 && m > 256) us += (double)m / 256.0 * (0.001 * cand + 0.004 * (double)k);
     double floor_us = 4.0;
     // lanes share column groups and merge inside the workgroup when the rows alone cannot fill the chip
     if ((double)m * groups < 16384.0) floor_us = 6.0 + bytes / 16.0e6;

@@ -425,6 +425,34 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
             k_max = key > k_max ? key : k_max;
             k_or |= key;
         }
+    // The lower end of the bins need not be the smallest candidate: any value that k candidates reach will do, and
+    // what lies below it is out of the running.  Such a value comes for free: split the candidates into k or more
+    // groups (the lanes' own candidates, those of 2, 4, 8, 16 or 64 lanes side by side - as large as still leaves k
+    // groups); every group's maximum is a candidate, so the smallest of these maxima is reached by k candidates.  With
+    // k far below the count this drops most candidates before the histogram; with k close to the count it still drops
+    // the stragglers (small or negative values, whose keys lie far below the rest and would stretch the bins' range
+    // until the winners crowd into a few of them).
+    {
+        const int lanes_with = count < T ? count : T;  // lanes that hold a candidate: 0 .. lanes_with - 1
+        int g = 0;
+        if (lanes_with >= k) {
+            g = 1;
+            if (lanes_with / 2 >= k) g = 2;
+            if (lanes_with / 4 >= k) g = 4;
+            if (lanes_with / 8 >= k) g = 8;
+            if (lanes_with / 16 >= k) g = 16;
+            if (lanes_with / 64 >= k) g = 64;
+        }
+        if (g) {
+            uint32_t gm = k_max;  // (0 in a lane without candidates)
+            if (g >= 2) gm = max(gm, dpp_u32<0xB1>(gm));
+            if (g >= 4) gm = max(gm, dpp_u32<0x4E>(gm));
+            if (g >= 8) gm = max(gm, dpp_u32<0x141>(gm));
+            if (g >= 16) gm = max(gm, dpp_u32<0x140>(gm));
+            if (g >= 64) gm = wave_max_u32(gm);
+            k_min = gm ? gm : 0xffffffffu;  // (a group without candidates does not count: full groups alone are k)
+        }
+    }
     __syncthreads();
     // ---- range of the value keys: fold inside the wavefront, one set of LDS atomics per wavefront
     k_min = wave_min_u32(k_min);
@@ -450,11 +478,14 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
     const int rbits = 64 - __clzll((long long)span);
     const int bshift = rbits > lg_bins ? rbits - lg_bins : 0;
     uint32_t bin[NS];
+    bool live[NS];  // a candidate, and not below the lower end
 #pragma unroll
     for (int e = 0; e < NS; ++e) {
-        const u64 bk = ((u64)(((uint32_t)(c[e] >> 32) - k_min) >> tz) << idx_bits) | (((uint32_t)c[e] >> 1) & imask);
-        bin[e] = (uint32_t)(bk >> bshift);
-        if (c[e]) atomicAdd(&cnt[bin[e]], 1u);
+        const uint32_t key = (uint32_t)(c[e] >> 32);
+        live[e] = c[e] != 0ull && key >= k_min;
+        const u64 bk = ((u64)((key - k_min) >> tz) << idx_bits) | (((uint32_t)c[e] >> 1) & imask);
+        bin[e] = live[e] ? (uint32_t)(bk >> bshift) : 0u;
+        if (live[e]) atomicAdd(&cnt[bin[e]], 1u);
     }
     __syncthreads();
     trace_mark<TR>(tr, 5);  // histogram done
@@ -464,38 +495,35 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
     {
         // general q: walk the own bins from the top; q is 2, 4, 8 ... for the usual workgroup sizes
         const int hi = n_bins - 1 - tid * q;
-        uint32_t s = 0, mx = 0;
-        for (int j = 0; j < q; ++j) {
-            const uint32_t v = cnt[hi - j];
-            s += v;
-            mx = v > mx ? v : mx;
-        }
+        uint32_t s = 0;
+        for (int j = 0; j < q; ++j) s += cnt[hi - j];
         // bins not covered because 2048 is not a multiple of T go to the last thread
         if (tid == T - 1)
-            for (int bb = hi - q; bb >= 0; --bb) {
-                const uint32_t v = cnt[bb];
-                s += v;
-                mx = v > mx ? v : mx;
-            }
+            for (int bb = hi - q; bb >= 0; --bb) s += cnt[bb];
         const uint32_t incl = wave_incl_scan_u32(s);
         if (lane == kWave - 1) misc[8 + wave] = incl;
-        if (mx > (uint32_t)kBkBinMax) misc[0] = 1u;
         __syncthreads();
         const uint32_t tot = (lane < n_waves) ? misc[8 + lane] : 0u;
         const uint32_t tot_incl = wave_incl_scan_u32(tot);
         uint32_t run = incl - s;
         if (wave > 0) run += (uint32_t)__builtin_amdgcn_readlane((int)tot_incl, wave - 1);
+        bool crowded = false;  // a bin that may hold winners and is too full for the in-bin count to stay cheap
         for (int j = 0; j < q; ++j) {
+            const uint32_t v = cnt[hi - j];
             abv[hi - j + 4] = run;
-            run += cnt[hi - j];
+            crowded = crowded || (run < (uint32_t)k && v > (uint32_t)kBkBinMax);
+            run += v;
         }
         if (tid == T - 1) {
             for (int bb = hi - q; bb >= 0; --bb) {
+                const uint32_t v = cnt[bb];
                 abv[bb + 4] = run;
-                run += cnt[bb];
+                crowded = crowded || (run < (uint32_t)k && v > (uint32_t)kBkBinMax);
+                run += v;
             }
-            abv[3] = (uint32_t)count;  // "bin -1" starts behind everything
+            abv[3] = run;  // "bin -1" starts behind every candidate that was counted
         }
+        if (crowded) misc[0] = 1u;
     }
     __syncthreads();
     trace_mark<TR>(tr, 6);  // prefix done
@@ -512,7 +540,7 @@ __device__ __forceinline__ void select_bucket_rank(u64 *cand, int count, int k, 
     uint32_t start[NS];
 #pragma unroll
     for (int e = 0; e < NS; ++e) {
-        start[e] = c[e] ? abv[bin[e] + 4] : 0xffffffffu;
+        start[e] = live[e] ? abv[bin[e] + 4] : 0xffffffffu;
         if (start[e] < (uint32_t)k) cand[start[e] + atomicSub(&cnt[bin[e]], 1u) - 1u] = c[e];
     }
     __syncthreads();
