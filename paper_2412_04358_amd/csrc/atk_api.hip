@@ -183,8 +183,11 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         if (t_s2 > 512) t_s2 = 512;
         if (T < t_s2) T = t_s2;
     }
-    // many column groups but few rows: smaller workgroups rather than row splits
-    if (p.G > 256)
+    // many column groups but few rows: smaller workgroups rather than row splits.  Not with Stage 2: there the
+    // column blocks of a row have to meet in one workgroup again, through scratch and a ticket, and that workgroup
+    // then selects from all candidates with few lanes (128 x 65536 f32, b = 2048: 21.0 us in two column blocks of 256
+    // lanes, 12.0 in one workgroup of 512; k = 1000: 38.7 -> 16.0; bf16 b = 4096: 36.9 -> 18.7)
+    if (p.G > 256 && !p.stage2)
         while (T > kWave && m * ceil_div(p.G, T) < (int64_t)kNumCU) T = (int)(ceil_div(T / 2, kWave) * kWave);  // whole wavefronts (T may be 384)
     if (T_forced) { T = T_forced; lanes_per_wg = 0; }
     if (T > t_max) T = t_max;
