@@ -271,6 +271,17 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
             return ceil_div(tail_cols, T / tpc) * ceil_div(s, tpc * tail_split_batch(p.KB));
         };
         while (S > 1 && batches(S) > 4) S = (S + 1) / 2;
+        // Queues of eight and sixteen slots on few, long rows: there the insertions are what takes the time, and a lane
+        // with a thousand matrix rows to itself costs more than the longer tail (one row of 2^20, b = 256, k_b = 16:
+        // 411 us with 4 splits, 144 with 32; 16 rows of 2^18: 138 -> 102 with 8), so split down to about 128 matrix
+        // rows per lane while that stays below one workgroup per CU
+        if (p.KB >= 8) {
+            int64_t s_long = p.L / ((int64_t)p.P * 128);
+            if (s_long > 32) s_long = 32;
+            if (s_long > s_rows) s_long = s_rows;
+            while (s_long > S && base * s_long > (int64_t)kNumCU) s_long >>= 1;
+            if (S < s_long) S = s_long;
+        }
     }
     return S;
     };
