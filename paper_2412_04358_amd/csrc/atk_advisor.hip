@@ -44,7 +44,8 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     double rate = (lean ? 7.2e6 : 6.5e6) * bytes / (bytes + (lean ? 8.0e6 : 6.0e6));  // bytes per microsecond
     if (rate < 0.5e6) rate = 0.5e6;
     // (sixteen slots: f32 rows go through the sorting-network scan, bf16 rows hold twice the elements per byte)
-    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.07 : KB == 4 ? 1.3 : KB == 8 ? 2.7 : (dtype == ATK_F32 ? 3.9 : 6.9);
+    // (eight slots on long buckets: few elements still enter a queue once the lanes of a column have pooled their floors)
+    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.07 : KB == 4 ? 1.3 : KB == 8 ? (n / b >= 4096 ? 1.7 : 2.7) : (dtype == ATK_F32 ? 3.9 : 6.9);
     double us = 1.5 + (rd * queue + wr) / rate;
     const bool stage2 = b * k_b > k;
     const double cand = (double)(b * k_b);

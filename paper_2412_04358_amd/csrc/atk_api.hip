@@ -84,6 +84,7 @@ static PlanOverride parse_plan_override(const char *e) {
     }
     if (const char *q = field("HF")) o.hf = atoi(q) == 0 ? -1 : 1;
     if (const char *q = field("HT")) o.ht = atoi(q);
+    if (const char *q = field("RF")) o.rf = atoi(q) <= 0 ? -1 : atoi(q);
     if (const char *q = field("SL")) o.sl = atoi(q);
     if (const char *q = field("HQ")) {
         const int v = atoi(q);
@@ -201,6 +202,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int p_want = 1;
     if (p.KB >= 8 && p.G >= T && !T_forced)
         while (p_want < 4 && m * p.G * p_want < 64 * 4 * (int64_t)kNumCU && p.L >= 4 * p_want * 2) p_want <<= 1;
+    // Eight unpacked slots on long rows: sixteen lanes of the workgroup on a column (pieces of 128 bytes of a matrix
+    // row per wavefront), which is what the pooled floors below need; the layout alone is faster too (128 x 2^20 f32,
+    // k = 64, b = 128: 183 us with four lanes a column, 166 with sixteen, 151 with pooled floors; b = 256: 201 -> 154)
+    // (with fewer than 128 workgroups before row splits the extra splits cost more: 16 x 2^20, b = 64: 50 -> 69 us)
+    if (p.KB == 8 && dtype == ATK_F32 && !T_forced && T >= 256 && p.L >= 4096 && p.G >= T / 16 && p_want < 16 &&
+        m * ceil_div(p.G, T / 16) >= 128)
+        p_want = 16;
     const bool P_forced = ov.P != 0;
     if (P_forced) p_want = ov.P;
 
@@ -330,6 +338,16 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.rows_per_split = (int)rps;
 
     p.packed = dtype == ATK_BF16 && p.KB >= 4 && p.rows_per_split + 2 < 32768 && !ov.pk_off;
+    // Eight unpacked slots with many lanes of the workgroup on a column, each with many matrix rows: what a lane has
+    // seen alone is a poor bound on what still matters (after t rows one element in t/8 still enters its queue, and
+    // with 128 lane-columns per wavefront some lane always needs the insertion), so the lanes of a column pool their
+    // queues - after 8 load batches, then 16, 32, ... - and raise their floors to the eighth best of all.  Measured on
+    // 128 x 2^20 f32, k_b = 8: b = 8 (64 lanes a column) 162 -> 116 us, b = 16 (32 lanes) 163 -> 129, b = 32 (16 lanes)
+    // 164 -> 151; with 8 lanes a column or fewer, or under 256 rows a lane, the pooling costs more than it saves.
+    p.refresh = 0;
+    if (p.KB == 8 && !p.packed && n % p.V == 0 && ov.rf >= 0 && p.P > 1 &&
+        (ov.rf > 0 || (p.P >= 16 && p.rows_per_split / p.P >= 256)))
+        p.refresh = ov.rf > 0 ? ov.rf : 8;
     p.tail_tpc = tail_lanes_per_column(p.stage2 ? b : std::min<int64_t>(b, (int64_t)p.Gw * p.V), p.T, p.KB, p.S);
     p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
     p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
@@ -850,10 +868,10 @@ int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     else
         snprintf(buf, (size_t)buflen,
                  "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
-                 "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d lean=%d pair_rows=%d",
+                 "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d lean=%d pair_rows=%d refresh=%d",
                  pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid, stage2,
                  (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
-                 (long long)(fp.state_bytes + fp.data_bytes), (int)pl.packed, (int)pl.lean, pl.pair_rows);
+                 (long long)(fp.state_bytes + fp.data_bytes), (int)pl.packed, (int)pl.lean, pl.pair_rows, pl.refresh);
     return ATK_OK;
 }
 

@@ -82,6 +82,7 @@ struct PlanOverride {
     int ht;           // HT=<lanes>: workgroup size of the two-workgroups-per-row plans, 0 not set
     int sl;           // SL=<lanes>: lanes of a workgroup that stream (the rest only join Stage 2), 0 not set
     bool ln_off;      // LN=0: never the lean kernels
+    int rf;           // RF=0: queues never pool their floors; RF=<n>: first after n load batches (0 not set)
 };
 const PlanOverride &plan_override();
 
@@ -109,6 +110,7 @@ struct Plan {
     bool direct;      // every lane owns whole buckets: write results straight from registers
     bool use_scratch; // partial lists go through global scratch + a per-row ticket
     bool packed;      // bf16, k_b >= 3: 32-bit (key, row) queue words; needs rows_per_split + 2 < 32768
+    int refresh;      // eight unpacked slots, lanes sharing columns: > 0 = the lanes of a column pool what they have seen after this many load batches (then after twice as many, ...) and raise their queues' floors to the k_b-th best of all
     bool lds_max;     // k_b = 1, no scratch, lanes share columns: they meet in LDS by atomic maximum
     bool bound_ok;    // lds_max with Stage 2: the merge yields a tight lower bound on the smallest candidate (see select_binned())
     bool lean;        // k_b = 1 on rows of whole aligned 16-byte vectors, one workgroup (or a pair) per row: the lean kernels

@@ -48,6 +48,7 @@ struct S1Params {
     int NB;              // short buckets: buckets a lane group takes in turn (0: one bucket per group)
     int lds_max;         // k_b = 1, no scratch: the lanes' running maxima meet in LDS by atomic maximum (see the kernel)
     int bound_ok;        // ... and the lower bound on the smallest candidate that comes with that merge is tight enough for select_binned()
+    int refresh;         // eight unpacked slots: the lanes of a column pool their queues' floors after this many load batches, then twice as many, ... (0: never)
     u64 *trace;          // measurement build only: phase timestamps, [workgroup][wavefront][phase]
 };
 
@@ -102,6 +103,22 @@ __device__ __forceinline__ void insert_word(u64 (&q)[KB], u64 c) {
 #pragma unroll
     for (int j = KB - 1; j >= 1; --j) q[j] = (c > q[j - 1]) ? q[j - 1] : (c > q[j] ? c : q[j]);
     q[0] = c > q[0] ? c : q[0];
+}
+
+// mine <- the N largest of (mine U theirs), as multisets; both sorted descending, result sorted descending.
+template <int N>
+__device__ __forceinline__ void merge_keys(uint32_t (&mine)[N], const uint32_t (&theirs)[N]) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) mine[j] = max(mine[j], theirs[N - 1 - j]);
+#pragma unroll
+    for (int stride = N / 2; stride >= 1; stride >>= 1)
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            if ((i & stride) == 0) {
+                const uint32_t a = mine[i], c = mine[i + stride];
+                mine[i] = max(a, c);
+                mine[i + stride] = min(a, c);
+            }
 }
 
 // Feed the V elements of one load into the lane's V queues.  With k_b > 1 the insertion costs
@@ -328,7 +345,7 @@ __device__ __forceinline__ void row_tail(const S1Params &p, int r, int64_t tk, i
     trace_mark<TR>(p.trace, 8);  // outputs written
 }
 
-template <int ELT, int V, int KB, int U, int MAXT, bool PKF, bool TR = false>
+template <int ELT, int V, int KB, int U, int MAXT, bool PKF, bool TR = false, bool RF = false>
 __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
     extern __shared__ __align__(16) unsigned char smem[];
     trace_mark<TR>(p.trace, 0);  // the wavefront has started
@@ -415,12 +432,116 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
             scan_vec<ELT, V, KB>(val, tt, vec, (row));                                               \
     } while (0)
 
+    // ---------------------------------------------------------------- pooled floors (instances of their own: RF)
+    // Eight unpacked slots, several lanes of the workgroup on a column, many matrix rows per lane, rows that start on a
+    // load boundary (rot = 0; the host sees to all of it).  What a lane has seen alone is a poor bound on what still
+    // matters: after t rows one element in t/8 still enters its queue, and with 128 lane-columns per wavefront some
+    // lane always needs the insertion.  So after `stop` load batches - the same number in every lane, and every lane
+    // has at least that many - the lanes of a column pool what they hold: between them they have seen all elements of
+    // a stretch of the row; the eighth best of that stretch bounds the column's final eighth best from below, and every
+    // element still to come has a higher index than all of the stretch, so it has to beat that value outright.  Slots
+    // below it, and empty ones, are set to it and marked empty.  The lanes pool their queues' value keys: a butterfly
+    // inside the wavefront where lanes of a column sit side by side, then through the exchange area in LDS (free
+    // until the lists are merged at the end).  Again after twice as many batches, and so on.
+    int t_resume = t0 + ph;  // the lane's next matrix row
+    if constexpr (RF) {
+        static_assert(!RF || (KB == 8 && !PKF), "pooled floors: eight unpacked slots");
+        const unsigned char *base = (const unsigned char *)p.x + ((int64_t)r * p.n + (int64_t)col0) * ES;
+        const int64_t row_bytes = (int64_t)p.b * ES;
+        const int step = p.P;
+        const int nfull = ((t1 - t0) / p.P) / U;  // full batches that every row phase has
+        int done = 0;
+        for (int stop = p.refresh; stop > 0 && stop < nfull; stop *= 2) {
+            if (active) {
+                // the batches up to the stop; the next batch's loads are issued before the current one is worked on
+                const int nb = stop - done;
+                int t = t_resume;
+                RowVec<ELT, V> v[U], w[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = load_vec<ELT, V>(base + (int64_t)(t + u * step) * row_bytes);
+                for (int i = 0; i < nb; ++i) {
+                    const int tn = t + U * step;
+                    if (i + 1 < nb) {
+#pragma unroll
+                        for (int u = 0; u < U; ++u) w[u] = load_vec<ELT, V>(base + (int64_t)(tn + u * step) * row_bytes);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) ATK_FEED_VEC(v[u], t + u * step);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) v[u] = w[u];
+                    t = tn;
+                }
+                t_resume = t;
+            }
+            done = stop;
+            uint32_t keys[V][KB];
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+#pragma unroll
+                for (int j = 0; j < KB; ++j)
+                    keys[e][j] = (active && tt[e][j] != kEmptyT) ? ukey_of_bits(__float_as_uint(val[e][j])) : 0u;
+            if (p.wave_merge) {
+                for (int off = p.Gw; off < kWave; off <<= 1) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        uint32_t theirs[KB];
+#pragma unroll
+                        for (int j = 0; j < KB; ++j) theirs[j] = (uint32_t)__shfl_xor((int)keys[e][j], off, kWave);
+                        merge_keys<KB>(keys[e], theirs);
+                    }
+                }
+            }
+            if (p.nparts > 1) {
+                uint32_t *xk = (uint32_t *)(smem + p.lds_xch_off);  // [part][column of the workgroup][slot]
+                const int part = p.wave_merge ? (tid >> 6) : ph;
+                const bool holder = active && (!p.wave_merge || (tid & (kWave - 1)) < p.Gw);
+                const int64_t pstride = (int64_t)p.Gw * V;
+                if (holder) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e)
+#pragma unroll
+                        for (int j = 0; j < KB; ++j) xk[((int64_t)part * pstride + cgl * V + e) * KB + j] = keys[e][j];
+                }
+                __syncthreads();
+                if (active) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+#pragma unroll
+                        for (int j = 0; j < KB; ++j) keys[e][j] = xk[((int64_t)cgl * V + e) * KB + j];
+                        for (int q = 1; q < p.nparts; ++q) {
+                            uint32_t theirs[KB];
+#pragma unroll
+                            for (int j = 0; j < KB; ++j) theirs[j] = xk[((int64_t)q * pstride + cgl * V + e) * KB + j];
+                            merge_keys<KB>(keys[e], theirs);
+                        }
+                    }
+                }
+                __syncthreads();  // (the area is written again at the next stop, and by the merge at the end)
+            }
+            if (active) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const uint32_t fk = keys[e][KB - 1];
+                    if (fk != 0u) {  // eight elements of the column have been seen
+                        const float floor_v = __uint_as_float(bits_of_ukey(fk));
+#pragma unroll
+                        for (int j = 0; j < KB; ++j)
+                            if (tt[e][j] == kEmptyT || val[e][j] < floor_v) {
+                                val[e][j] = floor_v;
+                                tt[e][j] = kEmptyT;
+                            }
+                    }
+                }
+            }
+        }
+    }
+
     // ---------------------------------------------------------------- streaming scan
     if (active) {
         const unsigned char *base = (const unsigned char *)p.x + ((int64_t)r * p.n - rot + (int64_t)col0) * ES;
         const int64_t row_bytes = (int64_t)p.b * ES;
         const int step = p.P;
-        int t = t0 + ph;
+        int t = t_resume;
         if (V > 1 && rot > 0 && cg == 0 && t == 0 && t < t1) {
             // the head of the virtual row: its first `rot` elements are not this row's
             RowVec<ELT, V> v = load_vec<ELT, V>(base);
@@ -997,6 +1118,13 @@ static hipError_t launch_one(const Plan &pl, const S1Params &prm, hipStream_t st
         }
     }
     if (prm.trace) return hipErrorNotSupported;  // the measurement build exists for the lean kernels only
+    if constexpr (KB == 8) {
+        if (pl.refresh) {
+            hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U, MAXT, false, false, true>), dim3((unsigned)pl.grid),
+                               dim3((unsigned)pl.T), (size_t)pl.lds_bytes, stream, prm);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((stage1_kernel<ELT, V, KB, U, MAXT, false>), dim3((unsigned)pl.grid), dim3((unsigned)pl.T),
                        (size_t)pl.lds_bytes, stream, prm);
     return hipGetLastError();
@@ -1043,6 +1171,7 @@ hipError_t launch_approx(const Plan &pl, const void *x, void *out_vals, int32_t 
     prm.lds_cand_off = pl.lds_cand_off;
     prm.lds_max = pl.lds_max;
     prm.bound_ok = pl.bound_ok;
+    prm.refresh = pl.refresh;
     prm.wgs_per_ticket = pl.stage2 ? pl.S * pl.colblocks : pl.S;
     prm.tail_tpc_shift = log2_exact(pl.tail_tpc);
     prm.cb_shift = log2_exact(pl.colblocks);

@@ -583,6 +583,38 @@ def test_helper_finisher_pairs(dtype, plan_override):
     plan_override(None)
 
 
+def test_pooled_queue_floors(plan_override):
+    """Eight-slot queues whose lanes pool what they have seen and raise their floors mid-scan (Appendix A's per-thread
+    queues, shared between the threads of a bucket before the final merge): the plans that do it on their own, on
+    normal, tie-heavy, constant, special-valued and sorted rows (ascending rows make every element enter, descending
+    rows none after the first), and forced onto small shapes from the first load batch on."""
+    def inputs(m, n, seed):
+        x = workloads.normal_rows(m, n, seed=seed)
+        yield "normal", x
+        yield "three levels", workloads.few_levels(m, n, levels=3, seed=seed + 1)
+        yield "constant", workloads.few_levels(m, n, levels=1, seed=seed + 2)
+        yield "specials", workloads.special_values(m, n, seed=seed + 3)
+        yield "ascending", torch.sort(x, dim=1).values.contiguous()
+        yield "descending", torch.sort(x, dim=1, descending=True).values.contiguous()
+    for (m, n, k, b) in [(128, 1 << 20, 64, 8), (128, 1 << 20, 40, 16), (128, 1 << 20, 64, 128)]:
+        plan = atk.plan_describe(m, n, k, b, 8, atk.ATK_F32)
+        assert " refresh=8" in plan, plan
+        run_case(workloads.normal_rows(m, n, seed=1200 + b), k, b, 8, tag="pooled floors")
+    for (m, n, k, b) in [(3, 1 << 20, 64, 8), (2, 1 << 19, 100, 32)]:
+        plan_override("RF=8")
+        assert " refresh=8" in atk.plan_describe(m, n, k, b, 8, atk.ATK_F32)
+        for name, x in inputs(m, n, 1210 + b):
+            run_case(x, k, b, 8, tag="pooled floors, " + name)
+    for spec in ["RF=1", "RF=2", "RF=3,P=4", "RF=1,T=64", "RF=1,S=3"]:
+        plan_override(spec)
+        for (m, n, k, b) in [(5, 8192, 16, 8), (3, 40000, 64, 16), (2, 1 << 16, 64, 128), (7, 30000, 24, 24)]:
+            plan = atk.plan_describe(m, n, k, b, 8, atk.ATK_F32)
+            print(spec, plan, flush=True)
+            for name, x in inputs(m, n, 1230 + b):
+                run_case(x, k, b, 8, tag=spec + ", " + name)
+    plan_override(None)
+
+
 @pytest.mark.parametrize("spec", ["LN=0", "LN=0,LM=0", "HF=0", "HF=0,SL=64"])
 def test_headline_shapes_on_every_kernel(spec, plan_override):
     """The configurations of the headline sweep and of the attention-score shape through the general kernel (LN=0:
