@@ -22,8 +22,12 @@
  * they enqueue kernels and return; buffers must stay valid until the stream has drained.
  * A per-device scratch pool (partial results, tickets, radix-select state) is owned by
  * the library; it grows on demand (growing allocates, which may synchronise the device)
- * and is shared by all calls on a device, so calls that may run concurrently on
- * different streams of one device must be serialised by the caller.
+ * and is shared by all calls on a device.  A call that needs the pool on another stream than
+ * the call before it first waits, on the host, for that earlier stream to drain (calls
+ * that stay on one stream never wait); calls from different host threads are serialised by
+ * a lock around the pool, not around the launches, so threads that share a device should
+ * share a stream or order their calls themselves.  Because of the allocation and the wait,
+ * approx_topk and exact_topk are not for streams under graph capture: approx_topk_noalloc is.
  *
  * Every function returns ATK_OK (0) or a negative error code.  Arguments are checked on
  * the host before any HIP call is made; nothing is launched when a check fails.

@@ -540,8 +540,13 @@ static std::mutex g_pool_mu;
 enum { kPoolState = 0, kPoolData = 1 };
 static void *g_pool_ptr[64][2];
 static size_t g_pool_bytes[64][2];
+static hipStream_t g_pool_stream[64];  // the stream of the last call that took a pool on the device
+static bool g_pool_stream_set[64];
 
-static hipError_t get_pool(int which, size_t bytes, void **out) {
+// The pools are per device, not per stream: work queued on one stream may still be using them when a call arrives
+// on another.  Such a call first waits, on the host, for the stream of the call before it (calls that stay on one
+// stream never wait: their kernels are ordered by the stream).
+static hipError_t get_pool(int which, size_t bytes, void **out, hipStream_t stream) {
     *out = nullptr;
     if (bytes == 0) return hipSuccess;
     int dev = 0;
@@ -549,6 +554,15 @@ static hipError_t get_pool(int which, size_t bytes, void **out) {
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     std::lock_guard<std::mutex> lock(g_pool_mu);
+    if (g_pool_stream_set[dev] && g_pool_stream[dev] != stream) {
+        if (hipStreamSynchronize(g_pool_stream[dev]) != hipSuccess) {  // (the stream may be gone by now)
+            (void)hipGetLastError();
+            e = hipDeviceSynchronize();
+            if (e != hipSuccess) return e;
+        }
+    }
+    g_pool_stream[dev] = stream;
+    g_pool_stream_set[dev] = true;
     if (g_pool_bytes[dev][which] < bytes) {
         if (g_pool_ptr[dev][which]) {
             e = hipFree(g_pool_ptr[dev][which]);  // waits for work that may still use it
@@ -772,9 +786,9 @@ static int run_approx(const void *x, int64_t m, int64_t n, int64_t k, int64_t b,
         if (trace_bytes < fp.s1.grid * kTraceWaves * kTracePhases * 8 || fp.s1.T > kTraceWaves * kWave) return ATK_ERR_BAD_SHAPE;
     }
     void *state = nullptr, *data = nullptr;
-    hipError_t e = get_pool(kPoolState, (size_t)fp.state_bytes, &state);
+    hipError_t e = get_pool(kPoolState, (size_t)fp.state_bytes, &state, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
-    e = get_pool(kPoolData, (size_t)fp.data_bytes, &data);
+    e = get_pool(kPoolData, (size_t)fp.data_bytes, &data, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
     void *s1_vals = out_vals;
     int32_t *s1_idx = out_idx;
@@ -938,9 +952,9 @@ int exact_topk(const void *x, int64_t m, int64_t n, int64_t k, int dtype, void *
     rc = make_exact_plans(m, n, k, dtype, &pl, &state_bytes, &data_bytes);
     if (rc != ATK_OK) return rc;
     void *state = nullptr, *data = nullptr;
-    hipError_t e = get_pool(kPoolState, (size_t)state_bytes, &state);
+    hipError_t e = get_pool(kPoolState, (size_t)state_bytes, &state, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
-    e = get_pool(kPoolData, (size_t)data_bytes, &data);
+    e = get_pool(kPoolData, (size_t)data_bytes, &data, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
     return run_exact(pl, x, nullptr, m, n, k, dtype, out_vals, out_idx, state, state_bytes, data, data_bytes,
                      (hipStream_t)stream);

@@ -583,6 +583,32 @@ def test_helper_finisher_pairs(dtype, plan_override):
     plan_override(None)
 
 
+def test_calls_on_two_streams_share_the_scratch_pools():
+    """The scratch pools are per device; calls that alternate between two streams must not see each other's tickets,
+    lists or mailboxes (a call on another stream than the one before it waits for that stream first)."""
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    xa = workloads.normal_rows(8, 1 << 20, seed=1300)   # row splits through scratch and tickets
+    xb = workloads.normal_rows(128, 65536, seed=1301)   # helper + finisher mailboxes
+    ea = oracle.approx_topk(workloads.as_numpy_bits(xa), 64, 64, 1, threads=THREADS)
+    eb = oracle.approx_topk(workloads.as_numpy_bits(xb), 64, 256, 1, threads=THREADS)
+    ec = oracle.exact_topk(workloads.as_numpy_bits(xb), 100, threads=THREADS)
+    ga, gb = xa.cuda(), xb.cuda()
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(6):
+        with torch.cuda.stream(s1):
+            outs.append(("a", atk.approx_topk(ga, 64, 64, 1)))
+        with torch.cuda.stream(s2):
+            outs.append(("b", atk.approx_topk(gb, 64, 256, 1)))
+        with torch.cuda.stream(s1):
+            outs.append(("c", atk.exact_topk(gb, 100)))
+    torch.cuda.synchronize()
+    for name, (v, i) in outs:
+        ev, ei = {"a": ea, "b": eb, "c": ec}[name]
+        assert np.array_equal(i.cpu().numpy(), ei), name
+        assert np.array_equal(as_bits(v), np.asarray(ev).view(as_bits(v).dtype)), name
+
+
 def test_pooled_queue_floors(plan_override):
     """Eight-slot queues whose lanes pool what they have seen and raise their floors mid-scan (Appendix A's per-thread
     queues, shared between the threads of a bucket before the final merge): the plans that do it on their own, on
