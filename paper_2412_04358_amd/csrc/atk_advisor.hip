@@ -45,7 +45,7 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     if (rate < 0.5e6) rate = 0.5e6;
     // (sixteen slots: f32 rows go through the sorting-network scan, bf16 rows hold twice the elements per byte)
     // (eight slots on long buckets: few elements still enter a queue once the lanes of a column have pooled their floors)
-    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.07 : KB == 4 ? 1.3 : KB == 8 ? (n / b >= 4096 ? 1.7 : 2.7) : (dtype == ATK_F32 ? 3.9 : 6.9);
+    const double queue = KB <= 1 ? 1.0 : KB == 2 ? 1.07 : KB == 4 ? 1.3 : KB == 8 ? (n / b >= 4096 ? 1.7 : 2.7) : (dtype == ATK_F32 && n / b < 4096 ? 3.9 : 6.9);
     double us = 1.5 + (rd * queue + wr) / rate;
     const bool stage2 = b * k_b > k;
     const double cand = (double)(b * k_b);
@@ -68,6 +68,15 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     const bool split = splits >= 2.0;
     if (split || stage2) us += 2.0;
     if (stage2) us += 0.3 + 0.001 * cand;
+    // Stage 2 behind queues: the candidates of a row come together through the general kernel's exchange, and from
+    // 2048 candidates on they are selected digit by digit (128 x 65536 f32, k = 512: b = 1024, k_b = 2 takes 24 us where
+    // b = 1024, k_b = 1 with half the candidates takes 11)
+    if (stage2 && KB >= 2) us += 0.005 * cand;
+    // more than four candidates per lane of the selecting workgroup: digit by digit (k = 512, b = 4096: 32 us)
+    if (stage2 && cand > 2048.0) us += 0.004 * cand;
+    // more candidates than one workgroup holds: Stage 1 leaves them in scratch and exact_topk's kernels select from
+    // the pairs (further launches; one workgroup per row in LDS up to 160 KB, sweeps beyond)
+    if (stage2 && b * k_b > atk_stage2_max_candidates()) us += 35.0 + 0.02 * (double)k + (double)m * cand * 24.0 / 5.0e6;
     // more rows than CUs: the selections of the rows that share a CU queue up behind each other (measured 2 us
     // a row at 1024 candidates, k = 256; 3 us at k = 512)
     if (stage2 && m > 256) us += (double)m / 256.0 * (0.001 * cand + 0.004 * (double)k);
@@ -76,6 +85,9 @@ static double estimate_us(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_
     if ((double)m * groups < 16384.0) floor_us = 6.0 + bytes / 16.0e6;
     if (split && !(stage2 && m >= 128)) floor_us = 6.5 + bytes / 12.0e6 + (stage2 ? 1.5 + 0.001 * cand : 0.0);
     if (us < floor_us) us = floor_us;
+    // long queues whose lists go through scratch: the last workgroup's merges of 8- and 16-slot lists (8 x 2^18 f32,
+    // k = 64, b = 16, k_b = 8: 25 us where the bytes and the floor say 10)
+    if (split && KB >= 8) us += KB >= 16 ? 25.0 : 15.0;
     // few rows: many splits per row, merged by the workgroup that finishes the row
     if (split && splits > 2.0) us += 0.04 * splits * (stage2 ? std::max(1.0, cand / 256.0) : 1.0);
     return us;
@@ -121,7 +133,6 @@ int atk_advise(int64_t m, int64_t n, int64_t k, int dtype, double min_recall, in
         for (int64_t ratio = 1; ratio <= 64; ratio <<= 1) {
             int64_t b = (ratio * k + k_b - 1) / k_b;
             if (ratio > 1 && b % lane) b += lane - b % lane;  // whole vector loads per lane
-            if (b * k_b > k && b * k_b > atk_stage2_max_candidates()) break;
             if (atk_check_approx(m, n, k, b, k_b, dtype) != ATK_OK) break;  // b grows with ratio: k_b > n/b from here on
             const double rec = eq1_recall(k, b, k_b), us = estimate_us(m, n, k, b, k_b, dtype);
             const bool ok = rec >= min_recall;

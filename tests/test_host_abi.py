@@ -364,9 +364,12 @@ def test_advise(lib):
     # the cheapest setting: one bucket per output, no Stage 2
     b, k_b, rec, us, reached = atk.advise(128, 65536, 64, atk.ATK_F32, 0.5)
     assert (b, k_b, reached) == (64, 1, True)
-    # k = n/4 leaves no room for more candidates: only larger k_b raises recall, and 0.99 is out of reach
+    # k = n/4: within b*k_b = k only larger k_b raises recall, and 0.99 is out of its reach; more candidates than a
+    # workgroup holds (Stage 1 into scratch, then the exact selection over the pairs) get there
     b, k_b, rec, us, reached = atk.advise(128, 65536, 16384, atk.ATK_F32, 0.99)
-    assert not reached and b * k_b == 16384 and k_b == 16
+    assert reached and rec >= 0.99 and b * k_b > lib.atk_stage2_max_candidates()
+    b, k_b, rec, us, reached = atk.advise(128, 65536, 16384, atk.ATK_F32, 0.9)
+    assert reached and b * k_b == 16384 and k_b == 16
     i64 = ctypes.c_int64
     bb, kk = i64(0), i64(0)
     assert lib.atk_advise(128, 65536, 64, 0, 1.5, ctypes.byref(bb), ctypes.byref(kk), None, None) == PARAMS
