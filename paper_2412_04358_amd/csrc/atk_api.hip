@@ -270,6 +270,10 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // (Rows that a helper + finisher pair takes stay in one piece here: 128 x 2^20 f32, b = 1024: 83.6 us in two
     // halves, 76.9 as a pair; 2^19: 45.7 -> 41.1; bf16 2^18, b = 256: 19.3 -> 15.9.)
     if (S == 2 && p.stage2 && p.colblocks == 1 && ((base * T >= 256 * (int64_t)kNumCU && one_piece) || pair_rule)) S = 1;
+    // Queues in front of Stage 2 on short rows: four splits per row give the last workgroup four lists per column to
+    // fetch and merge before it can select; two measured faster once the rows alone fill half the chip (128 x 65536
+    // f32: k = 512, b = 1024, k_b = 2: 24.0 -> 18.6 us; b = 512, k_b = 4: 25.1 -> 21.9; k = 64, b = 64, k_b = 8: 32.6 -> 29.3)
+    if (S == 4 && p.stage2 && p.KB >= 2 && base * T >= 256 * (int64_t)kNumCU && n * es <= (256 << 10)) S = 2;
     {
         // The workgroup that draws the last ticket merges S lists per column, SU splits per batch
         // of loads, tpc lanes per column: keep that serial tail to about four batches.
