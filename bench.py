@@ -51,6 +51,8 @@ def main():
                     help="phase timeline of the fused kernel on the headline workload: per b, 30 launches of the "
                          "measurement build (atk_trace_approx) on HBM-cold inputs, each right behind an ordinary launch; "
                          "prints when the first, the median and the last wavefront passed every phase boundary")
+    ap.add_argument("--probe-floors", action="store_true",
+                    help="cfg4 with eight-slot queues (k=64, b=8 and b=128), 10 calls each without and with pooled floors (for rocprofv3)")
     ap.add_argument("--probe-queues", action="store_true",
                     help="profiler run of the kernels with register queues: 5 plain copies, then 20 approx_topk calls each on "
                          "cfg3 (128 x 65536 f32, k=16384) at k_b = 1, 4, 8, 16 and on cfg5 (2048 x 8192 bf16, k=b=512); no timing")
@@ -119,6 +121,26 @@ def main():
                 raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
         torch.cuda.synchronize()
         print(json.dumps({"probe": "done", "copy_bytes": M * N * 4, "launches_each": 20, "cfg3_k_b": [1, 4, 8, 16], "cfg5": True}))
+        return
+
+    if args.probe_floors:
+        n_long = 1 << 20
+        xl = workloads.normal_rows(M, n_long, seed=0).to(dev)
+        ov = torch.empty((M, K), dtype=torch.float32, device=dev)
+        oi = torch.empty((M, K), dtype=torch.int32, device=dev)
+        st = torch.cuda.current_stream().cuda_stream
+        plans = {}
+        for spec in ("RF=0", ""):  # the override only decides whether the lanes pool their floors
+            atk.set_plan_override(spec)
+            for b in (8, 128):
+                plans["b=%d %s" % (b, spec or "default")] = atk.plan_describe(M, n_long, K, b, 8)
+                for i in range(10):
+                    rc = lib.approx_topk(xl.data_ptr(), M, n_long, K, b, 8, atk.ATK_F32, ov.data_ptr(), oi.data_ptr(), st)
+                    if rc != 0:
+                        raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
+                torch.cuda.synchronize()
+        atk.set_plan_override("")
+        print(json.dumps({"probe": "done", "launches_each": 10, "plans": plans}))
         return
 
     if args.probe_long:
