@@ -125,11 +125,19 @@ __device__ __forceinline__ void merge_keys(uint32_t (&mine)[N], const uint32_t (
 // about 5*k_b lane operations per element, so it is skipped whenever no lane of the wavefront
 // holds an element that beats the last slot of its queue (one compare per element and a
 // wavefront-uniform branch): on long buckets almost every load is rejected that way.
-template <int ELT, int V, int KB>
+template <int ELT, int V, int KB, bool PER_COLUMN = false>
 __device__ __forceinline__ void scan_vec(float (&val)[V][KB], int (&tt)[V][KB], const RowVec<ELT, V> &v, int t) {
     float x[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) x[e] = __uint_as_float(elem_bits<ELT, V>(v, e));
+    if constexpr (PER_COLUMN) {
+        // where insertions are rare (pooled floors) the test is made per column: a wavefront that needs the insertion
+        // for one of its columns does not pay for the others
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            if (__ballot(!(x[e] <= val[e][KB - 1])) != 0ull) insert<KB>(val[e], tt[e], x[e], t);
+        return;
+    }
     if (KB > 1) {
         bool any = false;
 #pragma unroll
@@ -429,7 +437,7 @@ __global__ void __launch_bounds__(MAXT) stage1_kernel(S1Params p) {
         else if constexpr (BATCH) {                                                                  \
             _Pragma("unroll") for (int e_ = 0; e_ < V; ++e_) ATK_FEED_ELEM(e_, (elem_bits<ELT, V>(vec, e_)), (row)); \
         } else                                                                                       \
-            scan_vec<ELT, V, KB>(val, tt, vec, (row));                                               \
+            scan_vec<ELT, V, KB, RF>(val, tt, vec, (row));                                           \
     } while (0)
 
     // ---------------------------------------------------------------- pooled floors (instances of their own: RF)
