@@ -149,6 +149,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // (128 x 2^20, b = 64: 85.6 us with 1024 workgroups of 512 lanes, 80.1 with 256, 75.5 with 256
     // of 256 lanes), and every split less is a partial list less through memory.
     if (p.KB == 1) want_threads = 512 * (int64_t)kNumCU;
+    // Without Stage 2 the workgroups of a row share out its columns in pieces of 128 bytes of a matrix row (below); a
+    // row whose matrix rows are no longer than that (64 buckets in bf16, 32 in f32) cannot be shared out that way, and
+    // two halves through scratch and a ticket cost more than the same pair of workgroups as helper and finisher
+    // (128 x 65536 bf16, b = k = 64: 8.4 -> 7.5 us)
+    const bool pair_out_rule = p.KB == 1 && !p.stage2 && allow_pair && ov.hf >= 0 && !ov.lm_off && !ov.ln_off && ptr16 &&
+                               p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && 2 * m <= (int64_t)kNumCU &&
+                               n * es >= (128 << 10) && b * es <= 128 && !S_forced;
     // rows short enough that a Stage 2 plan is better off in one workgroup per row than in two (below)
     const bool one_piece = n * (dtype == ATK_BF16 ? 4 : 1) <= 512 * 512;
     // Shapes on which two workgroups share a row as helper and finisher (atk_lean.hip) instead of one workgroup, or
@@ -270,6 +277,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // (Rows that a helper + finisher pair takes stay in one piece here: 128 x 2^20 f32, b = 1024: 83.6 us in two
     // halves, 76.9 as a pair; 2^19: 45.7 -> 41.1; bf16 2^18, b = 256: 19.3 -> 15.9.)
     if (S == 2 && p.stage2 && p.colblocks == 1 && ((base * T >= 256 * (int64_t)kNumCU && one_piece) || pair_rule)) S = 1;
+    if (S == 2 && pair_out_rule && p.colblocks == 1) S = 1;
     // Queues in front of Stage 2 on short rows: four splits per row give the last workgroup four lists per column to
     // fetch and merge before it can select; two measured faster once the rows alone fill half the chip (128 x 65536
     // f32: k = 512, b = 1024, k_b = 2: 24.0 -> 18.6 us; b = 512, k_b = 4: 25.1 -> 21.9; k = 64, b = 64, k_b = 8: 32.6 -> 29.3)
@@ -388,7 +396,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     p.lean = p.lds_max && ptr16 && p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && p.S == 1 && p.T <= 512 && !ov.ln_off;
     p.pair_rows = 0;
     if (p.lean && p.stage2 && ov.sl && ov.sl >= p.Gw && ov.sl <= p.T) p.P = ov.sl / p.Gw;  // SL=<lanes that stream> (sweeps)
-    if (p.lean && p.stage2 && p.colblocks == 1 && allow_pair && ov.hf >= 0 && (ov.hf > 0 || pair_rule)) {
+    if (p.lean && p.colblocks == 1 && allow_pair && ov.hf >= 0 && (p.stage2 ? (ov.hf > 0 || pair_rule) : pair_out_rule)) {
         // Two workgroups per row (helper + finisher, see atk_lean.hip) while that still leaves every workgroup a CU of
         // its own, on rows long enough to be worth a second CU.  What the memory system likes is four streaming
         // wavefronts per CU on all CUs (128 x 65536 f32: 256 workgroups of 256 lanes have their rows in 1.1 us before

@@ -49,6 +49,7 @@ struct LeanParams {
 };
 
 enum { kLeanOut = 0, kLeanSelect = 1, kLeanPair = 2 };
+constexpr int kFormOut = 8;  // value of NS in a pair without Stage 2 (b*k_b = k): the finisher writes the row of maxima
 constexpr int kLeanU = 8;  // loads in flight per lane
 
 // NS, BINNED: the form of Stage 2, fixed by the host so that a kernel holds the code of one form only (all of them
@@ -260,7 +261,10 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
     }
     __syncthreads();
     trace_mark<TR>(p.trace, 3);  // all candidates of the row are in LDS, their key range is known
-    if constexpr (NS == 0)
+    if constexpr (NS == kFormOut) {
+        for (int lc = tid; lc < wcols; lc += T)
+            write_composite<ELT>(cand[(lc % V) * p.Gw + lc / V], p.out_vals, p.out_idx, (int64_t)r * p.k + colbase + lc);
+    } else if constexpr (NS == 0)
         select_radix_write<ELT>(cand, wcols, p.k, p.out_vals, p.out_idx, (int64_t)r);
     else if constexpr (binned)
         select_binned_ns<ELT, NS, TR>(cand, wcols, p.k, p.idx_bits, p.out_vals, p.out_idx, (int64_t)r, p.trace);
@@ -298,6 +302,8 @@ static hipError_t launch_lean_mode(const Plan &pl, const LeanParams &prm, hipStr
     if constexpr (MODE == kLeanOut) {
         return launch_lean_form<ELT, MODE, 0, false>(pl, prm, stream);
     } else {
+        if constexpr (MODE == kLeanPair)
+            if (!pl.stage2) return launch_lean_form<ELT, MODE, kFormOut, false>(pl, prm, stream);
         // Stage 2 over the b candidates of the row (one column block): candidates per lane, and whether the merge's
         // key range serves the bins
         const int64_t per_lane = (pl.b + pl.T - 1) / pl.T;
@@ -336,7 +342,7 @@ hipError_t launch_approx_lean(const Plan &pl, const void *x, void *out_vals, int
     prm.spin_limit = 1 << 20;  // about a second of polling
     prm.bound_ok = pl.bound_ok;
     prm.trace = (u64 *)trace;
-    const int mode = !pl.stage2 ? kLeanOut : (pl.pair_rows > 0 ? kLeanPair : kLeanSelect);
+    const int mode = pl.pair_rows > 0 ? kLeanPair : (!pl.stage2 ? kLeanOut : kLeanSelect);
     if (mode == kLeanPair && !state) return hipErrorInvalidValue;
 #define ATK_LEAN(ELT)                                                              \
     switch (mode) {                                                                \

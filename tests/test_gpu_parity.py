@@ -564,6 +564,16 @@ def test_helper_finisher_pairs(dtype, plan_override):
         run_case(workloads.few_levels(m, n, levels=3, seed=960, dtype=dtype), 64, 256, 1, tag="pair ties")
         run_case(workloads.few_levels(m, n, levels=1, seed=961, dtype=dtype), 64, 128, 1, tag="pair constant")
         run_case(workloads.special_values(m, n, seed=962, dtype=dtype), 100, 512, 1, tag="pair specials")
+    # no Stage 2 (b = k) on rows whose 128-byte matrix rows cannot be shared out between two workgroups: the
+    # finisher writes the row of maxima
+    bo = 32 if dtype == "f32" else 64
+    for (m, n) in [(128, 65536), (40, 1 << 17), (3, 1 << 18)]:
+        plan = atk.plan_describe(m, n, bo, bo, 1, dt)
+        if m == 128:  # (fewer rows are split further, through scratch)
+            assert " lean=1 " in plan and " pair_rows=%d" % (n // bo // 2) in plan and " stage2=0 " in plan, plan
+        run_case(workloads.normal_rows(m, n, seed=985, dtype=dtype), bo, bo, 1, tag="pair, no Stage 2")
+        run_case(workloads.few_levels(m, n, levels=2, seed=986, dtype=dtype), bo, bo, 1, tag="pair, no Stage 2, ties")
+        run_case(workloads.special_values(m, n, seed=987, dtype=dtype), bo // 2, bo // 2, 1, tag="pair, no Stage 2, specials")
     # long rows: pairs also at 1024 buckets, half the matrix rows each, all 512 lanes streaming in bf16
     for (m, n, k, b) in [(128, 1 << 18, 64, 1024), (100, 1 << 19, 50, 256), (128, 1 << 17, 200, 1024)]:
         plan = atk.plan_describe(m, n, k, b, 1, dt)
