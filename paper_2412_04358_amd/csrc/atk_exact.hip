@@ -1059,7 +1059,10 @@ static hipError_t launch_exact_t(const ExactPlan &pl, const void *x, const int32
         pass(1, false, kSampledLast, kSampleChunk, sample_stride(k), true);
         copy_out();
     }
-    if (pl.filter && !sample && k <= kSortLdsMaxK && n <= kRestMaxRow) {
+    // (Not with few rows: when every row is open - values piled up on few levels - each hangs on one workgroup, and the
+    // sweeps by the whole chip below are several times faster: 16 x 2^18 on three levels, k = 64: 77 us against 502.
+    // With 128 such rows the one launch loses by half; with 1024 it wins.)
+    if (pl.filter && !sample && k <= kSortLdsMaxK && n <= kRestMaxRow && m >= 64) {
         // first digit, copy-out path, and one launch for whatever rows are left
         pass(0, true, (uint32_t)pl.filter_cap, pl.chunk_elems, 1, false);
         copy_out();
