@@ -245,9 +245,12 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
         // a wavefront long.  (The host keeps launches whose only bound would be loose - lanes that see few rows may
         // hold small or negative values, whose keys lie far below the candidates' - off this path.)
         uint32_t *misc = binned_misc(cand, wcols);
-        const uint32_t w_min = wave_min_u32(MODE == kLeanPair ? k_mail_min : k_own_min);
+        // (In a pair whose wavefronts each cover the row's columns the finisher's own maxima serve: on rows with a trend -
+        // sorted rows - the helper's share lies far from the finisher's, and the mailbox would stretch the bins.)
+        const bool by_mail = MODE == kLeanPair && p.Gw > kWave;
+        const uint32_t w_min = wave_min_u32(by_mail ? k_mail_min : k_own_min);
         const uint32_t w_max = wave_max_u32(k_max);
-        const bool cover = MODE != kLeanPair && p.Gw <= kWave && __ballot(active) == ~0ull;
+        const bool cover = !by_mail && p.Gw <= kWave && __ballot(active) == ~0ull;
         if ((tid & (kWave - 1)) == 0) {
             atomicMin(&misc[1], w_min);
             atomicMax(&misc[2], w_max);
