@@ -91,7 +91,8 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
         uint32_t *cnt = binned_cnt(cand, wcols), *misc = binned_misc(cand, wcols);
         for (int i = tid; i < (1 << binned_lg_bins(wcols)); i += T) cnt[i] = 0u;
         // [0] overflow flag, [1] and [4] lower bounds on the smallest candidate's key, [2] largest key
-        if (tid < 8) misc[tid] = (tid == 1) ? 0xffffffffu : 0u;
+        // (pairs wider than a wavefront: [4] is a minimum too, see below)
+        if (tid < 8) misc[tid] = (tid == 1 || (tid == 4 && MODE == kLeanPair && p.Gw > kWave)) ? 0xffffffffu : 0u;
     }
     __syncthreads();
 
@@ -251,10 +252,15 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
         const uint32_t w_min = wave_min_u32(by_mail ? k_mail_min : k_own_min);
         const uint32_t w_max = wave_max_u32(k_max);
         const bool cover = !by_mail && p.Gw <= kWave && __ballot(active) == ~0ull;
+        // (Wider pairs: the smallest of all the finisher's lanes' maxima is a second bound - every column's candidate
+        // is at least each of its lanes' maxima - and the larger of the two is used; it is the one that holds on rows
+        // with a trend.  Every finisher has lanes that have seen a matrix row, so the minimum is always set.)
+        const uint32_t w_own = by_mail ? wave_min_u32(k_own_min) : 0u;
         if ((tid & (kWave - 1)) == 0) {
             atomicMin(&misc[1], w_min);
             atomicMax(&misc[2], w_max);
             if (cover) atomicMax(&misc[4], w_min);
+            if (by_mail) atomicMin(&misc[4], w_own);
         }
     }
     trace_mark<TR>(p.trace, 2);  // this wavefront's maxima are in LDS
