@@ -246,21 +246,22 @@ __global__ void __launch_bounds__(512) lean_kernel(LeanParams p) {
         // a wavefront long.  (The host keeps launches whose only bound would be loose - lanes that see few rows may
         // hold small or negative values, whose keys lie far below the candidates' - off this path.)
         uint32_t *misc = binned_misc(cand, wcols);
-        // (In a pair whose wavefronts each cover the row's columns the finisher's own maxima serve: on rows with a trend -
-        // sorted rows - the helper's share lies far from the finisher's, and the mailbox would stretch the bins.)
-        const bool by_mail = MODE == kLeanPair && p.Gw > kWave;
-        const uint32_t w_min = wave_min_u32(by_mail ? k_mail_min : k_own_min);
+        // In a pair two bounds are taken and the larger is used: the smallest of the helper's maxima, and one from the
+        // finisher's own lanes - the cover bound where a wavefront covers the row's columns, else the smallest of all
+        // its lanes' maxima (every column's candidate is at least each of its lanes' maxima; every finisher has lanes
+        // that have seen a matrix row, so that minimum is always set).  On rows with a trend - sorted rows - one share
+        // lies far from the other, and either bound alone stretches the bins for one direction of the trend.
+        constexpr bool pair = MODE == kLeanPair;
+        const bool wide = p.Gw > kWave;
+        const uint32_t w_own = wave_min_u32(k_own_min);
+        const uint32_t w_mail = pair ? wave_min_u32(k_mail_min) : 0u;
         const uint32_t w_max = wave_max_u32(k_max);
-        const bool cover = !by_mail && p.Gw <= kWave && __ballot(active) == ~0ull;
-        // (Wider pairs: the smallest of all the finisher's lanes' maxima is a second bound - every column's candidate
-        // is at least each of its lanes' maxima - and the larger of the two is used; it is the one that holds on rows
-        // with a trend.  Every finisher has lanes that have seen a matrix row, so the minimum is always set.)
-        const uint32_t w_own = by_mail ? wave_min_u32(k_own_min) : 0u;
+        const bool cover = !wide && __ballot(active) == ~0ull;
         if ((tid & (kWave - 1)) == 0) {
-            atomicMin(&misc[1], w_min);
+            atomicMin(&misc[1], pair ? w_mail : w_own);
             atomicMax(&misc[2], w_max);
-            if (cover) atomicMax(&misc[4], w_min);
-            if (by_mail) atomicMin(&misc[4], w_own);
+            if (cover) atomicMax(&misc[4], w_own);
+            if (pair && wide) atomicMin(&misc[4], w_own);
         }
     }
     trace_mark<TR>(p.trace, 2);  // this wavefront's maxima are in LDS
