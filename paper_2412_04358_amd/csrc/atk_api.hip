@@ -149,6 +149,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // (128 x 2^20, b = 64: 85.6 us with 1024 workgroups of 512 lanes, 80.1 with 256, 75.5 with 256
     // of 256 lanes), and every split less is a partial list less through memory.
     if (p.KB == 1) want_threads = 512 * (int64_t)kNumCU;
+    const bool short_rule = p.KB == 1 && p.stage2 && !ov.lm_off && !ov.ln_off && ptr16 && p.V == 16 / es && n % b == 0 &&
+                            (n * es) % 16 == 0 && 2 * m <= (int64_t)kNumCU && n <= 65536 && !S_forced;
     // Without Stage 2 the workgroups of a row share out its columns in pieces of 128 bytes of a matrix row (below); a
     // row whose matrix rows are no longer than that (64 buckets in bf16, 32 in f32) cannot be shared out that way, and
     // two halves through scratch and a ticket cost more than the same pair of workgroups as helper and finisher
@@ -161,10 +163,11 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // Shapes on which two workgroups share a row as helper and finisher (atk_lean.hip) instead of one workgroup, or
     // two halves meeting through scratch and a ticket: rows of whole aligned vectors with one slot per bucket, few
     // enough that every workgroup still has a CU of its own, long enough to be worth a second CU; past 512 buckets
-    // Stage 2 outweighs what the second CU saves unless the row has 2^17 elements or more.
+    // Stage 2 outweighs what the second CU saves unless the row has 2^17 elements or more, or the batch is small
+    // (65536-long rows, b = 1024: level at 128 rows; 32 rows: 9.4 us in one workgroup, 9.0 as a pair).
     const bool pair_rule = p.KB == 1 && p.stage2 && allow_pair && ov.hf >= 0 && !ov.lm_off && !ov.ln_off && ptr16 &&
                            p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && 2 * m <= (int64_t)kNumCU &&
-                           n * es >= (128 << 10) && b <= 1024 && (b <= 512 || n >= (1 << 17));
+                           n * es >= (128 << 10) && b <= 1024 && (b <= 512 || n >= (1 << 17) || (m >= 8 && m <= 64));
     int T = 256;
     int64_t lanes_per_wg = 0;  // what a workgroup counts as when the splits are chosen (0: its size)
     if (p.G <= 256) {
@@ -278,6 +281,11 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // halves, 76.9 as a pair; 2^19: 45.7 -> 41.1; bf16 2^18, b = 256: 19.3 -> 15.9.)
     if (S == 2 && p.stage2 && p.colblocks == 1 && ((base * T >= 256 * (int64_t)kNumCU && one_piece) || pair_rule)) S = 1;
     if (S == 2 && pair_out_rule && p.colblocks == 1) S = 1;
+    // Short rows (up to 65536 elements) of a batch that leaves CUs idle: row splits through scratch and a ticket cost
+    // more than they bring; one workgroup per row on the lean kernel, or a pair, is faster at every batch size (f32
+    // n = 65536, k = 64: m = 1, b = 1024: 8.9 -> 6.6 us; m = 32: 11.1 -> 9.0; m = 64, b = 256: 9.7 -> 8.0; n = 32768:
+    // 8.6 -> 6.2; bf16 m = 32, b = 512: 9.6 -> 7.5).  From 2^17 elements on the splits win (16 x 2^17: 9.3 against 10.6).
+    if (S > 1 && short_rule && p.colblocks == 1) S = 1;
     // Queues in front of Stage 2 on short rows: four splits per row give the last workgroup four lists per column to
     // fetch and merge before it can select; two measured faster once the rows alone fill half the chip (128 x 65536
     // f32: k = 512, b = 1024, k_b = 2: 24.0 -> 18.6 us; b = 512, k_b = 4: 25.1 -> 21.9; k = 64, b = 64, k_b = 8: 32.6 -> 29.3)

@@ -128,9 +128,12 @@ def test_plan_shapes(lib):
     assert p["Gw"] == 8 and p["colblocks"] == 2 and p["S"] > 1 and p["scratch"] == 1
     assert p["S"] * p["rows_per_split"] >= 1024 and (p["S"] - 1) * p["rows_per_split"] < 1024
     assert p["rows_per_split"] % p["P"] == 0
-    # with Stage 2 one workgroup must see every candidate of the row: the columns stay together
-    p = parse_plan(atk.plan_describe(32, 65536, 64, 128, 1))
+    # with Stage 2 one workgroup must see every candidate of the row: the columns stay together; rows of 2^17 elements
+    # are split over workgroups that meet through scratch, shorter ones go to a helper + finisher pair
+    p = parse_plan(atk.plan_describe(32, 1 << 17, 64, 128, 1))
     assert p["Gw"] == 32 and p["colblocks"] == 1 and p["S"] > 1 and p["scratch"] == 1
+    p = parse_plan(atk.plan_describe(32, 65536, 64, 128, 1))
+    assert p["Gw"] == 32 and p["colblocks"] == 1 and p["S"] == 1 and p["scratch"] == 0 and p["lean"] == 1 and p["pair_rows"] == 256
     # Stage 2 fused
     p = parse_plan(atk.plan_describe(128, 65536, 64, 1024, 1))
     assert p["stage2"] == 1 and p["lds"] >= (1024 + 64) * 8
