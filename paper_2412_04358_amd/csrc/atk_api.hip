@@ -86,6 +86,11 @@ static PlanOverride parse_plan_override(const char *e) {
     if (const char *q = field("HT")) o.ht = atoi(q);
     if (const char *q = field("RF")) o.rf = atoi(q) <= 0 ? -1 : atoi(q);
     if (const char *q = field("SL")) o.sl = atoi(q);
+    if (const char *q = field("BO")) o.bo_off = atoi(q) == 0;
+    if (const char *q = field("MH")) {
+        const int v = atoi(q);
+        o.mh = v <= 0 ? -1 : (v <= 255 ? v : 0);
+    }
     if (const char *q = field("HQ")) {
         const int v = atoi(q);
         if (v >= 1 && v <= 63) o.hq = v;
@@ -151,6 +156,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (p.KB == 1) want_threads = 512 * (int64_t)kNumCU;
     const bool short_rule = p.KB == 1 && p.stage2 && !ov.lm_off && !ov.ln_off && ptr16 && p.V == 16 / es && n % b == 0 &&
                             (n * es) % 16 == 0 && 2 * m <= (int64_t)kNumCU && n <= 65536 && !S_forced;
+    const bool multi_short = short_rule && allow_pair && ov.hf >= 0 && ov.mh >= 0 && m <= 32 && b <= 512 && n > 32768;
     // Without Stage 2 the workgroups of a row share out its columns in pieces of 128 bytes of a matrix row (below); a
     // row whose matrix rows are no longer than that (64 buckets in bf16, 32 in f32) cannot be shared out that way, and
     // two halves through scratch and a ticket cost more than the same pair of workgroups as helper and finisher
@@ -160,7 +166,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
                                n * es >= (128 << 10) && b * es <= 128 && !S_forced;
     // rows short enough that a Stage 2 plan is better off in one workgroup per row than in two (below)
     const bool one_piece = n * (dtype == ATK_BF16 ? 4 : 1) <= 512 * 512;
-    // Shapes on which two workgroups share a row as helper and finisher (atk_lean.hip) instead of one workgroup, or
+    // Shapes on which two workgroups share a row as helper and finisher (atk_lean_kernel.h) instead of one workgroup, or
     // two halves meeting through scratch and a ticket: rows of whole aligned vectors with one slot per bucket, few
     // enough that every workgroup still has a CU of its own, long enough to be worth a second CU; past 512 buckets
     // Stage 2 outweighs what the second CU saves unless the row has 2^17 elements or more, or the batch is small
@@ -285,7 +291,10 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // more than they bring; one workgroup per row on the lean kernel, or a pair, is faster at every batch size (f32
     // n = 65536, k = 64: m = 1, b = 1024: 8.9 -> 6.6 us; m = 32: 11.1 -> 9.0; m = 64, b = 256: 9.7 -> 8.0; n = 32768:
     // 8.6 -> 6.2; bf16 m = 32, b = 512: 9.6 -> 7.5).  From 2^17 elements on the splits win (16 x 2^17: 9.3 against 10.6).
-    if (S > 1 && short_rule && p.colblocks == 1) S = 1;
+    // ... except that up to 32 such rows of more than 32768 elements with at most 512 buckets are better off still as three
+    // helpers and a finisher on the lean kernel (below; f32 n = 65536: m = 1, b = 128: 7.1 us in one workgroup, 6.6 as a
+    // pair, 5.6 in four; m = 32, b = 256: 7.7 -> 6.9; seven helpers are slower again from 256 buckets on)
+    if (S > 1 && short_rule && p.colblocks == 1) S = (multi_short && S >= 4) ? 4 : 1;
     // Queues in front of Stage 2 on short rows: four splits per row give the last workgroup four lists per column to
     // fetch and merge before it can select; two measured faster once the rows alone fill half the chip (128 x 65536
     // f32: k = 512, b = 1024, k_b = 2: 24.0 -> 18.6 us; b = 512, k_b = 4: 25.1 -> 21.9; k = 64, b = 64, k_b = 8: 32.6 -> 29.3)
@@ -348,12 +357,32 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
             S = row_splits();
         }
     }
+    // One slot per bucket on rows of whole aligned vectors, where the plan so far splits rows: the splits of a row (and
+    // column block) run as helpers and a finisher on the lean kernel (atk_lean_kernel.h, kLeanMulti) instead of meeting
+    // through partial lists, a fence and a ticket.  Every workgroup but the last takes the same whole number of row
+    // phases' worth of matrix rows, the last one - the finisher - what is left, at least one row per phase.
+    int helpers = 0;
+    int64_t helper_rows = 0;
+    const bool multi_ok = p.KB == 1 && allow_pair && ov.hf >= 0 && ov.mh >= 0 && !ov.lm_off && !ov.ln_off && ptr16 &&
+                          p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && !S_forced && T <= 512 &&
+                          (!p.stage2 || p.colblocks == 1);
+    if (multi_ok && ov.mh > 0) S = ov.mh + 1;  // (sweeps and tests; clamped like any other count below)
     if (S_forced) S = S_forced;
     if (S > p.L / p.P) S = p.L / p.P;
     if (S < 1) S = 1;
     int64_t rps = ceil_div(p.L, S);
     rps = ceil_div(rps, p.P) * p.P;
     S = ceil_div(p.L, rps);
+    if (multi_ok && S > 1 && (S - 1) * (int64_t)p.Gw * p.V <= (int64_t)kMultiSlots * T) {
+        int64_t lh = ceil_div(p.L, S * p.P) * p.P;
+        if (p.L - (S - 1) * lh < p.P) lh = p.L / (S * p.P) * p.P;
+        if (lh >= p.P && p.L - (S - 1) * lh >= p.P) {
+            helpers = (int)S - 1;
+            helper_rows = lh;
+            S = 1;
+            rps = ceil_div(p.L, p.P) * p.P;
+        }
+    }
     p.S = (int)S;
     p.rows_per_split = (int)rps;
 
@@ -369,7 +398,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         (ov.rf > 0 || (p.P >= 16 && p.rows_per_split / p.P >= 256)))
         p.refresh = ov.rf > 0 ? ov.rf : 8;
     p.tail_tpc = tail_lanes_per_column(p.stage2 ? b : std::min<int64_t>(b, (int64_t)p.Gw * p.V), p.T, p.KB, p.S);
-    p.direct = (p.P == 1 && p.S == 1 && !p.stage2);
+    p.direct = (p.P == 1 && p.S == 1 && !p.stage2 && helpers == 0);
     p.use_scratch = (p.S > 1) || (p.stage2 && p.colblocks > 1);
     if (p.use_scratch && p.stage2) {
         // the candidates are gathered by the last workgroup of the row, after its exchange area
@@ -398,14 +427,30 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // Stage 2's short form takes its bins' lower end from the merge: tight when some wavefront covers every column
     // (its minimum bounds the smallest candidate), else only as tight as the smallest value any lane holds -
     // good enough once every lane has seen a few dozen rows
-    p.bound_ok = p.lds_max && p.stage2 && (p.Gw <= kWave || p.L / p.P >= 24);
+    // (A lane that has seen few rows holds a negative maximum now and then - one lane-column in 2^rows on centred data -
+    // and a bound at or below zero stretches the bins over every exponent there is: all candidates land in a few bins
+    // and the selection falls back to digit by digit.  With a wavefront's cover bound it takes such a lane in every
+    // wavefront; measured with 8 rows per lane: bf16 128 x 32768, b = 256: 10.7 us, 6.5 with the range taken from the
+    // merged candidates instead; f32 128 x 8192, b = 128: 7.5 -> 5.2; level from 16 rows per lane.)
+    p.bound_ok = p.lds_max && p.stage2 && ((p.Gw <= kWave && p.L / p.P >= 16) || p.L / p.P >= 24) && !ov.bo_off;
     // Rows of whole, aligned 16-byte vectors with one slot per bucket and one workgroup per row or column
     // block: the lean kernels (same mapping, nothing else in the kernel).
     p.lean = p.lds_max && ptr16 && p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && p.S == 1 && p.T <= 512 && !ov.ln_off;
     p.pair_rows = 0;
+    p.helpers = 0;
+    if (helpers > 0) {
+        if (!p.lean) return ATK_ERR_UNSUPPORTED;  // never: multi_ok holds what the lean kernels ask for
+        p.pair_rows = (int)helper_rows;
+        p.helpers = helpers;
+        p.grid = m * p.colblocks * (helpers + 1);
+        if (p.grid >= (1ll << 31)) return ATK_ERR_UNSUPPORTED;
+        // the mailboxes: per (row, column block) one per helper, a composite per column of the block, zero between calls
+        p.scratch_ticket_bytes = m * p.colblocks * helpers * (int64_t)p.Gw * p.V * 8;
+        p.bound_ok = p.stage2 && helper_rows >= 16 && !ov.bo_off;  // (the first helper's mailbox is a bound, a column's maximum over that many rows)
+    }
     if (p.lean && p.stage2 && ov.sl && ov.sl >= p.Gw && ov.sl <= p.T) p.P = ov.sl / p.Gw;  // SL=<lanes that stream> (sweeps)
-    if (p.lean && p.colblocks == 1 && allow_pair && ov.hf >= 0 && (p.stage2 ? (ov.hf > 0 || pair_rule) : pair_out_rule)) {
-        // Two workgroups per row (helper + finisher, see atk_lean.hip) while that still leaves every workgroup a CU of
+    if (p.lean && helpers == 0 && p.colblocks == 1 && allow_pair && ov.hf >= 0 && (p.stage2 ? (ov.hf > 0 || pair_rule) : pair_out_rule)) {
+        // Two workgroups per row (helper + finisher, see atk_lean_kernel.h) while that still leaves every workgroup a CU of
         // its own, on rows long enough to be worth a second CU.  What the memory system likes is four streaming
         // wavefronts per CU on all CUs (128 x 65536 f32: 256 workgroups of 256 lanes have their rows in 1.1 us before
         // 128 of 512 do, and 256 of 512 are slower than either), so the pair streams with 256 lanes per workgroup: up to
@@ -431,7 +476,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
                 p.pair_rows = (int)lh;
                 p.grid = 2 * m;
                 p.scratch_ticket_bytes = m * b * 8;  // the mailbox: one composite per bucket, zero between calls
-                p.bound_ok = true;                   // (the mailbox is the bound)
+                p.bound_ok = lh >= 16 && !ov.bo_off;  // (the mailbox is the bound: a column's maximum over that many rows)
             }
         }
     }
@@ -902,10 +947,10 @@ int atk_plan_describe_assign(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     else
         snprintf(buf, (size_t)buflen,
                  "V=%d KB=%d T=%d Gw=%d P=%d colblocks=%d S=%d rows_per_split=%d grid=%lld stage2=%d direct=%d "
-                 "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d lean=%d pair_rows=%d refresh=%d",
+                 "scratch=%d wave_merge=%d nparts=%d lds=%d scratch_bytes=%lld packed=%d lean=%d pair_rows=%d refresh=%d helpers=%d",
                  pl.V, pl.KB, pl.T, pl.Gw, pl.P, pl.colblocks, pl.S, pl.rows_per_split, (long long)pl.grid, stage2,
                  (int)pl.direct, (int)pl.use_scratch, (int)pl.wave_merge, pl.nparts, pl.lds_bytes,
-                 (long long)(fp.state_bytes + fp.data_bytes), (int)pl.packed, (int)pl.lean, pl.pair_rows, pl.refresh);
+                 (long long)(fp.state_bytes + fp.data_bytes), (int)pl.packed, (int)pl.lean, pl.pair_rows, pl.refresh, pl.helpers);
     return ATK_OK;
 }
 

@@ -71,6 +71,8 @@ constexpr int kEmptyT = 0x7fffffff;       // "no element yet" row marker of a re
 
 // Launch-plan overrides for sweeps and tests: the ATK_PLAN environment variable, read once when the
 // library is loaded, or whatever atk_set_plan_override() was last given.  0 / false = not set.
+constexpr int kMultiSlots = 8;   // helpers + finisher on the lean kernel: mailbox words that a lane of the finisher fetches at once
+
 struct PlanOverride {
     int T, S, V, P;   // threads per workgroup, row splits, columns per lane, lanes sharing a column group
     bool pk_off;      // PK=0: no packed bf16 queue words
@@ -83,6 +85,8 @@ struct PlanOverride {
     int sl;           // SL=<lanes>: lanes of a workgroup that stream (the rest only join Stage 2), 0 not set
     bool ln_off;      // LN=0: never the lean kernels
     int rf;           // RF=0: queues never pool their floors; RF=<n>: first after n load batches (0 not set)
+    bool bo_off;      // BO=0: Stage 2's bins never take their range from the merge
+    int mh;           // MH=0: no helpers + finisher plans for split rows (-1); MH=<h>: that many helpers where legal (0 not set)
 };
 const PlanOverride &plan_override();
 
@@ -114,7 +118,8 @@ struct Plan {
     bool lds_max;     // k_b = 1, no scratch, lanes share columns: they meet in LDS by atomic maximum
     bool bound_ok;    // lds_max with Stage 2: the merge yields a tight lower bound on the smallest candidate (see select_binned())
     bool lean;        // k_b = 1 on rows of whole aligned 16-byte vectors, one workgroup (or a pair) per row: the lean kernels
-    int pair_rows;    // lean, Stage 2: > 0 = two workgroups per row, the helper takes this many matrix rows
+    int pair_rows;    // lean: > 0 = several workgroups per row (helpers + finisher), a helper takes this many matrix rows
+    int helpers;      // > 0: the splits of a row (and column block) as that many helpers and a finisher (kLeanMulti); 0 with the pair kernels
     bool wave_merge;  // Gw < 64 and a power of two: lanes of a wavefront share columns, merged by shuffles
     int nparts;       // partial lists per column left for the LDS exchange
     int lds_xch_off, lds_cand_off;
@@ -144,7 +149,7 @@ hipError_t launch_approx(const Plan &plan, const void *x, void *out_vals, int32_
 hipError_t launch_approx_contig(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state,
                                 void *data, hipStream_t stream);
 
-// The same for a plan with `lean` set (atk_lean.hip).  state: the helper-to-finisher mailbox of a pair plan
+// The same for a plan with `lean` set (atk_lean_kernel.h).  state: the helper-to-finisher mailbox of a pair plan
 // (plan.scratch_ticket_bytes, zero between calls), else unused.  trace: as for launch_approx.
 hipError_t launch_approx_lean(const Plan &plan, const void *x, void *out_vals, int32_t *out_idx, void *state,
                               hipStream_t stream, void *trace = nullptr);

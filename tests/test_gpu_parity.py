@@ -500,7 +500,10 @@ HAND_OVER_CASES = [
     ("cfg4 b=1024 Stage 2", ("cfg4",), (64, 1024, 1), None, "pair_rows=512 "),
     ("cfg4 b=1024 Stage 2 in two halves", ("cfg4",), (64, 1024, 1), "HF=0", "scratch=1"),
     ("cfg4 b=128 k_b=8 Stage 2", ("cfg4",), (64, 128, 8), None, "scratch=1"),
-    ("8 x 2^20 b=64", (8, 1 << 20, 51, "f32"), (64, 64, 1), None, "scratch=1"),
+    ("8 x 2^20 b=64 row splits through scratch", (8, 1 << 20, 51, "f32"), (64, 64, 1), "MH=0", "scratch=1"),
+    ("8 x 2^20 b=64 helpers + finisher", (8, 1 << 20, 51, "f32"), (64, 64, 1), None, "helpers=15 "),
+    ("16 x 2^17 b=256 helpers + finisher", (16, 1 << 17, 57, "f32"), (64, 256, 1), None, "helpers=15 "),
+    ("5 x 65536 bf16 b=128 helpers + finisher", (5, 65536, 58, "bf16"), (64, 128, 1), None, "helpers=3 "),
     ("3 x 2^18 b=256 S=64", (3, 1 << 18, 52, "f32"), (64, 256, 1), "S=64", "S=64 "),
     ("5 x 2^18 bf16 b=64 k_b=4 S=16 P=4", (5, 1 << 18, 53, "bf16"), (100, 64, 4), "S=16,P=4", "S=16 "),
     ("cfg2 b=512 two workgroups per row", ("cfg2",), (64, 512, 1), "S=2", "scratch=1"),
@@ -590,6 +593,41 @@ def test_helper_finisher_pairs(dtype, plan_override):
             run_case(x, k, b, 1, tag=spec)
         run_case(workloads.few_levels(4, 16384, levels=2, seed=980, dtype=dtype), 30, 128, 1, tag=spec + " ties")
         run_case(workloads.special_values(4, 16384, seed=981, dtype=dtype), 64, 256, 1, tag=spec + " specials")
+    plan_override(None)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_helpers_and_finisher(dtype, plan_override):
+    """Few long rows with one slot per bucket: the splits of a row run as helpers and a finisher (one mailbox per
+    helper).  The plans the library chooses on its own - with and without Stage 2, column blocks, ties and special
+    values - and forced helper counts on shapes it would not choose them for: bucket counts that are no power of
+    two, finishers with a short share, more helpers than a lane of the finisher fetches words for (those stay on
+    the row splits through scratch)."""
+    dt = atk.ATK_F32 if dtype == "f32" else atk.ATK_BF16
+    chosen = 0
+    for (m, n) in [(1, 1 << 20), (7, 1 << 18), (16, 1 << 17), (33, 1 << 19), (3, 65536)]:
+        for (k, b) in [(64, 64), (32, 32), (64, 128), (100, 256), (64, 512), (300, 1024)]:
+            plan = atk.plan_describe(m, n, k, b, 1, dt)
+            chosen += " helpers=0" not in plan
+            run_case(workloads.normal_rows(m, n, seed=1200 + b, dtype=dtype), k, b, 1, tag="helpers")
+        run_case(workloads.few_levels(m, n, levels=3, seed=1210, dtype=dtype), 64, 256, 1, tag="helpers ties")
+        run_case(workloads.few_levels(m, n, levels=1, seed=1211, dtype=dtype), 64, 64, 1, tag="helpers constant")
+        run_case(workloads.special_values(m, n, seed=1212, dtype=dtype), 100, 128, 1, tag="helpers specials")
+        # rows with a trend: the first helper's share lies far from the finisher's (the two lower bounds on Stage 2's bins)
+        xs = workloads.normal_rows(m, n, seed=1213, dtype=dtype)
+        asc = torch.sort(xs.float(), dim=1).values.to(xs.dtype)
+        run_case(asc, 64, 256, 1, tag="helpers ascending")
+        run_case(torch.flip(asc, dims=[1]).contiguous(), 64, 256, 1, tag="helpers descending")
+    assert chosen >= 15, chosen
+    for spec in ["MH=1", "MH=2", "MH=5", "MH=15", "MH=40", "MH=3,T=128", "MH=7,T=64"]:
+        plan_override(spec)
+        for (m, n, k, b) in [(3, 8192, 64, 128), (70, 4096, 16, 16), (5, 36864, 100, 288), (2, 65536, 64, 1024),
+                             (9, 96 * 512, 96, 96), (2, 1 << 16, 1000, 2048), (4, 24 * 1024, 20, 24)]:
+            x = workloads.normal_rows(m, n, seed=1220 + b, dtype=dtype)
+            print(spec, atk.plan_describe(m, n, k, b, 1, dt), flush=True)
+            run_case(x, k, b, 1, tag=spec)
+        run_case(workloads.few_levels(4, 16384, levels=2, seed=1230, dtype=dtype), 30, 128, 1, tag=spec + " ties")
+        run_case(workloads.special_values(4, 16384, seed=1231, dtype=dtype), 64, 256, 1, tag=spec + " specials")
     plan_override(None)
 
 

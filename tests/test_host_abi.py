@@ -123,17 +123,31 @@ def test_plan_shapes(lib):
     assert p["V"] == 4 and p["Gw"] == 8 and p["colblocks"] == 2 and p["P"] * p["Gw"] == p["T"] and p["wave_merge"] == 1
     assert p["S"] == 1 and p["scratch"] == 0 and p["direct"] == 0 and p["nparts"] == p["T"] // 64
     assert p["grid"] == 256
-    # fewer rows than that fills the chip with: rows are split on top, merged via scratch
+    # fewer rows than that fills the chip with: rows are split on top; the splits of a row and column block run as
+    # helpers and a finisher (one mailbox per helper, the finisher takes what the helpers' equal shares leave)
     p = parse_plan(atk.plan_describe(32, 65536, 64, 64, 1))
-    assert p["Gw"] == 8 and p["colblocks"] == 2 and p["S"] > 1 and p["scratch"] == 1
+    assert p["Gw"] == 8 and p["colblocks"] == 2 and p["S"] == 1 and p["scratch"] == 0 and p["lean"] == 1
+    assert p["helpers"] >= 1 and p["grid"] == 32 * 2 * (p["helpers"] + 1)
+    assert p["pair_rows"] % p["P"] == 0 and 0 < 1024 - p["helpers"] * p["pair_rows"] <= 2 * p["pair_rows"]
+    assert p["scratch_bytes"] == 32 * 2 * p["helpers"] * p["Gw"] * p["V"] * 8
+    # ... or, with queues of several slots, meet through scratch and a ticket
+    p = parse_plan(atk.plan_describe(32, 65536, 128, 64, 2))
+    assert p["S"] > 1 and p["scratch"] == 1 and p["helpers"] == 0
     assert p["S"] * p["rows_per_split"] >= 1024 and (p["S"] - 1) * p["rows_per_split"] < 1024
     assert p["rows_per_split"] % p["P"] == 0
-    # with Stage 2 one workgroup must see every candidate of the row: the columns stay together; rows of 2^17 elements
-    # are split over workgroups that meet through scratch, shorter ones go to a helper + finisher pair
+    # with Stage 2 one workgroup must see every candidate of the row: the columns stay together; few rows of 2^17
+    # elements go to helpers and a finisher, up to 32 rows of 65536 to three helpers and a finisher, more to a pair
     p = parse_plan(atk.plan_describe(32, 1 << 17, 64, 128, 1))
-    assert p["Gw"] == 32 and p["colblocks"] == 1 and p["S"] > 1 and p["scratch"] == 1
+    assert p["Gw"] == 32 and p["colblocks"] == 1 and p["S"] == 1 and p["scratch"] == 0 and p["helpers"] > 1
+    assert p["helpers"] * p["Gw"] * p["V"] <= 8 * p["T"]  # (the finisher fetches at most eight words per lane)
     p = parse_plan(atk.plan_describe(32, 65536, 64, 128, 1))
-    assert p["Gw"] == 32 and p["colblocks"] == 1 and p["S"] == 1 and p["scratch"] == 0 and p["lean"] == 1 and p["pair_rows"] == 256
+    assert p["colblocks"] == 1 and p["S"] == 1 and p["scratch"] == 0 and p["lean"] == 1 and p["helpers"] == 3 and p["pair_rows"] == 128
+    p = parse_plan(atk.plan_describe(64, 65536, 64, 128, 1))
+    assert p["Gw"] == 32 and p["colblocks"] == 1 and p["S"] == 1 and p["scratch"] == 0 and p["lean"] == 1
+    assert p["helpers"] == 0 and p["pair_rows"] == 256 and p["grid"] == 128
+    # more helpers' words than that: the row splits stay, through scratch and a ticket
+    p = parse_plan(atk.plan_describe(1, 1 << 20, 64, 1024, 1))
+    assert p["S"] > 1 and p["scratch"] == 1 and p["helpers"] == 0
     # Stage 2 fused
     p = parse_plan(atk.plan_describe(128, 65536, 64, 1024, 1))
     assert p["stage2"] == 1 and p["lds"] >= (1024 + 64) * 8
