@@ -163,7 +163,11 @@ int atk_exact_workspace_parts(int64_t m, int64_t n, int64_t k, int dtype, int64_
  * one specialised for running maxima), LM=0 (k_b = 1: the lanes of a column merge through per-part lists and
  * a pass over them instead of atomic maxima in LDS), HF=0 / HF=1 (never / whenever the shape allows, two
  * workgroups - a helper and a finisher - share a row of a Stage-2 plan), HQ=<sixty-fourths of the matrix rows
- * that the helper takes: 1..63>, HT=<threads of such a workgroup>, SL=<lanes of a workgroup that stream>.
+ * that the helper takes: 1..63>, HT=<threads of such a workgroup>, SL=<lanes of a workgroup that stream>,
+ * MH=0 / MH=<h> (k_b = 1: split rows never / with h helpers run as helpers and a finisher that meet through
+ * mailboxes instead of partial lists and a ticket; HF=0 switches these off as well), BO=0 (Stage 2's bins take their
+ * key range from the merged candidates, never from the bounds that come with the merge), RF=0 / RF=<n> (queues of
+ * eight slots never / from n load batches on pool their floors).
  * Values the kernels cannot take are ignored or clamped; results never depend on the plan.
  */
 int atk_plan_describe(int64_t m, int64_t n, int64_t k, int64_t b, int64_t k_b, int dtype, char *buf,
