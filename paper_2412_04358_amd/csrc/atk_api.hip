@@ -156,6 +156,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (p.KB == 1) want_threads = 512 * (int64_t)kNumCU;
     const bool short_rule = p.KB == 1 && p.stage2 && !ov.lm_off && !ov.ln_off && ptr16 && p.V == 16 / es && n % b == 0 &&
                             (n * es) % 16 == 0 && 2 * m <= (int64_t)kNumCU && n <= 65536 && !S_forced;
+    const bool lean_shape = ptr16 && p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0;  // what the lean kernels ask of the input
     const bool multi_short = short_rule && allow_pair && ov.hf >= 0 && ov.mh >= 0 && m <= 32 && b <= 512 && n > 32768;
     // Without Stage 2 the workgroups of a row share out its columns in pieces of 128 bytes of a matrix row (below); a
     // row whose matrix rows are no longer than that (64 buckets in bf16, 32 in f32) cannot be shared out that way, and
@@ -295,6 +296,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // helpers and a finisher on the lean kernel (below; f32 n = 65536: m = 1, b = 128: 7.1 us in one workgroup, 6.6 as a
     // pair, 5.6 in four; m = 32, b = 256: 7.7 -> 6.9; seven helpers are slower again from 256 buckets on)
     if (S > 1 && short_rule && p.colblocks == 1) S = (multi_short && S >= 4) ? 4 : 1;
+    // The same on the general kernel (rows that are not whole aligned vectors, or b does not divide n): one slot per
+    // bucket up to 65536 elements (f32 n = 50000: one row, b = 1024: 9.4 -> 6.5 us; 32 rows, b = 2048: 15.0 -> 11.7; 128
+    // rows, b = 64: 9.2 -> 7.7), queues of several slots up to 16384 (512 x 16384 f32, b = 8, k_b = 8: 24.8 -> 20;
+    // 128 x 16384 bf16, b = 32, k_b = 2: 7.5 -> 6.5); longer rows with queues are better off split (128 x 65536,
+    // b = 8, k_b = 8: four splits are the fastest)
+    if (S > 1 && p.KB == 1 && n <= 65536 && !lean_shape) S = 1;
+    if (S > 1 && p.KB >= 2 && n <= 16384) S = 1;
     // Queues in front of Stage 2 on short rows: four splits per row give the last workgroup four lists per column to
     // fetch and merge before it can select; two measured faster once the rows alone fill half the chip (128 x 65536
     // f32: k = 512, b = 1024, k_b = 2: 24.0 -> 18.6 us; b = 512, k_b = 4: 25.1 -> 21.9; k = 64, b = 64, k_b = 8: 32.6 -> 29.3)
@@ -323,6 +331,18 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     return S;
     };
     int64_t S = row_splits();
+    // Many rows with few column groups came out above with workgroups of one or two wavefronts (a lane per column group
+    // fills the chip) and may still get row splits on top - through scratch and a ticket, between workgroups of 64
+    // lanes.  Bigger workgroups whose lanes share the columns do the same without memory in between (2048 x 16384 bf16,
+    // k = 256, b = 64, k_b = 4: 35.0 -> 21 us; 2048 x 4096 f32, b = 32, k_b = 2: 11.6 -> 9.0; b = 8, k_b = 8: 27.2 -> 20)
+    while (S >= 2 && T < 256 && 2 * T <= t_max && !T_forced && !P_forced && !S_forced) {
+        const int t_before = T;
+        T *= 2;
+        layout(p_want);
+        if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
+        S = row_splits();
+        if (T <= t_before) break;  // (rows too short to give more lanes something to do)
+    }
     // Without Stage 2 nothing ties the columns of a row together, and a workgroup that owns whole
     // buckets needs no hand-over at all: as long as rows would be split, and a workgroup's piece of
     // a matrix row stays 128 bytes or more, halve the workgroup's column groups instead (measured on
