@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 
@@ -335,7 +336,9 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // fills the chip) and may still get row splits on top - through scratch and a ticket, between workgroups of 64
     // lanes.  Bigger workgroups whose lanes share the columns do the same without memory in between (2048 x 16384 bf16,
     // k = 256, b = 64, k_b = 4: 35.0 -> 21 us; 2048 x 4096 f32, b = 32, k_b = 2: 11.6 -> 9.0; b = 8, k_b = 8: 27.2 -> 20)
-    while (S >= 2 && T < 256 && 2 * T <= t_max && !T_forced && !P_forced && !S_forced) {
+    // (and so do 512 lanes instead of two workgroups of 256 with queues: 512 x 50000 f32, k = 1024, b = 256, k_b = 4:
+    // 32.3 -> 23 us)
+    while (S >= 2 && (T < 256 || (T < 512 && S == 2 && p.KB >= 2)) && 2 * T <= t_max && !T_forced && !P_forced && !S_forced) {
         const int t_before = T;
         T *= 2;
         layout(p_want);
@@ -386,6 +389,21 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     const bool multi_ok = p.KB == 1 && allow_pair && ov.hf >= 0 && ov.mh >= 0 && !ov.lm_off && !ov.ln_off && ptr16 &&
                           p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && !S_forced && T <= 512 &&
                           (!p.stage2 || p.colblocks == 1);
+    // Queues of two to four slots without Stage 2: the workgroup that draws the last ticket merges S lists of (its
+    // columns) x k_b entries, so the splits that pay grow with the square root of the row's length over that, and beyond 32
+    // the tickets and the fetch of that many lists cost more than shorter streams save whatever the lists' size - unless
+    // a split would then stream more than 128 KB, which few workgroups cannot pull fast enough (f32, k = 1024, b = 256,
+    // k_b = 4: 8 x 2^17: 18.0 us with 32 splits, 12.3 with 8; 8 x 2^18: 19.1 -> 15.1 with 16; k = 64, b = 32, k_b = 2, one
+    // row of 2^20: 15.7 with 256 splits, 11.2 with 32, but 2^22: 17.6 with 256, 25.5 with 32)
+    if (p.KB >= 2 && p.KB <= 4 && !p.stage2 && !S_forced) {
+        const int64_t cols = std::min<int64_t>(b, (int64_t)p.Gw * p.V);
+        int64_t s_tail = (int64_t)(0.75 * std::sqrt((double)n / (double)(cols * k_b)));
+        if (s_tail > 32) s_tail = 32;
+        const int64_t s_stream = n * es / (128 << 10);
+        if (s_tail < s_stream) s_tail = s_stream;
+        if (s_tail < 1) s_tail = 1;
+        if (S > s_tail) S = s_tail;
+    }
     if (multi_ok && ov.mh > 0) S = ov.mh + 1;  // (sweeps and tests; clamped like any other count below)
     if (S_forced) S = S_forced;
     if (S > p.L / p.P) S = p.L / p.P;
