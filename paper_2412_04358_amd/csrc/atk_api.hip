@@ -303,7 +303,9 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // 128 x 16384 bf16, b = 32, k_b = 2: 7.5 -> 6.5); longer rows with queues are better off split (128 x 65536,
     // b = 8, k_b = 8: four splits are the fastest)
     if (S > 1 && p.KB == 1 && n <= 65536 && !lean_shape) S = 1;
-    if (S > 1 && p.KB >= 2 && n <= 16384) S = 1;
+    // (eight slots and more on fewer rows than half the CUs are bound by their insertions and want the lanes:
+    // 8 x 16384 f32, b = 8, k_b = 8: 15.2 us in one workgroup, 11.3 in eight)
+    if (S > 1 && p.KB >= 2 && n <= 16384 && (p.KB < 8 || n <= 4096 || 2 * m >= (int64_t)kNumCU)) S = 1;
     // Queues in front of Stage 2 on short rows: four splits per row give the last workgroup four lists per column to
     // fetch and merge before it can select; two measured faster once the rows alone fill half the chip (128 x 65536
     // f32: k = 512, b = 1024, k_b = 2: 24.0 -> 18.6 us; b = 512, k_b = 4: 25.1 -> 21.9; k = 64, b = 64, k_b = 8: 32.6 -> 29.3)
@@ -403,6 +405,10 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         if (s_tail < s_stream) s_tail = s_stream;
         if (s_tail < 1) s_tail = 1;
         if (S > s_tail) S = s_tail;
+        // (a launch just over one workgroup per CU runs as two rounds: 32 x 2^18, k = 1024, b = 256, k_b = 4: 22.6 us
+        // with 12 or 16 splits, 18.2 with 8)
+        const int64_t per = m * p.colblocks;
+        if (per * S > (int64_t)kNumCU && per * S < 2 * (int64_t)kNumCU && per <= (int64_t)kNumCU) S = (int64_t)kNumCU / per;
     }
     if (multi_ok && ov.mh > 0) S = ov.mh + 1;  // (sweeps and tests; clamped like any other count below)
     if (S_forced) S = S_forced;
