@@ -220,6 +220,32 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     int p_want = 1;
     if (p.KB >= 8 && p.G >= T && !T_forced)
         while (p_want < 4 && m * p.G * p_want < 64 * 4 * (int64_t)kNumCU && p.L >= 4 * p_want * 2) p_want <<= 1;
+    // Queues without Stage 2 (b*k_b = k) on inputs that give the chip few lanes: more lanes of the workgroup share a column
+    // group (merged once, in LDS) rather than row splits that meet through scratch - up to four wavefronts per SIMD where
+    // every lane would own its column groups (two for k_b = 2, whose workgroups also share out the columns below), as
+    // long as a lane keeps 16 matrix rows.  Eight slots and more cost a lane many insertions to fill its queues: only
+    // on launches of under one wavefront per SIMD, down to 4*k_b rows per lane, also with fewer column groups than lanes
+    // (then up to two wavefronts per SIMD).  Measured on 128 x 65536 f32, k = 4096: b = 1024, k_b = 4: 28.1 us in two splits,
+    // 11.9 with four lanes a column group; b = 512, k_b = 8: 35.6 -> 19.4; b = 256, k_b = 16: 81.4 -> 44.4; k = 1024, b = 128,
+    // k_b = 8: 46.1 -> 22.9; one row of 2^20, k = 4096, b = 1024, k_b = 4: 35.8 -> 8.9; k = 16384 on 128 rows (one lane per
+    // column group fills the chip) stays as it is, and so do launches with more rows than that.
+    if (p.KB >= 2 && !p.stage2 && !T_forced && (p.G >= T || p.KB >= 8)) {
+        const int64_t min_rows = p.KB >= 8 ? 4 * p.KB : 16;
+        const int64_t full = 256 * (int64_t)kNumCU;  // lanes of one wavefront per SIMD
+        const int64_t target = p.KB <= 2 ? 2 * full : (p.G >= T ? 4 * full : 2 * full);
+        auto lanes = [&](int pw) { return m * ceil_div(p.G, std::min<int64_t>(p.G, std::max(1, T / pw))) * T; };
+        // A workgroup's piece of a matrix row gets shorter as lanes share column groups; pieces under 512 bytes (256 where
+        // the insertions, not memory, bound the launch) stream badly once the input is more than the caches smooth over
+        // (32 x 2^20 f32, k = 4096, b = 1024, k_b = 4: 53 us in row splits, 101 with sixteen lanes a column group and pieces of
+        // 128 bytes); inputs of up to 8 MB take pieces down to 128 bytes (one row of 2^20: 35.8 -> 8.9 us).
+        const int64_t piece_min = m * n * es <= (8 << 20) ? 128 : (p.KB >= 8 ? 256 : 512);
+        const int64_t pw_max = std::max<int64_t>(1, (int64_t)T * p.V * es / piece_min);
+        if (p.KB < 8 || lanes(1) < full) {
+            int pw = 1;
+            while (pw < 16 && 2 * pw <= pw_max && lanes(pw) < target && p.L / (2 * pw) >= min_rows) pw <<= 1;
+            if (pw > p_want) p_want = pw;
+        }
+    }
     // Eight unpacked slots on long rows: sixteen lanes of the workgroup on a column (pieces of 128 bytes of a matrix
     // row per wavefront), which is what the pooled floors below need; the layout alone is faster too (128 x 2^20 f32,
     // k = 64, b = 128: 183 us with four lanes a column, 166 with sixteen, 151 with pooled floors; b = 256: 201 -> 154)
@@ -269,13 +295,16 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
 
     // row splits for the layout just chosen
-    auto row_splits = [&]() -> int64_t {
+    auto row_splits = [&](bool strict_traffic = true) -> int64_t {
     int64_t base = m * p.colblocks;
     int64_t S = want_threads / (base * (lanes_per_wg ? lanes_per_wg : T));
     // every lane keeps at least 4 loads; a running maximum at least one full batch of 8 (one row of 2^20,
     // b = 64: 8.5 us with 128 splits of 4 loads per lane, 6.6 us with 64 of 8)
     int64_t s_rows = p.L / ((int64_t)p.P * (p.KB == 1 && !p.stage2 ? 8 : 4));  // (with Stage 2 more, shorter splits still measured faster)
     int64_t s_traffic = (p.L * es) / (32 * k_b);     // partial lists (written + read back) below half the bytes streamed
+    // (a quarter for queues without Stage 2, whose lists are the whole output S times over: 128 x 2^18 f32, k = 16384,
+    // b = 2048, k_b = 8: 145 us in two splits, 51 in one; 128 x 65536, k = 1024, b = 64, k_b = 16: 76.6 with 8, 42.1 with 4)
+    if (p.KB >= 2 && !p.stage2 && strict_traffic) s_traffic /= 2;
     int64_t s_fill = ceil_div(kNumCU, base);         // splits that give every CU a workgroup
     if (S > s_traffic) S = s_traffic > s_fill ? s_traffic : (S < s_fill ? S : s_fill);  // filling the chip comes first
     if (S > s_rows) S = s_rows;
@@ -361,7 +390,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if ((p.KB <= 2 || (p.KB == 4 && n * es <= (256 << 10))) && !p.stage2 && p.P > 1 && !P_forced && !S_forced &&
         (n * es) % 128 == 0) {
         int gw = p.Gw;
-        int64_t s = S, cb = p.colblocks;
+        // (how far the columns are shared out goes by the splits that the looser bound on the lists' traffic allows)
+        int64_t s = std::max(S, row_splits(false)), cb = p.colblocks;
         // ... and as long as the launch has fewer workgroups than the chip has CUs (rows that allow no
         // more splits: 64 x 128256 bf16, b = 256 came out with 128 workgroups)
         while ((s >= 2 || m * cb * s < (int64_t)kNumCU) && (gw & 1) == 0 && (int64_t)(gw / 2) * p.V * es >= 128 &&
