@@ -352,6 +352,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         // with a thousand matrix rows to itself costs more than the longer tail (one row of 2^20, b = 256, k_b = 16:
         // 411 us with 4 splits, 144 with 32; 16 rows of 2^18: 138 -> 102 with 8), so split down to about 128 matrix
         // rows per lane while that stays below one workgroup per CU
+        // ... on rows of up to 2^18 elements no more splits than give the launch two wavefronts per SIMD: beyond that the
+        // lists - S per column, k_b entries each, all through one workgroup at the end - cost more than the lanes bring
+        // (128 x 65536 f32, k = 256, b = 32, k_b = 16: 67.3 us with 8 splits, 42 with 4; 512 x 32768, b = 16: 69.7 with 2, 50 with 1)
+        if (p.KB >= 8 && n <= (1 << 18)) {
+            const int64_t s_lanes = std::max<int64_t>(1, 512 * (int64_t)kNumCU / (base * T));
+            if (S > s_lanes) S = s_lanes;
+        }
         if (p.KB >= 8) {
             int64_t s_long = p.L / ((int64_t)p.P * 128);
             if (s_long > 32) s_long = 32;
