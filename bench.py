@@ -53,6 +53,10 @@ def main():
                          "prints when the first, the median and the last wavefront passed every phase boundary")
     ap.add_argument("--probe-floors", action="store_true",
                     help="cfg4 with eight-slot queues (k=64, b=8 and b=128), 10 calls each without and with pooled floors (for rocprofv3)")
+    ap.add_argument("--probe-small", action="store_true",
+                    help="small batches of long rows (k=64, k_b=1; 1 x 2^20, 8 x 2^20, 32 x 2^17 at b=64 and b=256; 64 x 2^18 at "
+                         "b=512): 10 calls each with row splits through scratch (plan override MH=0), then with the library's "
+                         "own plan - helpers and a finisher (for rocprofv3)")
     ap.add_argument("--probe-queues", action="store_true",
                     help="profiler run of the kernels with register queues: 5 plain copies, then 20 approx_topk calls each on "
                          "cfg3 (128 x 65536 f32, k=16384) at k_b = 1, 4, 8, 16 and on cfg5 (2048 x 8192 bf16, k=b=512); no timing")
@@ -136,6 +140,27 @@ def main():
                 plans["b=%d %s" % (b, spec or "default")] = atk.plan_describe(M, n_long, K, b, 8)
                 for i in range(10):
                     rc = lib.approx_topk(xl.data_ptr(), M, n_long, K, b, 8, atk.ATK_F32, ov.data_ptr(), oi.data_ptr(), st)
+                    if rc != 0:
+                        raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
+                torch.cuda.synchronize()
+        atk.set_plan_override("")
+        print(json.dumps({"probe": "done", "launches_each": 10, "plans": plans}))
+        return
+
+    if args.probe_small:
+        st = torch.cuda.current_stream().cuda_stream
+        cases = [(1, 1 << 20, 64), (1, 1 << 20, 256), (8, 1 << 20, 64), (8, 1 << 20, 256), (32, 1 << 17, 64), (32, 1 << 17, 256),
+                 (64, 1 << 18, 512)]
+        plans = {}
+        for spec in ("MH=0", ""):  # the override only decides how the splits of a row meet
+            atk.set_plan_override(spec)
+            for (m_s, n_s, b) in cases:
+                ring = [workloads.normal_rows(m_s, n_s, seed=s).to(dev) for s in range(4)]
+                ov = torch.empty((m_s, K), dtype=torch.float32, device=dev)
+                oi = torch.empty((m_s, K), dtype=torch.int32, device=dev)
+                plans["%d x %d b=%d %s" % (m_s, n_s, b, spec or "default")] = atk.plan_describe(m_s, n_s, K, b, 1)
+                for i in range(10):
+                    rc = lib.approx_topk(ring[i % 4].data_ptr(), m_s, n_s, K, b, 1, atk.ATK_F32, ov.data_ptr(), oi.data_ptr(), st)
                     if rc != 0:
                         raise RuntimeError("approx_topk failed: %s" % atk.strerror(rc))
                 torch.cuda.synchronize()
