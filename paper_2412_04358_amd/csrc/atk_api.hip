@@ -165,7 +165,11 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // (128 x 65536 bf16, b = k = 64: 8.4 -> 7.5 us)
     const bool pair_out_rule = p.KB == 1 && !p.stage2 && allow_pair && ov.hf >= 0 && !ov.lm_off && !ov.ln_off && ptr16 &&
                                p.V == 16 / es && n % b == 0 && (n * es) % 16 == 0 && 2 * m <= (int64_t)kNumCU &&
-                               n * es >= (128 << 10) && b * es <= 128 && !S_forced;
+                               n * es >= (128 << 10) && b * es <= 128 && !S_forced && !(dtype == ATK_BF16 && n <= 65536);
+    // (bf16 rows of up to 65536 elements are better off in one workgroup of 512 lanes, all streaming: 128 x 65536, b = k = 64:
+    // 6.9 us as a pair, 5.9 in one workgroup; 32 rows: 5.9 -> 5.4)
+    const bool out_one_rule = p.KB == 1 && !p.stage2 && dtype == ATK_BF16 && ptr16 && p.V == 16 / es && n % b == 0 &&
+                              (n * es) % 16 == 0 && n <= 65536 && b * es <= 128 && !S_forced && !ov.lm_off && !ov.ln_off;
     // rows short enough that a Stage 2 plan is better off in one workgroup per row than in two (below)
     const bool one_piece = n * (dtype == ATK_BF16 ? 4 : 1) <= 512 * 512;
     // Shapes on which two workgroups share a row as helper and finisher (atk_lean_kernel.h) instead of one workgroup, or
@@ -318,6 +322,7 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // halves, 76.9 as a pair; 2^19: 45.7 -> 41.1; bf16 2^18, b = 256: 19.3 -> 15.9.)
     if (S == 2 && p.stage2 && p.colblocks == 1 && ((base * T >= 256 * (int64_t)kNumCU && one_piece) || pair_rule)) S = 1;
     if (S == 2 && pair_out_rule && p.colblocks == 1) S = 1;
+    if (S > 1 && out_one_rule && p.colblocks == 1) S = 1;
     // Short rows (up to 65536 elements) of a batch that leaves CUs idle: row splits through scratch and a ticket cost
     // more than they bring; one workgroup per row on the lean kernel, or a pair, is faster at every batch size (f32
     // n = 65536, k = 64: m = 1, b = 1024: 8.9 -> 6.6 us; m = 32: 11.1 -> 9.0; m = 64, b = 256: 9.7 -> 8.0; n = 32768:
