@@ -233,7 +233,12 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // 11.9 with four lanes a column group; b = 512, k_b = 8: 35.6 -> 19.4; b = 256, k_b = 16: 81.4 -> 44.4; k = 1024, b = 128,
     // k_b = 8: 46.1 -> 22.9; one row of 2^20, k = 4096, b = 1024, k_b = 4: 35.8 -> 8.9; k = 16384 on 128 rows (one lane per
     // column group fills the chip) stays as it is, and so do launches with more rows than that.
-    if (p.KB >= 2 && !p.stage2 && !T_forced && (p.G >= T || p.KB >= 8)) {
+    // With Stage 2 behind them the same holds for eight slots and more from 2048 candidates on (128 x 65536 f32, k = 1024:
+    // b = 128, k_b = 16: 106 -> 68 us; b = 512, k_b = 8: 151 -> 98; 8 x 2^18 bf16, b = 128, k_b = 16: 111 -> 71); with fewer
+    // candidates the sweeps are mixed (8 x 2^18 f32, k = 256, b = 64, k_b = 16: 47 -> 66), and so they are in bf16 on rows past
+    // 2^18 elements or past 256 buckets (128 x 65536, k = 1024, b = 512, k_b = 8: 96 -> 131), which stay as they were.
+    const bool share_s2 = p.stage2 && p.KB >= 8 && b * k_b >= 2048 && (dtype == ATK_F32 || (n <= (1 << 18) && b <= 256));
+    if (p.KB >= 2 && !T_forced && (p.stage2 ? share_s2 : (p.G >= T || p.KB >= 8))) {
         const int64_t min_rows = p.KB >= 8 ? 4 * p.KB : 16;
         const int64_t full = 256 * (int64_t)kNumCU;  // lanes of one wavefront per SIMD
         const int64_t target = p.KB <= 2 ? 2 * full : (p.G >= T ? 4 * full : 2 * full);
