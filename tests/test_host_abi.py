@@ -176,6 +176,43 @@ def test_plan_shapes(lib):
         assert p["T"] % 64 == 0 and p["P"] * p["Gw"] <= p["T"] and p["lds"] <= 65536
 
 
+def test_helper_and_pair_plans_fit_what_the_kernels_index(lib):
+    """Plans that hand maxima over through mailboxes (a helper + finisher pair; several helpers per finisher): the grid,
+    the helpers' shares of the matrix rows, the finisher's share and the mailbox bytes must be what the kernels' index
+    arithmetic assumes - a pair knows no column blocks, helpers take whole numbers of row phases and leave the finisher at
+    least one row per phase, and the finisher fetches at most eight mailbox words per lane."""
+    n_multi = n_pair = 0
+    for dt, es in ((atk.ATK_F32, 4), (atk.ATK_BF16, 2)):
+        for n in (1 << 16, 1 << 17, 1 << 18, 1 << 19, 1 << 20, 1 << 22, 96 * 4096, 3 * (1 << 17)):
+            for m in (1, 2, 3, 4, 8, 16, 32, 64, 100, 128):
+                for b in (32, 64, 96, 128, 256, 512, 1024, 2048):
+                    if n % b:
+                        continue
+                    for k in (64, b):
+                        if k > b:
+                            continue
+                        d = atk.plan_describe(m, n, k, b, 1, dt)
+                        p = parse_plan(d)
+                        L = n // b
+                        if p["helpers"] == 0:
+                            if p["pair_rows"] > 0:
+                                n_pair += 1
+                                assert p["grid"] == 2 * m and p["colblocks"] == 1 and p["lean"] == 1 and p["S"] == 1, d
+                                assert 0 < p["pair_rows"] < L and p["pair_rows"] % p["P"] == 0 and L - p["pair_rows"] >= p["P"], d
+                                assert p["scratch_bytes"] >= m * b * 8, d
+                            continue
+                        n_multi += 1
+                        H, Lh = p["helpers"], p["pair_rows"]
+                        stride = p["Gw"] * p["V"]
+                        assert p["lean"] == 1 and p["S"] == 1 and p["V"] == 16 // es, d
+                        assert p["grid"] == m * p["colblocks"] * (H + 1), d
+                        assert Lh >= p["P"] and Lh % p["P"] == 0 and H * Lh < L and L - H * Lh >= p["P"], d
+                        assert p["scratch_bytes"] >= m * p["colblocks"] * H * stride * 8, d
+                        assert H * stride <= 8 * p["T"] and p["Gw"] * p["P"] <= p["T"], d
+                        assert p["stage2"] == 0 or p["colblocks"] == 1, d
+    assert n_multi > 500 and n_pair > 100, (n_multi, n_pair)
+
+
 def parse_contig_plan(s):
     assert s.startswith("contiguous ")
     return parse_plan(s[len("contiguous "):])
