@@ -204,6 +204,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     if (p.stage2) {
         int t_s2 = (int)(ceil_div(ceil_div(b * k_b, 2), kWave) * kWave);
         if (t_s2 > 512) t_s2 = 512;
+        // ... and a lane for every column group where one workgroup can still hold them all: narrow lanes (rows that are not
+        // whole vectors: one column per lane) otherwise end up in two column blocks that meet through scratch and a ticket
+        // (256 x 32000 bf16, k = 64, b = 501: 13.6 us in two column blocks of 256 lanes, 9.7 in one workgroup of 512)
+        const int t_cols_s2 = (int)(ceil_div(p.G, kWave) * kWave);
+        // (rows past 320 KB in batches that give every CU a workgroup of 256 stream faster in the two column blocks:
+        // 128 x 128256 f32: 19.6 us, 23.6 in one workgroup of 512 per row)
+        if (t_cols_s2 <= 512 && t_s2 < t_cols_s2 && (n * es <= (320 << 10) || 2 * m < (int64_t)kNumCU)) t_s2 = t_cols_s2;
         if (T < t_s2) T = t_s2;
     }
     // many column groups but few rows: smaller workgroups rather than row splits.  Not with Stage 2: there the
