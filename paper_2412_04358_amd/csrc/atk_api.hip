@@ -401,6 +401,36 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         S = row_splits();
         if (T <= t_before) break;  // (rows too short to give more lanes something to do)
     }
+    // With Stage 2 the workgroups of a row meet in one of them whichever way the row is shared out; column blocks leave
+    // that workgroup one candidate per column to fetch, row splits a list per split to merge first.  So few rows - up
+    // to an eighth of the CUs' worth of workgroups - that would be split by rows, or fill under half the chip, share
+    // out their columns instead (more lanes per column group, narrower workgroups) while that stays within one workgroup
+    // per CU, 8 matrix rows per lane and pieces of 256 bytes of a matrix row; rows that the helpers + finisher plans
+    // take (below) are left to them.  Measured (f32): 4 x 2^22, k = 64, b = 4096: 139 -> 25 us; one row of 2^20, b = 1024: 14.1 -> 11.6;
+    // 8 x 2^20: 16.0 -> 13.7; one row of 2^24, b = 128: 34.0 -> 22.7; 32 x 128256, k = 256, b = 2048: 16.3 -> 13.2; 8 x 151936,
+    // k = 256, b = 512, k_b = 2: 15.3 -> 10.2; 128 rows keep their plans (128 x 2^18, b = 2048: 27.7 us, 32 and more with column blocks).
+    // (Not for matrix rows that do not start on 128-byte lines - pieces would straddle lines, read once by each of two
+    // workgroups: 32 x 2^22, b = 500: 81 -> 119 us; a plan that needs no scratch as it is - one workgroup per row - only on
+    // rows of 2 MB and more: 64 x 65536 bf16, k = 256, b = 2048: 9.7 us in one workgroup, 12.8 in column blocks; pieces of 512
+    // bytes at least once the input is more than the caches smooth over.)
+    if (p.stage2 && p.KB <= 4 && !T_forced && !P_forced && !S_forced && m * p.colblocks * 8 <= (int64_t)kNumCU &&
+        (b * es) % 128 == 0 && (S >= 2 || (m * p.colblocks * 2 < (int64_t)kNumCU && n * es >= (2 << 20)))) {
+        const bool to_helpers = p.KB == 1 && lean_shape && allow_pair && ov.hf >= 0 && ov.mh >= 0 && !ov.lm_off && !ov.ln_off &&
+                                T <= 512 && p.colblocks == 1 && S >= 2 && (S - 1) * (int64_t)p.Gw * p.V <= (int64_t)kMultiSlots * T;
+        if (!to_helpers) {
+            int pw = std::max(1, T / std::max(1, p.Gw));  // lanes on a column group now
+            const int pw0 = pw;
+            auto blocks = [&](int q) { return ceil_div(p.G, std::min<int64_t>(p.G, std::max(1, T / q))); };
+            while (pw < 16 && m * blocks(2 * pw) <= (int64_t)kNumCU && p.L / (2 * pw) >= 8 &&
+                   (int64_t)(T / (2 * pw)) * p.V * es >= (m * n * es > (8 << 20) ? 512 : 256))
+                pw <<= 1;
+            if (pw > pw0 && blocks(pw) > p.colblocks) {
+                layout(pw);
+                if (lds > kLdsBudget) return ATK_ERR_UNSUPPORTED;
+                S = row_splits();
+            }
+        }
+    }
     // Without Stage 2 nothing ties the columns of a row together, and a workgroup that owns whole
     // buckets needs no hand-over at all: as long as rows would be split, and a workgroup's piece of
     // a matrix row stays 128 bytes or more, halve the workgroup's column groups instead (measured on
