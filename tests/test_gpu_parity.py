@@ -633,6 +633,40 @@ def test_helpers_and_finisher(dtype, plan_override):
     plan_override(None)
 
 
+PLAN_FAMILIES = [
+    # (dtype, m, n, k, b, k_b, what the plan must say, rows compared or None for all)
+    ("f32", 4, 1 << 20, 64, 4096, 1, " stage2=1 ", None),          # few rows with Stage 2: column blocks, not row splits
+    ("f32", 1, 1 << 22, 64, 128, 1, " stage2=1 ", None),
+    ("f32", 8, 151936, 256, 512, 2, " stage2=1 ", None),
+    ("bf16", 32, 128256, 256, 2048, 1, " stage2=1 ", None),
+    ("f32", 128, 65536, 4096, 1024, 4, " S=1 ", list(range(0, 128, 8))),   # queues without Stage 2: lanes share column groups
+    ("f32", 128, 65536, 4096, 256, 16, " stage2=0 ", list(range(0, 128, 8))),
+    ("f32", 1, 1 << 20, 4096, 256, 16, " stage2=0 ", None),
+    ("bf16", 128, 1 << 18, 4096, 2048, 2, " stage2=0 ", list(range(0, 128, 16))),
+    ("f32", 128, 65536, 1024, 128, 16, " stage2=1 ", list(range(0, 128, 8))),  # ... and in front of Stage 2 from 2048 candidates
+    ("bf16", 2048, 16384, 256, 64, 4, " S=1 ", list(range(0, 2048, 128))),   # many rows: bigger workgroups, no row splits
+    ("bf16", 256, 32000, 64, 501, 1, " colblocks=1 ", list(range(0, 256, 16))),  # narrow lanes: a lane per column group
+    ("f32", 32, 1 << 18, 1024, 256, 4, " stage2=0 ", None),          # splits capped by the last workgroup's merge
+    ("f32", 8, 16384, 64, 8, 8, " stage2=0 ", None),                 # long queues on few short rows keep their splits
+    ("f32", 128, 65536, 256, 32, 16, " stage2=1 ", list(range(0, 128, 8))),
+    ("bf16", 128, 32768, 64, 256, 1, " lean=1 ", None),             # short rows: the bins' range comes from the merged candidates
+    ("f32", 1024, 4096, 64, 128, 1, " lean=1 ", list(range(0, 1024, 32))),
+]
+
+
+@pytest.mark.parametrize("case", PLAN_FAMILIES, ids=["%s %dx%d k=%d b=%d k_b=%d" % c[:6] for c in PLAN_FAMILIES])
+def test_plan_families(case):
+    """One shape from every family of launch plans that the planner's rules tell apart (Section 2's two stages on very
+    different launch geometries): results must not depend on the plan."""
+    dtype, m, n, k, b, k_b, must, rows = case
+    dt = atk.ATK_F32 if dtype == "f32" else atk.ATK_BF16
+    plan = atk.plan_describe(m, n, k, b, k_b, dt)
+    assert must in plan + " ", plan
+    run_case(workloads.normal_rows(m, n, seed=1300 + b + k_b, dtype=dtype), k, b, k_b, rows=rows, tag="family")
+    if m * n <= 1 << 23:
+        run_case(workloads.few_levels(m, n, levels=3, seed=1310 + b, dtype=dtype), k, b, k_b, rows=rows, tag="family ties")
+
+
 def test_calls_on_two_streams_share_the_scratch_pools():
     """The scratch pools are per device; calls that alternate between two streams must not see each other's tickets,
     lists or mailboxes (a call on another stream than the one before it waits for that stream first)."""

@@ -168,7 +168,12 @@ def test_plan_shapes(lib):
     # the grid always covers every matrix row and column exactly once, LDS stays within 64 KB
     for (m, n, k, b, kb) in [(1, 4096, 64, 64, 1), (3, 12288, 96, 96, 1), (7, 1 << 20, 64, 8, 8),
                              (128, 1 << 20, 1 << 18, 1 << 15, 8), (5, 8192, 1, 1, 1), (4, 16384, 100, 128, 16),
-                             (1, 1 << 18, 64, 512, 1), (130, 4096, 64, 128, 1), (5, 1677, 371, 371, 2), (3, 3000, 700, 350, 2)]:
+                             (1, 1 << 18, 64, 512, 1), (130, 4096, 64, 128, 1), (5, 1677, 371, 371, 2), (3, 3000, 700, 350, 2),
+                             # few rows with Stage 2 (column blocks instead of row splits), queues on launches of few lanes
+                             # (lanes share column groups), many short rows, vocabulary-sized rows with odd bucket counts
+                             (4, 1 << 22, 64, 4096, 1), (8, 151936, 256, 512, 2), (1, 1 << 24, 64, 128, 1), (128, 65536, 4096, 1024, 4),
+                             (128, 65536, 1024, 128, 16), (1, 1 << 20, 4096, 256, 16), (2048, 16384, 256, 64, 4), (256, 32000, 64, 501, 1),
+                             (32, 1 << 18, 1024, 256, 4), (128, 1 << 18, 16384, 2048, 8), (512, 50000, 1024, 256, 4)]:
         p = parse_plan(atk.plan_describe(m, n, k, b, kb))
         assert p["grid"] == m * p["S"] * p["colblocks"]
         assert p["colblocks"] * p["Gw"] * p["V"] >= b
