@@ -372,7 +372,8 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
         // ... on rows of up to 2^18 elements no more splits than give the launch two wavefronts per SIMD: beyond that the
         // lists - S per column, k_b entries each, all through one workgroup at the end - cost more than the lanes bring
         // (128 x 65536 f32, k = 256, b = 32, k_b = 16: 67.3 us with 8 splits, 42 with 4; 512 x 32768, b = 16: 69.7 with 2, 50 with 1)
-        if (p.KB >= 8 && n <= (1 << 18)) {
+        // (inputs past 128 MB are bound by memory again and want the lanes: 512 x 2^18, b = 8, k_b = 8: 109 us in two splits, 137 in one)
+        if (p.KB >= 8 && n <= (1 << 18) && m * n * es <= (1ll << 27)) {
             const int64_t s_lanes = std::max<int64_t>(1, 512 * (int64_t)kNumCU / (base * T));
             if (S > s_lanes) S = s_lanes;
         }
@@ -393,7 +394,13 @@ static int make_plan_aligned(int64_t m, int64_t n, int64_t k, int64_t b, int64_t
     // k = 256, b = 64, k_b = 4: 35.0 -> 21 us; 2048 x 4096 f32, b = 32, k_b = 2: 11.6 -> 9.0; b = 8, k_b = 8: 27.2 -> 20)
     // (and so do 512 lanes instead of two workgroups of 256 with queues: 512 x 50000 f32, k = 1024, b = 256, k_b = 4:
     // 32.3 -> 23 us)
-    while (S >= 2 && (T < 256 || (T < 512 && S == 2 && p.KB >= 2)) && 2 * T <= t_max && !T_forced && !P_forced && !S_forced) {
+    // (what counts below 256 lanes is whether the lanes asked for are there, not whether the splits survived their caps)
+    // (queues of eight slots and more are bound by insertions, and their splits' caps say how many lanes they want)
+    // (... while a lane of the bigger workgroup still has sixteen matrix rows: 512 x 1024, k = 1024, b = 256, k_b = 4 has four a column)
+    while (((T < 256 && (p.KB >= 8 ? S >= 2
+                                   : (S >= 2 || (want_threads / (m * p.colblocks * (lanes_per_wg ? lanes_per_wg : T)) >= 2 &&
+                                                 p.L / (2 * (int64_t)p.P) >= 16)))) ||
+            (S >= 2 && T < 512 && S == 2 && p.KB >= 2)) && 2 * T <= t_max && !T_forced && !P_forced && !S_forced) {
         const int t_before = T;
         T *= 2;
         layout(p_want);
